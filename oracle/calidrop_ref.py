@@ -1,0 +1,248 @@
+"""CaliDrop reference ("oracle"): plain, slow, float64 numpy.  TEST INFRASTRUCTURE ONLY.
+
+This file is the yardstick the HIP path is compared against.  It shares no code with the HIP
+path and must never be imported by the product (only by tests/, the smoke check and the
+benchmark's CPU-baseline leg).  Every function follows the paper step by step, in the paper's
+order and notation; nothing is blocked, fused or reordered.
+
+What the paper fixes and what it leaves open
+--------------------------------------------
+* Eq. 1-2 (attention decomposition) and Alg. 1 / Alg. 2 are followed literally, with the logit
+  scale 1/sqrt(d_k) of Eq. 2 (Alg. 1/2 print d_k; Eq. 1 only holds with a single scale).
+* C_weight of Alg. 1 is kept as its logarithm ``c_lse`` (same information, no overflow).
+* The eviction strategy f of Alg. 1 step 3 is "SnapKV-style" (Sec. 4.1.3: observation window,
+  average pooling).  The paper does not spell out its internals; the reading implemented here
+  is: softmax of the window queries over all keys with a causal mask inside the window,
+  summed over the window and over the query heads of a KV group, 1-D average pooling (stride
+  1, zero padding, divisor k), top-(B - w) prefix positions, ties to the lower index, window
+  always kept.  PARITY UNPINNED for these internal choices: no value in the paper checks them;
+  closed forms and brute force pin the arithmetic of the chosen reading.
+* The gate rho is compared with the thresholds in float32 (the precision the kernels decide
+  in); everything else is float64.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F = np.float64
+
+
+# --------------------------------------------------------------------------------------------
+# Attention and its decomposition (Sec. 3.1.2, Eq. 1-2)
+# --------------------------------------------------------------------------------------------
+def logits(q, K, scale):
+    """z_t = scale * q . K_t for one query vector q [D] and keys K [n][D]."""
+    return scale * (np.asarray(K, F) @ np.asarray(q, F))
+
+
+def attention(q, K, V, scale):
+    """Att(q, K, V) = softmax(q K^T * scale) V for one query; also returns log sum exp.
+
+    Returns (out [D], lse).  For an empty key set: (zeros, -inf)."""
+    K = np.asarray(K, F)
+    V = np.asarray(V, F)
+    if K.shape[0] == 0:
+        return np.zeros(V.shape[1], F), -np.inf
+    z = logits(q, K, scale)
+    m = z.max()
+    e = np.exp(z - m)
+    denom = e.sum()
+    return (e @ V) / denom, m + np.log(denom)
+
+
+def merge_weights(lse_i, lse_j):
+    """alpha_i, alpha_j of Eq. 2 from the two subsets' log-denominators."""
+    if lse_j == -np.inf:
+        return 1.0, 0.0
+    if lse_i == -np.inf:
+        return 0.0, 1.0
+    m = max(lse_i, lse_j)
+    wi, wj = np.exp(lse_i - m), np.exp(lse_j - m)
+    return wi / (wi + wj), wj / (wi + wj)
+
+
+def merge(out_i, lse_i, out_j, lse_j):
+    """Eq. 1: Att over S_i u S_j from the two partial attentions.  Returns (out, lse)."""
+    ai, aj = merge_weights(lse_i, lse_j)
+    out = ai * np.asarray(out_i, F) + aj * np.asarray(out_j, F)
+    return out, np.logaddexp(lse_i, lse_j)
+
+
+# --------------------------------------------------------------------------------------------
+# Eviction strategy f (Alg. 1 step 3), SnapKV-style (Sec. 4.1.3)
+# --------------------------------------------------------------------------------------------
+def window_votes(q_win_group, K_g, w, scale):
+    """Accumulated attention of the observation window onto the prefix, for one KV head.
+
+    q_win_group [G][w][D]: the window queries of the G query heads that share this KV head;
+    query i of the window sits at position P + i (P = n - w) and may attend positions
+    0..P+i.  Returns vote [P]: sum over heads and window rows of the softmax probability that
+    lands on each prefix column.  Window columns take part in the softmax but get no vote."""
+    q = np.asarray(q_win_group, F)
+    K = np.asarray(K_g, F)
+    n = K.shape[0]
+    P = n - w
+    vote = np.zeros(P, F)
+    for h in range(q.shape[0]):
+        for i in range(w):
+            z = logits(q[h, i], K[:P + i + 1], scale)       # causal: columns 0..P+i
+            e = np.exp(z - z.max())
+            p = e / e.sum()
+            vote += p[:P]
+    return vote
+
+
+def avg_pool(vote, k):
+    """1-D average pooling, stride 1, zero padding floor(k/2) each side, divisor always k."""
+    vote = np.asarray(vote, F)
+    P = vote.shape[0]
+    half = k // 2
+    score = np.zeros(P, F)
+    for d in range(-half, half + 1):            # same operation order at every position
+        shifted = np.zeros(P, F)                # shifted[j] = vote[j + d], 0 outside [0, P)
+        lo, hi = max(0, -d), min(P, P - d)
+        if hi > lo:
+            shifted[lo:hi] = vote[lo + d:hi + d]
+        score = score + shifted
+    return score / k
+
+
+def select_top(score, k_sel):
+    """Positions of the k_sel largest scores, ties to the lower index, returned ascending.
+
+    Also returns the relative boundary margin (s_(k_sel) - s_(k_sel+1)) / s_(k_sel) of the
+    sorted scores (inf when nothing is left out)."""
+    score = np.asarray(score, F)
+    order = np.argsort(-score, kind="stable")   # stable: equal scores keep index order
+    keep = np.sort(order[:k_sel])
+    if k_sel >= score.shape[0] or k_sel == 0:
+        return keep, np.inf
+    a, b = score[order[k_sel - 1]], score[order[k_sel]]
+    margin = (a - b) / a if a > 0 else 0.0
+    return keep, margin
+
+
+# --------------------------------------------------------------------------------------------
+# Alg. 1 (prefill side): compression + calibration state, one sequence
+# --------------------------------------------------------------------------------------------
+def calibration_state(q_cal, K, V, evicted, G, scale):
+    """Alg. 1 steps 5-8 for every query head: attention of the calibration query over the
+    evicted tokens of its KV head.  evicted: list over KV heads of position arrays."""
+    q_cal = np.asarray(q_cal, F)
+    Hq, D = q_cal.shape
+    c_out = np.zeros((Hq, D), F)
+    c_lse = np.full(Hq, -np.inf, F)
+    for h in range(Hq):
+        g = h // G
+        ev = evicted[g]
+        c_out[h], c_lse[h] = attention(q_cal[h], np.asarray(K[g], F)[ev],
+                                       np.asarray(V[g], F)[ev], scale)
+    return q_cal.copy(), c_out, c_lse
+
+
+def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=None):
+    """Alg. 1 steps 3-8 for one sequence.
+
+    q_win [Hq][w][D] last w prompt queries; K, V [Hkv][n][D]; B = KV budget (window included);
+    k = pooling kernel; q_cal [Hq][D] calibration query (default Q_{-1} = q_win[:, -1]).
+    retained_override: optional list over KV heads of ascending position arrays to use instead
+    of the selection (lets a test evaluate downstream values for a given retained set).
+
+    Returns dict: idx [Hkv][min(B,n)] ascending retained positions, K_c, V_c [Hkv][len][D],
+    c_q, c_out [Hq][D], c_lse [Hq], vote/score (lists per KV head, None if n <= B),
+    margin [Hkv]."""
+    q_win = np.asarray(q_win, F)
+    K = np.asarray(K, F)
+    V = np.asarray(V, F)
+    Hq, _, D = q_win.shape
+    Hkv, n, _ = K.shape
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    if q_cal is None:
+        q_cal = q_win[:, w - 1]
+    P = n - w
+    idx, votes, scores, margins, evicted = [], [], [], [], []
+    for g in range(Hkv):
+        if n <= B:                                   # nothing to evict (upper bound: FullKV)
+            keep_all = np.arange(n)
+            idx.append(keep_all)
+            votes.append(None)
+            scores.append(None)
+            margins.append(np.inf)
+            evicted.append(np.zeros(0, np.int64))
+            continue
+        vote = window_votes(q_win[g * G:(g + 1) * G], K[g], w, scale)
+        score = avg_pool(vote, k)
+        if retained_override is not None:
+            sel = np.asarray(retained_override[g])[:B - w]
+            margin = np.inf
+        else:
+            sel, margin = select_top(score, B - w)
+        idx_g = np.concatenate([sel, np.arange(P, n)])
+        mask = np.ones(P, bool)
+        mask[sel] = False
+        idx.append(idx_g)
+        votes.append(vote)
+        scores.append(score)
+        margins.append(margin)
+        evicted.append(np.nonzero(mask)[0])          # KV_evict = KV_full \ KV_compress
+    idx = np.stack(idx)
+    K_c = np.stack([K[g][idx[g]] for g in range(Hkv)])
+    V_c = np.stack([V[g][idx[g]] for g in range(Hkv)])
+    c_q, c_out, c_lse = calibration_state(q_cal, K, V, evicted, G, scale)
+    return dict(idx=idx, K_c=K_c, V_c=V_c, c_q=c_q, c_out=c_out, c_lse=c_lse,
+                vote=votes, score=scores, margin=np.asarray(margins), evicted=evicted)
+
+
+# --------------------------------------------------------------------------------------------
+# Alg. 2 (decode side), one sequence, one step
+# --------------------------------------------------------------------------------------------
+FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE = 0, 1, 2
+
+
+def cosine(a, b):
+    """rho = cos(a, b); 0 when either vector has zero norm."""
+    a = np.asarray(a, F)
+    b = np.asarray(b, F)
+    na, nb = np.sqrt(a @ a), np.sqrt(b @ b)
+    if na == 0.0 or nb == 0.0:
+        return 0.0
+    return (a @ b) / (na * nb)
+
+
+def decode(q_t, K_c, V_c, length, c_q, c_out, c_lse, theta1, theta2, scale=None):
+    """Alg. 2 for one sequence: attention over the compressed cache, cosine gate, Eq. 1 merge.
+
+    q_t [Hq][D]; K_c, V_c [Hkv][cap][D] of which the first `length` rows are live.
+    The recompute branch (rho < theta1) is only flagged: the output there is the uncalibrated
+    attention (recomputation needs the evicted K/V, which this entry point does not take).
+    Returns (out [Hq][D], a_lse [Hq], flags [Hq] uint8, rho [Hq])."""
+    q_t = np.asarray(q_t, F)
+    Hq, D = q_t.shape
+    Hkv = np.asarray(K_c).shape[0]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    out = np.zeros((Hq, D), F)
+    a_lse = np.zeros(Hq, F)
+    flags = np.zeros(Hq, np.uint8)
+    rhos = np.zeros(Hq, F)
+    t1, t2 = np.float32(theta1), np.float32(theta2)
+    for h in range(Hq):
+        g = h // G
+        o_a, lse_a = attention(q_t[h], np.asarray(K_c[g], F)[:length],
+                               np.asarray(V_c[g], F)[:length], scale)      # Alg. 2 step 1
+        rho = cosine(q_t[h], c_q[h])                                       # Alg. 2 step 2
+        rho32 = np.float32(rho)                                            # decision precision
+        rhos[h] = rho
+        a_lse[h] = lse_a
+        if rho32 < t1:                                                     # recompute branch
+            flags[h] = FLAG_RECOMPUTE
+            out[h] = o_a
+        elif rho32 > t2 and c_lse[h] > -np.inf:                            # calibrate (Eq. 1)
+            flags[h] = FLAG_CALIBRATED
+            out[h], _ = merge(o_a, lse_a, c_out[h], c_lse[h])
+        else:
+            out[h] = o_a
+    return out, a_lse, flags, rhos
