@@ -1,0 +1,178 @@
+/*
+ * calidrop.h - C ABI of the MI355X (gfx950) CaliDrop hot path.
+ *
+ * Two operations, both defined by the CaliDrop paper (arXiv 2507.19906):
+ *
+ *   calidrop_compress  - prefill side, Alg. 1 steps 3-8: apply a SnapKV-style eviction
+ *                        strategy f (Sec. 4.1.3: observation window, average pooling) per KV
+ *                        head, gather KV_compress, and precompute the calibration state
+ *                        (C_q, C_out, log C_weight) of the last prompt query over KV_evict.
+ *   calidrop_decode    - decode side, Alg. 2: attention of the current query over
+ *                        KV_compress, cosine gate against C_q, and the Eq. 1-2 merge with the
+ *                        calibration state.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller (for example a torch
+ *     tensor's data_ptr()); they must stay alive until `stream` has executed the enqueued
+ *     work.  `p` and the returned strings are HOST memory.  The library keeps no pointer
+ *     after a call returns and holds no state except a thread-local error string.
+ *   - Calls validate their arguments on the host first (no HIP call is made before
+ *     validation passes), then enqueue kernels on `stream` (a hipStream_t; NULL = default
+ *     stream) and return without synchronising.  They never allocate or free device memory.
+ *   - Return value: CALIDROP_OK (0) or a negative calidrop_status.  On error nothing was
+ *     enqueued, except for CALIDROP_EHIP (a launch failed; earlier kernels of the same call
+ *     may already be queued).  calidrop_last_error() describes the last failure on this
+ *     thread.
+ *   - Base pointers must be 16-byte aligned (CALIDROP_EALIGN otherwise).
+ *   - head_dim must be 64 or 128, n_q_heads / n_kv_heads an integer G with 1 <= G <= 16
+ *     (CALIDROP_EUNSUPPORTED otherwise).
+ *   - Accumulation is always fp32; `dtype` is the storage type of Q/K/V, the compressed cache
+ *     and the decode output.  The calibration state is always fp32.
+ *   - Logits are scaled by 1/sqrt(head_dim) (Eq. 2) unless `scale` is non-zero.
+ */
+#ifndef CALIDROP_H
+#define CALIDROP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CALIDROP_OK = 0,
+  CALIDROP_EINVAL = -1,       /* null pointer, bad struct_size, bad parameter value        */
+  CALIDROP_ESHAPE = -2,       /* sizes inconsistent with each other                        */
+  CALIDROP_EALIGN = -3,       /* a base pointer is not 16-byte aligned                     */
+  CALIDROP_EWORKSPACE = -4,   /* workspace missing or smaller than *_workspace_bytes()     */
+  CALIDROP_EUNSUPPORTED = -5, /* head_dim / group size / dtype outside the supported set   */
+  CALIDROP_EHIP = -6          /* a kernel launch reported an error                         */
+} calidrop_status;
+
+typedef enum { CALIDROP_BF16 = 0, CALIDROP_FP32 = 1 } calidrop_dtype;
+
+/* Flags written by calidrop_decode, one per (sequence, query head): the branch of Alg. 2. */
+enum {
+  CALIDROP_FLAG_NONE = 0,       /* theta1 <= rho <= theta2: plain compressed attention     */
+  CALIDROP_FLAG_CALIBRATED = 1, /* rho > theta2: output merged with C_out by Eq. 1         */
+  CALIDROP_FLAG_RECOMPUTE = 2   /* rho < theta1: caller should recompute the calibration
+                                   state; the output is the plain compressed attention     */
+};
+
+typedef struct {
+  uint32_t struct_size; /* = sizeof(calidrop_params); checked                               */
+  int32_t dtype;        /* calidrop_dtype                                                   */
+  int32_t batch;        /* sequences; a stack of layers is passed as batch = layers * seqs   */
+  int32_t n_q_heads;    /* Hq                                                               */
+  int32_t n_kv_heads;   /* Hkv; G = Hq / Hkv query heads share one KV head                  */
+  int32_t head_dim;     /* D                                                                */
+  int32_t window;       /* w >= 1: observation window = the last w prompt positions          */
+  int32_t budget;       /* B > w: retained tokens per KV head, window included               */
+  int32_t pool_kernel;  /* k odd >= 1: average-pooling width (1 = no pooling)                */
+  float scale;          /* logit scale; 0 selects 1/sqrt(D)                                  */
+  float theta1, theta2; /* Alg. 2 thresholds, theta1 <= theta2, compared strictly in fp32;
+                           (-inf, -inf) calibrates whenever a calibration state exists       */
+} calidrop_params;
+
+/* Bytes of device workspace calidrop_compress needs for these shapes (0 on invalid params).
+ * total_tokens = sum of prompt lengths, max_seq_len = longest prompt.                       */
+size_t calidrop_compress_workspace_bytes(const calidrop_params* p, int64_t total_tokens,
+                                         int32_t max_seq_len);
+
+/* Bytes of device workspace calidrop_decode needs (0 on invalid params).                     */
+size_t calidrop_decode_workspace_bytes(const calidrop_params* p, int32_t max_cache_len);
+
+/* Named regions inside the compress workspace, for inspection by tests and tools after the
+ * stream has finished.  Layouts:
+ *   ROW_LSE   float [batch][Hkv][NRB*128]: per window-query row, log2 of its softmax
+ *             denominator over all visible keys (logits in log2 units); rows of a KV head are
+ *             ordered (query head in group, window position); NRB = ceil(G*w / 128).
+ *   SCORE     float, packed like K with D = 1: pooled score of prefix position j of KV head g
+ *             of sequence b at [seq_offsets[b]*Hkv + g*n_b + j], j < n_b - w.
+ * Returns CALIDROP_OK and fills offset/bytes, or CALIDROP_EINVAL.                            */
+typedef enum { CALIDROP_REGION_ROW_LSE = 0, CALIDROP_REGION_SCORE = 1 } calidrop_region;
+int calidrop_compress_workspace_region(const calidrop_params* p, int64_t total_tokens,
+                                       int32_t max_seq_len, int32_t region, size_t* offset,
+                                       size_t* bytes);
+
+/*
+ * calidrop_compress - Alg. 1 steps 3-8 for `batch` independent sequences (one layer each).
+ *
+ * For every sequence b with prompt length n_b = seq_offsets[b+1] - seq_offsets[b] and every
+ * KV head g:
+ *   n_b <= B : every position is retained, nothing is evicted, c_lse = -inf, c_out = 0.
+ *   n_b >  B : (P = n_b - w)
+ *     1. S = scale * Q_win K^T for the G*w window-query rows of the group; window query i sits
+ *        at position P+i and sees columns 0..P+i; row softmax over the visible columns.
+ *     2. vote[j] = sum over those rows of the probability on prefix column j < P.
+ *     3. score = average pool of vote (stride 1, zero padding floor(k/2), divisor k).
+ *     4. retained = the B-w prefix positions of largest score (ties to the lower position),
+ *        in ascending order, followed by the window positions P..n_b-1.
+ *     5. K_c, V_c = the retained rows of K, V (KV_compress); every other prefix row is
+ *        KV_evict and stays where it is, in the caller's k / v.
+ *     6. for each query head h of the group, with q = q_cal[h] (default Q_{-1}, the last
+ *        window query): c_lse[h] = log sum_{t in evict} exp(scale q.K_t) (= log C_weight),
+ *        c_out[h] = Att(q, K_evict, V_evict), c_q[h] = q.
+ *
+ * Arguments
+ *   q_win         [batch][Hq][w][D] dtype: the last w prompt queries (as used by attention).
+ *   k, v          packed prompts, dtype: sequence b starts at token seq_offsets[b]; inside a
+ *                 sequence the layout is [Hkv][n_b][D].
+ *   seq_offsets   [batch+1] int32, ascending, seq_offsets[0] = 0.
+ *   total_tokens  = seq_offsets[batch]; max_seq_len >= every n_b (host copies; they size the
+ *                 launch grids - a sequence longer than max_seq_len is truncated in scoring).
+ *   q_cal         [batch][Hq][D] dtype calibration query, or NULL for Q_{-1}.
+ *   k_c, v_c      out, dtype: sequence b at token cache_offsets[b] of capacity
+ *                 cap_b = cache_offsets[b+1]-cache_offsets[b] >= min(B, n_b); inside:
+ *                 [Hkv][cap_b][D]; the first min(B, n_b) rows of each head are written.
+ *   cache_offsets [batch+1] int32.
+ *   cache_lens    out [batch] int32 = min(B, n_b).
+ *   indices       out [batch][Hkv][B] int32: retained prompt positions, ascending; -1 padded
+ *                 when n_b < B.
+ *   c_q, c_out    out [batch][Hq][D] fp32.   c_lse  out [batch][Hq] fp32.
+ *   workspace     >= calidrop_compress_workspace_bytes(p, total_tokens, max_seq_len) bytes,
+ *                 256-byte aligned; contents need no initialisation.
+ */
+int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k, const void* v,
+                      const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
+                      const void* q_cal, void* k_c, void* v_c, const int32_t* cache_offsets,
+                      int32_t* cache_lens, int32_t* indices, float* c_q, float* c_out,
+                      float* c_lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * calidrop_decode - Alg. 2 for one decode step of `batch` sequences.
+ *
+ * Per sequence b and query head h (KV head g = h / G):
+ *   1. z_r = scale * q_t[h].K_c[g][r] over the cache_lens[b] live rows; a_lse = logsumexp(z)
+ *      (= log A_weight); o_a = sum softmax(z)_r V_c[g][r]                (Alg. 2 step 1)
+ *   2. rho = cos(q_t[h], c_q[h]), taken as 0 when either norm is 0, in fp32   (step 2)
+ *   3. rho < theta1: flag RECOMPUTE, out = o_a.
+ *      rho > theta2 and c_lse[h] > -inf: alpha_j = 1/(1+exp(a_lse - c_lse[h])),
+ *          out = (1-alpha_j) o_a + alpha_j c_out[h]  (Eq. 1-2), flag CALIBRATED.
+ *      otherwise out = o_a, flag NONE.
+ *
+ * Arguments: q_t [batch][Hq][D] dtype; k_c, v_c, cache_offsets, cache_lens as produced by
+ * calidrop_compress (the caller may have appended rows and raised cache_lens);
+ * max_cache_len >= every cache_lens[b] (host copy; sizes the grid); c_q, c_out, c_lse the
+ * calibration state; out [batch][Hq][D] dtype; a_lse optional out [batch][Hq] fp32 (may be
+ * NULL); flags optional out [batch][Hq] uint8 (may be NULL); workspace >=
+ * calidrop_decode_workspace_bytes(p, max_cache_len) bytes, 256-byte aligned.
+ * A sequence with cache_lens[b] = 0 yields out = 0 and a_lse = -inf.
+ */
+int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, const void* v_c,
+                    const int32_t* cache_offsets, const int32_t* cache_lens,
+                    int32_t max_cache_len, const float* c_q, const float* c_out,
+                    const float* c_lse, void* out, float* a_lse, uint8_t* flags,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Host string describing the last error on the calling thread ("" if none). Never NULL.      */
+const char* calidrop_last_error(void);
+
+/* Library version as major*10000 + minor*100 + patch.                                        */
+int calidrop_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CALIDROP_H */

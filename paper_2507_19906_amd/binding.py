@@ -1,0 +1,212 @@
+"""ctypes binding of libcalidrop.so: the same entry points as include/calidrop.h, taking torch
+tensors for the device pointers.  Argument marshalling only - every step of the method runs in
+the HIP kernels.  There is no CPU fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libcalidrop.so")
+
+OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6
+BF16, FP32 = 0, 1
+FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE = 0, 1, 2
+REGION_ROW_LSE, REGION_SCORE = 0, 1
+
+
+class CalidropError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"calidrop status {status}: {message}")
+        self.status = status
+
+
+class Params(ctypes.Structure):
+    """Mirror of calidrop_params."""
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("batch", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("window", ctypes.c_int32),
+        ("budget", ctypes.c_int32),
+        ("pool_kernel", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("theta1", ctypes.c_float),
+        ("theta2", ctypes.c_float),
+    ]
+
+
+def make_params(*, dtype, batch, n_q_heads, n_kv_heads, head_dim, window, budget, pool_kernel,
+                scale=0.0, theta1=0.7, theta2=0.85) -> Params:
+    if isinstance(dtype, torch.dtype):
+        dtype = BF16 if dtype == torch.bfloat16 else FP32
+    elif isinstance(dtype, str):
+        dtype = BF16 if dtype == "bf16" else FP32
+    return Params(ctypes.sizeof(Params), dtype, batch, n_q_heads, n_kv_heads, head_dim, window,
+                  budget, pool_kernel, scale, theta1, theta2)
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcalidrop.so (built in-tree by paper_2507_19906_amd.build); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2507_19906_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        pp = ctypes.POINTER(Params)
+        L.calidrop_last_error.restype = ctypes.c_char_p
+        L.calidrop_last_error.argtypes = []
+        L.calidrop_version.restype = ctypes.c_int
+        L.calidrop_version.argtypes = []
+        L.calidrop_compress_workspace_bytes.restype = sz
+        L.calidrop_compress_workspace_bytes.argtypes = [pp, i64, i32]
+        L.calidrop_decode_workspace_bytes.restype = sz
+        L.calidrop_decode_workspace_bytes.argtypes = [pp, i32]
+        L.calidrop_compress_workspace_region.restype = ctypes.c_int
+        L.calidrop_compress_workspace_region.argtypes = [pp, i64, i32, i32, ctypes.POINTER(sz),
+                                                         ctypes.POINTER(sz)]
+        L.calidrop_compress.restype = ctypes.c_int
+        L.calidrop_compress.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp,
+                                        vp, vp, vp, sz, vp]
+        L.calidrop_decode.restype = ctypes.c_int
+        L.calidrop_decode.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz,
+                                      vp]
+        _lib = L
+    return _lib
+
+
+def calidrop_last_error() -> str:
+    return lib().calidrop_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise CalidropError(status, calidrop_last_error())
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def calidrop_compress_workspace_bytes(p: Params, total_tokens: int, max_seq_len: int) -> int:
+    n = lib().calidrop_compress_workspace_bytes(ctypes.byref(p), total_tokens, max_seq_len)
+    if n == 0:
+        raise CalidropError(EINVAL, calidrop_last_error())
+    return n
+
+
+def calidrop_decode_workspace_bytes(p: Params, max_cache_len: int) -> int:
+    n = lib().calidrop_decode_workspace_bytes(ctypes.byref(p), max_cache_len)
+    if n == 0:
+        raise CalidropError(EINVAL, calidrop_last_error())
+    return n
+
+
+def calidrop_compress_workspace_region(p: Params, total_tokens: int, max_seq_len: int, region: int):
+    off, nbytes = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().calidrop_compress_workspace_region(ctypes.byref(p), total_tokens, max_seq_len,
+                                                    region, ctypes.byref(off), ctypes.byref(nbytes)))
+    return off.value, nbytes.value
+
+
+def calidrop_compress(p: Params, q_win, k, v, seq_offsets, total_tokens: int, max_seq_len: int,
+                      q_cal, k_c, v_c, cache_offsets, cache_lens, indices, c_q, c_out, c_lse,
+                      workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().calidrop_compress(
+        ctypes.byref(p), _ptr(q_win), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
+        _ptr(q_cal), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens), _ptr(indices),
+        _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def calidrop_decode(p: Params, q_t, k_c, v_c, cache_offsets, cache_lens, max_cache_len: int, c_q,
+                    c_out, c_lse, out, a_lse, flags, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().calidrop_decode(
+        ctypes.byref(p), _ptr(q_t), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens),
+        max_cache_len, _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(out), _ptr(a_lse), _ptr(flags),
+        _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+# ---- device-memory plumbing (allocation only) ----------------------------------------------
+class CompressBuffers:
+    """Output and workspace tensors for calidrop_compress / calidrop_decode, allocated with
+    torch on `device`.  cache capacity per sequence = budget + extra_capacity."""
+
+    def __init__(self, p: Params, seq_lens, device, extra_capacity: int = 0):
+        dt = torch.bfloat16 if p.dtype == BF16 else torch.float32
+        self.p = p
+        B, Hq, Hkv, D, nb = p.budget, p.n_q_heads, p.n_kv_heads, p.head_dim, p.batch
+        assert len(seq_lens) == nb
+        self.total_tokens = int(sum(seq_lens))
+        self.max_seq_len = int(max(seq_lens))
+        cap = B + extra_capacity
+        self.cap = cap
+        self.cache_offsets = torch.arange(0, (nb + 1) * cap, cap, dtype=torch.int32, device=device)
+        self.k_c = torch.zeros(nb * Hkv * cap * D, dtype=dt, device=device)
+        self.v_c = torch.zeros(nb * Hkv * cap * D, dtype=dt, device=device)
+        self.cache_lens = torch.zeros(nb, dtype=torch.int32, device=device)
+        self.indices = torch.zeros((nb, Hkv, B), dtype=torch.int32, device=device)
+        self.c_q = torch.zeros((nb, Hq, D), dtype=torch.float32, device=device)
+        self.c_out = torch.zeros((nb, Hq, D), dtype=torch.float32, device=device)
+        self.c_lse = torch.zeros((nb, Hq), dtype=torch.float32, device=device)
+        self.ws_compress = torch.empty(
+            calidrop_compress_workspace_bytes(p, self.total_tokens, self.max_seq_len),
+            dtype=torch.uint8, device=device)
+        self.max_cache_len = cap
+        self.ws_decode = torch.empty(calidrop_decode_workspace_bytes(p, cap), dtype=torch.uint8,
+                                     device=device)
+        self.out = torch.zeros((nb, Hq, D), dtype=dt, device=device)
+        self.a_lse = torch.zeros((nb, Hq), dtype=torch.float32, device=device)
+        self.flags = torch.zeros((nb, Hq), dtype=torch.uint8, device=device)
+
+    def compress(self, q_win, k, v, seq_offsets, q_cal=None, stream=None):
+        calidrop_compress(self.p, q_win, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
+                          q_cal, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
+                          self.indices, self.c_q, self.c_out, self.c_lse, self.ws_compress, stream)
+
+    def decode(self, q_t, stream=None, max_cache_len=None):
+        calidrop_decode(self.p, q_t, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
+                        max_cache_len or self.max_cache_len, self.c_q, self.c_out, self.c_lse,
+                        self.out, self.a_lse, self.flags, self.ws_decode, stream)
+
+    def region(self, region: int) -> torch.Tensor:
+        off, nbytes = calidrop_compress_workspace_region(self.p, self.total_tokens,
+                                                         self.max_seq_len, region)
+        return self.ws_compress[off:off + nbytes].view(torch.float32)
+
+    def cache_view(self, which: str, b: int) -> torch.Tensor:
+        """[Hkv][cap][D] view of sequence b inside k_c / v_c."""
+        t = self.k_c if which == "k" else self.v_c
+        Hkv, D = self.p.n_kv_heads, self.p.head_dim
+        sz = Hkv * self.cap * D
+        return t[b * sz:(b + 1) * sz].view(Hkv, self.cap, D)
+
+
+def default_scale(head_dim: int) -> float:
+    return 1.0 / math.sqrt(head_dim)

@@ -1,0 +1,345 @@
+// C ABI of the CaliDrop hot path: argument validation, workspace carving and kernel launches.
+// Everything here runs on the host; validation never touches HIP, so it can be exercised on a
+// machine without a GPU.
+#include "../../include/calidrop.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "cd_attend.h"
+#include "cd_common.h"
+#include "cd_score.h"
+#include "cd_select.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+int check_params(const calidrop_params* p) {
+  if (!p) return fail(CALIDROP_EINVAL, "params is NULL");
+  if (p->struct_size != sizeof(calidrop_params))
+    return fail(CALIDROP_EINVAL, "params.struct_size is %u, this library expects %zu", p->struct_size,
+                sizeof(calidrop_params));
+  if (p->dtype != CALIDROP_BF16 && p->dtype != CALIDROP_FP32)
+    return fail(CALIDROP_EUNSUPPORTED, "dtype %d is not CALIDROP_BF16 or CALIDROP_FP32", p->dtype);
+  if (p->batch < 1) return fail(CALIDROP_EINVAL, "batch must be >= 1 (got %d)", p->batch);
+  if (p->n_q_heads < 1 || p->n_kv_heads < 1)
+    return fail(CALIDROP_EINVAL, "head counts must be >= 1 (got %d query, %d KV)", p->n_q_heads, p->n_kv_heads);
+  if (p->n_q_heads % p->n_kv_heads != 0)
+    return fail(CALIDROP_ESHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", p->n_q_heads, p->n_kv_heads);
+  if (p->n_q_heads / p->n_kv_heads > 16)
+    return fail(CALIDROP_EUNSUPPORTED, "GQA group size %d exceeds 16", p->n_q_heads / p->n_kv_heads);
+  if (p->head_dim != 64 && p->head_dim != 128)
+    return fail(CALIDROP_EUNSUPPORTED, "head_dim %d is not 64 or 128", p->head_dim);
+  if (p->window < 1) return fail(CALIDROP_EINVAL, "window must be >= 1 (got %d)", p->window);
+  if (p->budget <= p->window)
+    return fail(CALIDROP_EINVAL, "budget %d must exceed window %d (the window counts toward the budget)", p->budget,
+                p->window);
+  if (p->pool_kernel < 1 || p->pool_kernel % 2 == 0)
+    return fail(CALIDROP_EINVAL, "pool_kernel must be odd and >= 1 (got %d)", p->pool_kernel);
+  if (!(p->scale >= 0.f) || std::isinf(p->scale))
+    return fail(CALIDROP_EINVAL, "scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))");
+  if (std::isnan(p->theta1) || std::isnan(p->theta2) || p->theta1 > p->theta2)
+    return fail(CALIDROP_EINVAL, "thresholds must satisfy theta1 <= theta2 and not be NaN");
+  {  // launch grids put (sequence, KV head, row block) on one grid axis of at most 65535
+    const int64_t nrb = (static_cast<int64_t>(p->n_q_heads / p->n_kv_heads) * p->window + cd::kRowBlock - 1) / cd::kRowBlock;
+    if (static_cast<int64_t>(p->batch) * p->n_kv_heads * nrb > 65535 || p->n_q_heads > 65535)
+      return fail(CALIDROP_EUNSUPPORTED, "batch * n_kv_heads * ceil(G*window/128) exceeds 65535");
+  }
+  return CALIDROP_OK;
+}
+
+float logit_scale(const calidrop_params* p) {
+  return p->scale > 0.f ? p->scale : 1.0f / std::sqrt(static_cast<float>(p->head_dim));
+}
+
+// How the rows of a streaming-attention pass are split over workgroups.
+struct SplitPlan { int rows_per_split, NS; };
+SplitPlan plan_splits(int heads_kv_total, int max_rows) {
+  const int kTargetGroups = 2048;                      // ~8 workgroups per compute unit
+  const int kMinRows = cd::kTileRows * cd::kAttWaves;  // one tile per wave
+  if (max_rows < 1) max_rows = 1;
+  int want = ceil_div(kTargetGroups, heads_kv_total);
+  if (want < 1) want = 1;
+  int rps = ceil_div(ceil_div(max_rows, want), kMinRows) * kMinRows;
+  if (rps < kMinRows) rps = kMinRows;
+  return SplitPlan{rps, ceil_div(max_rows, rps)};
+}
+
+struct CompressLayout {
+  size_t rowpart, row_lse, vote, score, bitmap, part_o, part_ml, total;
+  int NRB, NCH, W32;
+  SplitPlan sp;
+};
+
+CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len) {
+  CompressLayout L{};
+  const int G = p->n_q_heads / p->n_kv_heads;
+  L.NRB = ceil_div(G * p->window, cd::kRowBlock);
+  L.NCH = ceil_div(max_seq_len, cd::kChunkKeys);
+  L.W32 = ceil_div(max_seq_len, 64) * 2;
+  L.sp = plan_splits(p->batch * p->n_kv_heads, max_seq_len);
+  const size_t rows = static_cast<size_t>(p->batch) * p->n_kv_heads * L.NRB * cd::kRowBlock;
+  const size_t toks = static_cast<size_t>(total_tokens) * p->n_kv_heads;
+  size_t off = 0;
+  L.rowpart = off; off += round256(rows * L.NCH * sizeof(float2));
+  L.row_lse = off; off += round256(rows * sizeof(float));
+  L.vote = off;    off += round256(toks * L.NRB * sizeof(float));
+  L.score = off;   off += round256(toks * sizeof(float));
+  L.bitmap = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.W32 * sizeof(uint32_t));
+  const size_t slots = static_cast<size_t>(p->batch) * p->n_q_heads * L.sp.NS;
+  L.part_o = off;  off += round256(slots * p->head_dim * sizeof(float));
+  L.part_ml = off; off += round256(slots * sizeof(float2));
+  L.total = off;
+  return L;
+}
+
+struct DecodeLayout { size_t part_o, part_ml, total; SplitPlan sp; };
+
+DecodeLayout decode_layout(const calidrop_params* p, int32_t max_cache_len) {
+  DecodeLayout L{};
+  L.sp = plan_splits(p->batch * p->n_kv_heads, max_cache_len);
+  const size_t slots = static_cast<size_t>(p->batch) * p->n_q_heads * L.sp.NS;
+  size_t off = 0;
+  L.part_o = off;  off += round256(slots * p->head_dim * sizeof(float));
+  L.part_ml = off; off += round256(slots * sizeof(float2));
+  L.total = off;
+  return L;
+}
+
+int check_sizes(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len) {
+  if (total_tokens < 1 || max_seq_len < 1 || max_seq_len > total_tokens)
+    return fail(CALIDROP_ESHAPE, "need 1 <= max_seq_len <= total_tokens (got %d, %lld)", max_seq_len,
+                static_cast<long long>(total_tokens));
+  if (total_tokens > (static_cast<int64_t>(1) << 31) - 1)
+    return fail(CALIDROP_EUNSUPPORTED, "total_tokens exceeds int32 offsets");
+  if (static_cast<int64_t>(p->batch) * max_seq_len < total_tokens)
+    return fail(CALIDROP_ESHAPE, "batch * max_seq_len < total_tokens");
+  return CALIDROP_OK;
+}
+
+int launch_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(CALIDROP_EHIP, "%s: %s", what, hipGetErrorString(e));
+  return CALIDROP_OK;
+}
+
+template <typename T, int D>
+int compress_impl(const calidrop_params* p, const void* q_win, const void* k, const void* v,
+                  const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, const void* q_cal,
+                  void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
+                  float* c_q, float* c_out, float* c_lse, char* ws, const CompressLayout& L, hipStream_t st) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  const float sl2 = logit_scale(p) * cd::kLog2e;
+  int rc;
+
+  cd::ScoreArgs sa{};
+  sa.q_win = q_win; sa.k = k; sa.seq_off = seq_offsets; sa.total_tokens = total_tokens;
+  sa.batch = p->batch; sa.Hq = p->n_q_heads; sa.Hkv = p->n_kv_heads; sa.G = G; sa.w = p->window;
+  sa.B = p->budget; sa.R = G * p->window; sa.NRB = L.NRB; sa.NCH = L.NCH; sa.max_seq_len = max_seq_len;
+  sa.pool_k = p->pool_kernel; sa.sl2 = sl2;
+  sa.rowpart = reinterpret_cast<float2*>(ws + L.rowpart);
+  sa.row_lse = reinterpret_cast<float*>(ws + L.row_lse);
+  sa.vote = reinterpret_cast<float*>(ws + L.vote);
+  sa.score = reinterpret_cast<float*>(ws + L.score);
+
+  const int bg = p->batch * p->n_kv_heads;
+  if (max_seq_len > p->budget) {       // otherwise no sequence can need eviction
+    dim3 grid_s(L.NCH, bg * L.NRB);
+    hipLaunchKernelGGL((cd::score_rowstats_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
+    if ((rc = launch_status("score_rowstats"))) return rc;
+    const int64_t rows = static_cast<int64_t>(bg) * L.NRB * cd::kRowBlock;
+    hipLaunchKernelGGL(cd::rowstats_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, sa);
+    if ((rc = launch_status("rowstats_merge"))) return rc;
+    hipLaunchKernelGGL((cd::score_votes_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
+    if ((rc = launch_status("score_votes"))) return rc;
+    hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
+    if ((rc = launch_status("pool_scores"))) return rc;
+  }
+
+  cd::SelectArgs se{};
+  se.seq_off = seq_offsets; se.total_tokens = total_tokens; se.batch = p->batch; se.Hkv = p->n_kv_heads;
+  se.w = p->window; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
+  se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
+  se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
+  hipLaunchKernelGGL(cd::select_topk_kernel, dim3(bg), dim3(cd::kSelThreads), 0, st, se);
+  if ((rc = launch_status("select_topk"))) return rc;
+
+  cd::GatherArgs ga{};
+  ga.k = k; ga.v = v; ga.k_c = k_c; ga.v_c = v_c; ga.seq_off = seq_offsets; ga.cache_off = cache_offsets;
+  ga.indices = indices; ga.total_tokens = total_tokens; ga.batch = p->batch; ga.Hkv = p->n_kv_heads;
+  ga.B = p->budget; ga.max_seq_len = max_seq_len; ga.row_bytes = D * static_cast<int>(sizeof(T));
+  const int vecs = p->budget * (ga.row_bytes / 16);
+  hipLaunchKernelGGL(cd::gather_kv_kernel, dim3(ceil_div(vecs, 256), bg), dim3(256), 0, st, ga);
+  if ((rc = launch_status("gather_kv"))) return rc;
+
+  cd::AttendArgs aa{};
+  aa.q = q_cal ? q_cal : q_win; aa.q_is_window = q_cal ? 0 : 1;
+  aa.k = k; aa.v = v; aa.row_off = seq_offsets; aa.row_len = nullptr; aa.bitmap = se.bitmap;
+  aa.total_tokens = total_tokens; aa.batch = p->batch; aa.Hq = p->n_q_heads; aa.Hkv = p->n_kv_heads; aa.G = G;
+  aa.w = p->window; aa.B = p->budget; aa.max_len = max_seq_len; aa.W32 = L.W32;
+  aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = sl2;
+  aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
+  aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+  if (max_seq_len > p->budget) {
+    hipLaunchKernelGGL((cd::attend_partial_kernel<T, D>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0, st, aa);
+    if ((rc = launch_status("attend_partial(calibration)"))) return rc;
+  }
+  cd::FinalArgs fa{};
+  fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = seq_offsets; fa.row_len = nullptr;
+  fa.total_tokens = total_tokens; fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G;
+  fa.w = p->window; fa.B = p->budget; fa.max_len = max_seq_len; fa.rows_per_split = L.sp.rows_per_split;
+  fa.NS = L.sp.NS; fa.calib_mode = 1; fa.q_is_window = aa.q_is_window; fa.q = aa.q;
+  fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse;
+  hipLaunchKernelGGL((cd::attend_finalize_kernel<T, D>), dim3(p->n_q_heads, p->batch), dim3(D), 0, st, fa);
+  return launch_status("attend_finalize(calibration)");
+}
+
+template <typename T, int D>
+int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, const void* v_c,
+                const int32_t* cache_offsets, const int32_t* cache_lens, int32_t max_cache_len, const float* c_q,
+                const float* c_out, const float* c_lse, void* out, float* a_lse, uint8_t* flags, char* ws,
+                const DecodeLayout& L, hipStream_t st) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  int rc;
+  cd::AttendArgs aa{};
+  aa.q = q_t; aa.q_is_window = 0; aa.k = k_c; aa.v = v_c; aa.row_off = cache_offsets; aa.row_len = cache_lens;
+  aa.bitmap = nullptr; aa.total_tokens = 0; aa.batch = p->batch; aa.Hq = p->n_q_heads; aa.Hkv = p->n_kv_heads;
+  aa.G = G; aa.w = p->window; aa.B = p->budget; aa.max_len = max_cache_len; aa.W32 = 0;
+  aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = logit_scale(p) * cd::kLog2e;
+  aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
+  aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+  hipLaunchKernelGGL((cd::attend_partial_kernel<T, D>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0, st, aa);
+  if ((rc = launch_status("attend_partial(decode)"))) return rc;
+  cd::FinalArgs fa{};
+  fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = cache_offsets; fa.row_len = cache_lens;
+  fa.total_tokens = 0; fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G;
+  fa.w = p->window; fa.B = p->budget; fa.max_len = max_cache_len; fa.rows_per_split = L.sp.rows_per_split;
+  fa.NS = L.sp.NS; fa.calib_mode = 0; fa.q_is_window = 0; fa.q = q_t; fa.theta1 = p->theta1; fa.theta2 = p->theta2;
+  fa.c_q = const_cast<float*>(c_q); fa.c_out = const_cast<float*>(c_out); fa.c_lse = const_cast<float*>(c_lse);
+  fa.out = out; fa.a_lse = a_lse; fa.flags = flags;
+  hipLaunchKernelGGL((cd::attend_finalize_kernel<T, D>), dim3(p->n_q_heads, p->batch), dim3(D), 0, st, fa);
+  return launch_status("attend_finalize(decode)");
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* calidrop_last_error(void) { return g_err; }
+int calidrop_version(void) { return 100; }
+
+size_t calidrop_compress_workspace_bytes(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len) {
+  if (check_params(p) != CALIDROP_OK || check_sizes(p, total_tokens, max_seq_len) != CALIDROP_OK) return 0;
+  return compress_layout(p, total_tokens, max_seq_len).total;
+}
+
+size_t calidrop_decode_workspace_bytes(const calidrop_params* p, int32_t max_cache_len) {
+  if (check_params(p) != CALIDROP_OK) return 0;
+  if (max_cache_len < 1) { fail(CALIDROP_ESHAPE, "max_cache_len must be >= 1"); return 0; }
+  return decode_layout(p, max_cache_len).total;
+}
+
+int calidrop_compress_workspace_region(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len,
+                                       int32_t region, size_t* offset, size_t* bytes) {
+  int rc;
+  if ((rc = check_params(p))) return rc;
+  if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
+  if (!offset || !bytes) return fail(CALIDROP_EINVAL, "offset/bytes is NULL");
+  const CompressLayout L = compress_layout(p, total_tokens, max_seq_len);
+  if (region == CALIDROP_REGION_ROW_LSE) {
+    *offset = L.row_lse;
+    *bytes = static_cast<size_t>(p->batch) * p->n_kv_heads * L.NRB * cd::kRowBlock * sizeof(float);
+  } else if (region == CALIDROP_REGION_SCORE) {
+    *offset = L.score;
+    *bytes = static_cast<size_t>(total_tokens) * p->n_kv_heads * sizeof(float);
+  } else {
+    return fail(CALIDROP_EINVAL, "unknown workspace region %d", region);
+  }
+  return CALIDROP_OK;
+}
+
+int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k, const void* v,
+                      const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, const void* q_cal,
+                      void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
+                      float* c_q, float* c_out, float* c_lse, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  int rc;
+  if ((rc = check_params(p))) return rc;
+  if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
+  const struct { const void* ptr; const char* name; } req[] = {
+      {q_win, "q_win"}, {k, "k"}, {v, "v"}, {seq_offsets, "seq_offsets"}, {k_c, "k_c"}, {v_c, "v_c"},
+      {cache_offsets, "cache_offsets"}, {cache_lens, "cache_lens"}, {indices, "indices"}, {c_q, "c_q"},
+      {c_out, "c_out"}, {c_lse, "c_lse"}};
+  for (const auto& r : req)
+    if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
+  for (const auto& r : req)
+    if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  if (q_cal && !aligned16(q_cal)) return fail(CALIDROP_EALIGN, "q_cal is not 16-byte aligned");
+  const CompressLayout L = compress_layout(p, total_tokens, max_seq_len);
+  if (!workspace || workspace_bytes < L.total)
+    return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
+                L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+#define CD_DISPATCH(T, D)                                                                                       \
+  return compress_impl<T, D>(p, q_win, k, v, seq_offsets, total_tokens, max_seq_len, q_cal, k_c, v_c,           \
+                             cache_offsets, cache_lens, indices, c_q, c_out, c_lse, ws, L, st)
+  if (p->dtype == CALIDROP_BF16) {
+    if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
+    CD_DISPATCH(cd::bf16_t, 64);
+  }
+  if (p->head_dim == 128) CD_DISPATCH(float, 128);
+  CD_DISPATCH(float, 64);
+#undef CD_DISPATCH
+}
+
+int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, const void* v_c,
+                    const int32_t* cache_offsets, const int32_t* cache_lens, int32_t max_cache_len,
+                    const float* c_q, const float* c_out, const float* c_lse, void* out, float* a_lse,
+                    uint8_t* flags, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_params(p))) return rc;
+  if (max_cache_len < 1) return fail(CALIDROP_ESHAPE, "max_cache_len must be >= 1 (got %d)", max_cache_len);
+  const struct { const void* ptr; const char* name; } req[] = {
+      {q_t, "q_t"}, {k_c, "k_c"}, {v_c, "v_c"}, {cache_offsets, "cache_offsets"}, {cache_lens, "cache_lens"},
+      {c_q, "c_q"}, {c_out, "c_out"}, {c_lse, "c_lse"}, {out, "out"}};
+  for (const auto& r : req)
+    if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
+  for (const auto& r : req)
+    if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  const DecodeLayout L = decode_layout(p, max_cache_len);
+  if (!workspace || workspace_bytes < L.total)
+    return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
+                L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+#define CD_DISPATCH(T, D)                                                                                      \
+  return decode_impl<T, D>(p, q_t, k_c, v_c, cache_offsets, cache_lens, max_cache_len, c_q, c_out, c_lse, out, \
+                           a_lse, flags, ws, L, st)
+  if (p->dtype == CALIDROP_BF16) {
+    if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
+    CD_DISPATCH(cd::bf16_t, 64);
+  }
+  if (p->head_dim == 128) CD_DISPATCH(float, 128);
+  CD_DISPATCH(float, 64);
+#undef CD_DISPATCH
+}
+
+}  // extern "C"

@@ -1,0 +1,300 @@
+// Streaming GQA attention of one query per head over a range of K/V rows, with the running
+// softmax kept as (max, sum, unnormalised output) so that partial results over disjoint row
+// sets merge by the attention-decomposition identity (Eq. 1-2).  Used twice:
+//   * calibration precompute (Alg. 1 steps 5-8): q = calibration query, rows = the prefix of
+//     the prompt with the retained positions masked out (i.e. KV_evict);
+//   * decode (Alg. 2 step 1): q = current query, rows = the compressed cache.
+// A workgroup owns one (sequence, KV head, split of the rows); its 4 waves take 32-row tiles
+// round-robin.  Per tile: S^T = K Q^T on the matrix cores (rows are the A rows, the G heads
+// are B columns 0..G-1, the other columns are zero padding), softmax weights stay in the
+// lanes that produced them and feed O^T += V^T P^T directly as the B operand.
+#pragma once
+#include "cd_common.h"
+#include "cd_score.h"
+
+namespace cd {
+
+constexpr int kTileRows = 32;
+constexpr int kAttWaves = 4;
+
+struct AttendArgs {
+  const void* q;              // [batch][Hq][D] or, when q_is_window, [batch][Hq][w][D] (last row used)
+  const void* k; const void* v;
+  const int32_t* row_off;     // [batch+1] token offsets of the K/V buffers
+  const int32_t* row_len;     // decode: live rows per sequence; NULL in calibration mode
+  const uint32_t* bitmap;     // calibration mode: [batch*Hkv][W32] not-evicted bits; else NULL
+  int64_t total_tokens;       // calibration mode: contract check of row_off
+  int batch, Hq, Hkv, G, w, B, max_len, W32, rows_per_split, NS;
+  int q_is_window;            // 1: q points at q_win and the last window row is the query
+  float sl2;                  // scale * log2(e)
+  float* part_o;              // [batch][Hq][NS][D]
+  float2* part_ml;            // [batch][Hq][NS]  (max in log2 units, sum)
+};
+
+// Number of rows the streaming pass covers for sequence b, the stride between heads and the
+// token offset, for both modes.  rows = 0 means nothing to do.
+__device__ __forceinline__ void attend_geometry(const AttendArgs& a, int b, int& rows, int& head_stride, int& off0) {
+  if (a.bitmap) {                                   // calibration: prefix rows of the prompt
+    int n = seq_len_checked(a.row_off, b, a.max_len, a.total_tokens, off0);
+    head_stride = n;
+    rows = (n > a.B) ? n - a.w : 0;
+  } else {                                          // decode: live rows of the cache
+    off0 = a.row_off[b];
+    head_stride = a.row_off[b + 1] - off0;
+    int len = a.row_len[b];
+    rows = (len < 0 || len > head_stride || len > a.max_len) ? 0 : len;
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
+  constexpr int EPL = Elem<T>::kPer16B;
+  constexpr int KD = Elem<T>::kStepK;
+  constexpr int NK = D / KD;
+  constexpr bool kBf16 = sizeof(T) == 2;
+  constexpr int NACC = kBf16 ? 8 : D / 16;          // output accumulators per lane (x4 floats)
+  const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  int rows, head_stride, off0;
+  attend_geometry(a, b, rows, head_stride, off0);
+  const int row_begin = split * a.rows_per_split;
+  if (row_begin >= rows) return;
+  const int row_end = min(rows, row_begin + a.rows_per_split);
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int i = lane & 15, c = lane >> 4;
+  const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * head_stride;
+  const T* kbase = static_cast<const T*>(a.k) + head_tok * D;
+  const T* vbase = static_cast<const T*>(a.v) + head_tok * D;
+  const uint32_t* bm = a.bitmap ? a.bitmap + static_cast<int64_t>(b * a.Hkv + g) * a.W32 : nullptr;
+
+  // query fragments: B operand, column i = head i of the group (zero beyond G)
+  u32x4 qf[NK];
+  {
+    const int h = g * a.G + i;
+    const T* qp = static_cast<const T*>(a.q);
+    if (a.q_is_window) qp += (static_cast<int64_t>(b * a.Hq + h) * a.w + (a.w - 1)) * D;
+    else qp += static_cast<int64_t>(b * a.Hq + h) * D;
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) qf[kk] = (i < a.G) ? ld16(qp + kk * KD + c * EPL) : zero16();
+  }
+
+  f32x4 acc_o[NACC];
+#pragma unroll
+  for (int x = 0; x < NACC; ++x) acc_o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, l = 0.f;     // per head (column i); l is this lane's share of the sum
+
+  for (int row0 = row_begin + wv * kTileRows; row0 < row_end; row0 += kAttWaves * kTileRows) {
+    // ---- logits: acc_s[g2][r] <-> row row0 + 16 g2 + 4 c + r, head i ----------------------
+    f32x4 acc_s[2];
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2) {
+      const int krow = min(row0 + 16 * g2 + i, rows - 1);
+      const T* kp = kbase + static_cast<int64_t>(krow) * D + c * EPL;
+      u32x4 kf[NK];
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) kf[kk] = ld16(kp + kk * KD);
+      acc_s[g2] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc_s[g2], kf[kk], qf[kk]);
+    }
+    const uint32_t notev = bm ? bm[row0 >> 5] : 0u;
+    float x[2][4];
+    float tm = -INFINITY;
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int rr = 16 * g2 + 4 * c + r;
+        const bool live = (row0 + rr < row_end) && !((notev >> rr) & 1u);
+        x[g2][r] = live ? acc_s[g2][r] * a.sl2 : -INFINITY;
+        tm = fmaxf(tm, x[g2][r]);
+      }
+    tm = col4_max(tm);
+    const float mn = fmaxf(m, tm);
+    const float ms = (mn == -INFINITY) ? 0.f : mn;
+    const float alpha = fast_exp2(m - ms);
+    m = mn;
+    float p[2][4];
+    float ps = 0.f;
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) { p[g2][r] = fast_exp2(x[g2][r] - ms); ps += p[g2][r]; }
+    l = l * alpha + ps;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int xx = 0; xx < NACC; ++xx) acc_o[xx] *= alpha;
+    }
+    // ---- O^T += V^T P^T -------------------------------------------------------------------
+    if constexpr (kBf16) {
+      // lane (i, c) loads, for e = 4 g2 + r, the 16-byte piece i of row row0 + 16 g2 + 4 c + r
+      u32x4 vf[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int vrow = min(row0 + 16 * (e >> 2) + 4 * c + (e & 3), rows - 1);
+        vf[e] = (i < D / 8) ? ld16(vbase + static_cast<int64_t>(vrow) * D + i * 8) : zero16();
+      }
+      u32x4 pf;
+      pf[0] = pack_bf16x2(p[0][0], p[0][1]);
+      pf[1] = pack_bf16x2(p[0][2], p[0][3]);
+      pf[2] = pack_bf16x2(p[1][0], p[1][1]);
+      pf[3] = pack_bf16x2(p[1][2], p[1][3]);
+#pragma unroll
+      for (int xx = 0; xx < 8; ++xx) {
+        // A fragment of instruction xx: element xx of each of the 8 loaded pieces (8 rows)
+        u32x4 af;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) {
+          const uint32_t lo = vf[2 * ww][xx >> 1], hi = vf[2 * ww + 1][xx >> 1];
+          af[ww] = (xx & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
+        }
+        mma_step<bf16_t>(acc_o[xx], af, pf);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int vrow = min(row0 + 16 * (e >> 2) + 4 * c + (e & 3), rows - 1);
+        const float pe = p[e >> 2][e & 3];
+#pragma unroll
+        for (int dh = 0; dh < D / 64; ++dh) {
+          u32x4 vf = ld16(vbase + static_cast<int64_t>(vrow) * D + (i + 16 * dh) * 4);
+#pragma unroll
+          for (int xx = 0; xx < 4; ++xx)
+            acc_o[dh * 4 + xx] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                __builtin_bit_cast(float, vf[xx]), pe, acc_o[dh * 4 + xx], 0, 0, 0);
+        }
+      }
+    }
+  }
+  l = col4_sum(l);
+
+  // ---- merge the 4 waves through LDS and write this split's partial ------------------------
+  __shared__ float s_o[kAttWaves][16][D];
+  __shared__ float2 s_ml[kAttWaves][16];
+  if (i < a.G) {
+    if (c == 0) s_ml[wv][i] = make_float2(m, l);
+#pragma unroll
+    for (int xx = 0; xx < NACC; ++xx)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int slot = 4 * c + r;      // output row of the tile = d slot
+        int d;
+        if constexpr (kBf16) d = 8 * slot + xx;
+        else d = 4 * (slot + 16 * (xx >> 2)) + (xx & 3);
+        if (d < D) s_o[wv][i][d] = acc_o[xx][r];
+      }
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < a.G * D; t += 256) {
+    const int hh = t / D, d = t - hh * D;
+    float mm = -INFINITY;
+#pragma unroll
+    for (int ww = 0; ww < kAttWaves; ++ww) mm = fmaxf(mm, s_ml[ww][hh].x);
+    const float ms = (mm == -INFINITY) ? 0.f : mm;
+    float o = 0.f, ll = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < kAttWaves; ++ww) {
+      const float sc = fast_exp2(s_ml[ww][hh].x - ms);
+      o += s_o[ww][hh][d] * sc;
+      ll += s_ml[ww][hh].y * sc;
+    }
+    const int64_t slot = (static_cast<int64_t>(b * a.Hq + g * a.G + hh)) * a.NS + split;
+    a.part_o[slot * D + d] = o;
+    if (d == 0) a.part_ml[slot] = make_float2(mm, ll);
+  }
+}
+
+struct FinalArgs {
+  const float* part_o; const float2* part_ml;
+  const int32_t* row_off; const int32_t* row_len;
+  int64_t total_tokens;
+  int batch, Hq, Hkv, G, w, B, max_len, rows_per_split, NS, calib_mode, q_is_window;
+  float theta1, theta2;
+  const void* q;                 // query tensor (see AttendArgs)
+  // calibration mode outputs / decode mode inputs
+  float* c_q; float* c_out; float* c_lse;
+  // decode outputs
+  void* out; float* a_lse; uint8_t* flags;
+};
+
+__device__ __forceinline__ float block_sum(float x, float* red, int nthreads) {
+  // sum over the workgroup (nthreads = 64 or 128), fixed order; result in every thread
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) x += __shfl_xor(x, s);
+  const int wv = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wv] = x;
+  __syncthreads();
+  float t = red[0];
+  for (int ww = 1; ww < nthreads / 64; ++ww) t += red[ww];
+  return t;
+}
+
+// One workgroup of D threads per (sequence, query head): merge the split partials (Eq. 1-2
+// applied NS-1 times), then either store the calibration state (Alg. 1 steps 6-8) or apply
+// the cosine gate and the calibration merge (Alg. 2 steps 2-15).
+template <typename T, int D>
+__global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const int g = h / a.G;
+  __shared__ float red[4];
+  int rows;
+  if (a.calib_mode) {
+    int off0;
+    int n = seq_len_checked(a.row_off, b, a.max_len, a.total_tokens, off0);
+    rows = (n > a.B) ? n - a.w : 0;
+  } else {
+    int cap = a.row_off[b + 1] - a.row_off[b];
+    int len = a.row_len[b];
+    rows = (len < 0 || len > cap || len > a.max_len) ? 0 : len;
+  }
+  (void)g;
+  const int ns = (rows + a.rows_per_split - 1) / a.rows_per_split;
+  const int64_t slot0 = static_cast<int64_t>(b * a.Hq + h) * a.NS;
+  float mm = -INFINITY;
+  for (int s = 0; s < ns; ++s) mm = fmaxf(mm, a.part_ml[slot0 + s].x);
+  const float ms = (mm == -INFINITY) ? 0.f : mm;
+  float o = 0.f, ll = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const float2 ml = a.part_ml[slot0 + s];
+    const float sc = fast_exp2(ml.x - ms);
+    o += a.part_o[(slot0 + s) * D + d] * sc;
+    ll += ml.y * sc;
+  }
+  const bool any = ll > 0.f;
+  const float o_n = any ? o / ll : 0.f;
+  const float lse = any ? (mm + fast_log2(ll)) * kLn2 : -INFINITY;     // natural-log units
+  const T* qp = static_cast<const T*>(a.q);
+  const int64_t hd = static_cast<int64_t>(b * a.Hq + h);
+  const float qd = a.q_is_window ? load_elem<T>(qp, (hd * a.w + (a.w - 1)) * D + d) : load_elem<T>(qp, hd * D + d);
+  if (a.calib_mode) {
+    a.c_q[hd * D + d] = qd;
+    a.c_out[hd * D + d] = o_n;
+    if (d == 0) a.c_lse[hd] = lse;
+    return;
+  }
+  // decode: rho = cos(q_t, c_q) in fp32
+  const float cq = a.c_q[hd * D + d];
+  const float dot = block_sum(qd * cq, red, D);
+  const float nq2 = block_sum(qd * qd, red, D);
+  const float nc2 = block_sum(cq * cq, red, D);
+  float rho = 0.f;
+  if (nq2 > 0.f && nc2 > 0.f) rho = dot / (sqrtf(nq2) * sqrtf(nc2));
+  const float c_lse = a.c_lse[hd];
+  uint8_t flag = 0;
+  float res = o_n;
+  if (rho < a.theta1) {
+    flag = 2;
+  } else if (rho > a.theta2 && c_lse > -INFINITY) {
+    flag = 1;
+    // alpha_j = sigmoid(c_lse - a_lse); a_lse = -inf (empty cache) gives alpha_j = 1
+    const float aj = 1.f / (1.f + __expf(lse - c_lse));
+    res = (1.f - aj) * o_n + aj * a.c_out[hd * D + d];
+  }
+  store_elem<T>(static_cast<T*>(a.out), hd * D + d, res);
+  if (d == 0) {
+    if (a.a_lse) a.a_lse[hd] = lse;
+    if (a.flags) a.flags[hd] = flag;
+  }
+}
+
+}  // namespace cd

@@ -1,0 +1,126 @@
+// Device-side building blocks shared by the CaliDrop kernels (gfx950 / CDNA4, wave64).
+//
+// Matrix-core convention used everywhere: one "mma step" multiplies a 16 x KD tile A by a
+// KD x 16 tile B into a 16x16 fp32 tile, where every lane contributes one 16-byte fragment of
+// A and one of B.  Lane l = 16*c + i holds, for A, row i and the c-th 16-byte piece of the
+// step's K range; for B, column i and the same piece.  The result tile is spread as
+// acc[r] = C[4*c + r][i].  For bf16 a step is one v_mfma_f32_16x16x32_bf16 (KD = 32); for
+// fp32 it is four v_mfma_f32_16x16x4_f32 (KD = 16, the x-th instruction takes element x of
+// each fragment).  Because A and B fragments use the same K placement, any contraction over
+// the step's K range comes out right.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cd {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+struct bf16_t { uint16_t bits; };   // storage type tag for bf16 tensors
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kWave = 64;
+
+template <typename T> struct Elem;
+template <> struct Elem<bf16_t> {
+  static constexpr int kPer16B = 8;    // elements in one 16-byte fragment
+  static constexpr int kStepK = 32;    // contraction depth of one mma step
+};
+template <> struct Elem<float> {
+  static constexpr int kPer16B = 4;
+  static constexpr int kStepK = 16;
+};
+
+__device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ void st16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
+__device__ __forceinline__ u32x4 zero16() { return u32x4{0u, 0u, 0u, 0u}; }
+
+template <typename T>
+__device__ __forceinline__ void mma_step(f32x4& acc, const u32x4& a, const u32x4& b);
+
+template <>
+__device__ __forceinline__ void mma_step<bf16_t>(f32x4& acc, const u32x4& a, const u32x4& b) {
+  acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ void mma_step<float>(f32x4& acc, const u32x4& a, const u32x4& b) {
+#pragma unroll
+  for (int x = 0; x < 4; ++x)
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__builtin_bit_cast(float, a[x]),
+                                               __builtin_bit_cast(float, b[x]), acc, 0, 0, 0);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// bf16 <-> fp32 (round to nearest even; inputs are finite)
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+  return __builtin_bit_cast(float, static_cast<uint32_t>(b) << 16);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_elem(const T* p, int64_t i);
+template <> __device__ __forceinline__ float load_elem<bf16_t>(const bf16_t* p, int64_t i) {
+  return bf16_to_f32(p[i].bits);
+}
+template <> __device__ __forceinline__ float load_elem<float>(const float* p, int64_t i) { return p[i]; }
+
+template <typename T> __device__ __forceinline__ void store_elem(T* p, int64_t i, float v);
+template <> __device__ __forceinline__ void store_elem<bf16_t>(bf16_t* p, int64_t i, float v) {
+  p[i].bits = f32_to_bf16(v);
+}
+template <> __device__ __forceinline__ void store_elem<float>(float* p, int64_t i, float v) { p[i] = v; }
+
+// Data-parallel-primitive lane exchange inside a row of 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+// Sum over the 16 lanes that share l/16; every lane ends with the same bits (fixed tree).
+__device__ __forceinline__ float row16_sum(float x) {
+  x += dpp_f32<0xB1>(x);    // quad_perm [1,0,3,2]
+  x += dpp_f32<0x4E>(x);    // quad_perm [2,3,0,1]
+  x += dpp_f32<0x141>(x);   // row_half_mirror
+  x += dpp_f32<0x140>(x);   // row_mirror
+  return x;
+}
+__device__ __forceinline__ float row16_max(float x) {
+  x = fmaxf(x, dpp_f32<0xB1>(x));
+  x = fmaxf(x, dpp_f32<0x4E>(x));
+  x = fmaxf(x, dpp_f32<0x141>(x));
+  x = fmaxf(x, dpp_f32<0x140>(x));
+  return x;
+}
+// Reductions over the four lanes {i, i+16, i+32, i+48} (same column, different c).
+__device__ __forceinline__ float col4_max(float x) {
+  x = fmaxf(x, __shfl_xor(x, 16));
+  x = fmaxf(x, __shfl_xor(x, 32));
+  return x;
+}
+__device__ __forceinline__ float col4_sum(float x) {
+  x += __shfl_xor(x, 16);
+  x += __shfl_xor(x, 32);
+  return x;
+}
+
+// Merge two (max, sum-of-exp2) pairs in the log2 domain; (-inf, 0) is the identity.
+__device__ __forceinline__ void merge_ml(float& m, float& l, float m2, float l2) {
+  float mn = fmaxf(m, m2);
+  if (mn == -INFINITY) { m = mn; l = 0.f; return; }
+  l = l * fast_exp2(m - mn) + l2 * fast_exp2(m2 - mn);
+  m = mn;
+}
+
+}  // namespace cd

@@ -1,0 +1,112 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_19906_amd import binding as cd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def good(**kw):
+    base = dict(dtype=cd.BF16, batch=2, n_q_heads=32, n_kv_heads=8, head_dim=128, window=32,
+                budget=512, pool_kernel=7)
+    base.update(kw)
+    return cd.make_params(**base)
+
+
+def test_header_symbols_are_exported():
+    hdr = open(os.path.join(ROOT, "include", "calidrop.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(calidrop_[a-z_]+)\s*\(", hdr))
+    assert {"calidrop_compress", "calidrop_decode", "calidrop_last_error",
+            "calidrop_compress_workspace_bytes", "calidrop_decode_workspace_bytes",
+            "calidrop_compress_workspace_region", "calidrop_version"} <= names
+    L = cd.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.calidrop_version() >= 100
+    assert ctypes.sizeof(cd.Params) == 48
+
+
+def test_workspace_sizes():
+    p = good()
+    n1 = cd.calidrop_compress_workspace_bytes(p, 2 * 8192, 8192)
+    n2 = cd.calidrop_compress_workspace_bytes(p, 2 * 32768, 32768)
+    assert 0 < n1 < n2 and n1 % 256 == 0
+    assert cd.calidrop_decode_workspace_bytes(p, 512) > 0
+    off, nbytes = cd.calidrop_compress_workspace_region(p, 2 * 8192, 8192, cd.REGION_SCORE)
+    assert nbytes == 2 * 8192 * 8 * 4 and off % 256 == 0 and off + nbytes <= n1
+    off, nbytes = cd.calidrop_compress_workspace_region(p, 2 * 8192, 8192, cd.REGION_ROW_LSE)
+    assert nbytes == 2 * 8 * 128 * 4
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(head_dim=96), cd.EUNSUPPORTED),
+    (dict(n_q_heads=30), cd.ESHAPE),
+    (dict(n_q_heads=34, n_kv_heads=2), cd.EUNSUPPORTED),     # G = 17
+    (dict(window=0), cd.EINVAL),
+    (dict(budget=32), cd.EINVAL),                            # budget must exceed window
+    (dict(pool_kernel=4), cd.EINVAL),
+    (dict(pool_kernel=0), cd.EINVAL),
+    (dict(theta1=0.9, theta2=0.5), cd.EINVAL),
+    (dict(theta1=float("nan")), cd.EINVAL),
+    (dict(scale=-1.0), cd.EINVAL),
+    (dict(batch=0), cd.EINVAL),
+    (dict(dtype=7), cd.EUNSUPPORTED),
+])
+def test_bad_params_rejected(kw, status):
+    p = good(**kw)
+    A = 4096     # fake, aligned, never dereferenced: validation fails first
+    rc = cd.lib().calidrop_compress(ctypes.byref(p), A, A, A, A, 2 * 8192, 8192, None, A, A, A, A,
+                                    A, A, A, A, A, 1 << 40, None)
+    assert rc == status, cd.calidrop_last_error()
+    assert cd.calidrop_last_error() != ""
+    rc = cd.lib().calidrop_decode(ctypes.byref(p), A, A, A, A, A, 512, A, A, A, A, None, None, A,
+                                  1 << 40, None)
+    assert rc == status
+
+
+def test_bad_struct_size_null_align_workspace():
+    A = 4096
+    L = cd.lib()
+    p = good()
+    p.struct_size = 40
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
+                               A, A, 1 << 40, None) == cd.EINVAL
+    p = good()
+    assert L.calidrop_compress(None, A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A, A, A,
+                               1 << 40, None) == cd.EINVAL
+    # null k
+    assert L.calidrop_compress(ctypes.byref(p), A, None, A, A, 16384, 8192, None, A, A, A, A, A, A,
+                               A, A, A, 1 << 40, None) == cd.EINVAL
+    assert "k is NULL" in cd.calidrop_last_error()
+    # misaligned v
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A + 8, A, 16384, 8192, None, A, A, A, A, A, A,
+                               A, A, A, 1 << 40, None) == cd.EALIGN
+    # workspace too small / missing / misaligned
+    need = cd.calidrop_compress_workspace_bytes(p, 16384, 8192)
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
+                               A, A, need - 1, None) == cd.EWORKSPACE
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
+                               A, None, 0, None) == cd.EWORKSPACE
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
+                               A, A + 16, need, None) == cd.EALIGN
+    # inconsistent sizes
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 100, 8192, None, A, A, A, A, A, A, A, A,
+                               A, 1 << 40, None) == cd.ESHAPE
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 3 * 8192, 8192, None, A, A, A, A, A, A,
+                               A, A, A, 1 << 40, None) == cd.ESHAPE      # batch*max < total
+    # decode
+    needd = cd.calidrop_decode_workspace_bytes(p, 512)
+    assert L.calidrop_decode(ctypes.byref(p), A, A, A, A, A, 512, A, A, A, A, None, None, A,
+                             needd - 1, None) == cd.EWORKSPACE
+    assert L.calidrop_decode(ctypes.byref(p), A, A, A, A, A, 0, A, A, A, A, None, None, A, needd,
+                             None) == cd.ESHAPE
+    assert L.calidrop_decode(ctypes.byref(p), A, A, A, A, A, 512, A, A, A, None, None, None, A,
+                             needd, None) == cd.EINVAL
+    with pytest.raises(cd.CalidropError):
+        cd.calidrop_compress_workspace_bytes(good(head_dim=100), 16384, 8192)

@@ -1,0 +1,192 @@
+"""HIP path vs fp64 oracle, through the C ABI, on seeded synthetic inputs.  Needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import calidrop_ref as ref
+from paper_2507_19906_amd import binding as cd
+from paper_2507_19906_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def to_dev(x):
+    return {k: v.to(DEV) for k, v in x.items()}
+
+
+def run_case(wl, seed=synth.BASE_SEED, decode_steps=None, heads=None, seqs=None):
+    x = to_dev(synth.make_inputs(wl, seed))
+    bufs = H.gpu_compress(wl, x)
+    rep = {}
+    seqs = range(wl.batch) if seqs is None else seqs
+    for b in seqs:
+        H.check_compress(wl, x, bufs, b, heads=heads, report=rep)
+    T = wl.decode_steps if decode_steps is None else decode_steps
+    for t in range(T):
+        bufs.decode(x["q_dec"][t])
+        torch.cuda.synchronize()
+        for b in seqs:
+            H.check_decode_step(wl, bufs, x["q_dec"][t], b, heads=heads, report=rep)
+    print(wl.name, {k: (v if k != "flags" else np.bincount(v, minlength=3).tolist())
+                    for k, v in rep.items()}, flush=True)
+    return rep
+
+
+def small(dtype, Hq, Hkv, D, lens, w, B, k, T=4, name="small"):
+    return synth.Workload(name, len(lens), Hq, Hkv, D, list(lens), w, B, k, dtype, T)
+
+
+def test_config1_fp32_compress_and_16_decode_steps():
+    rep = run_case(synth.config(1))
+    flags = np.bincount(rep["flags"], minlength=3)
+    assert flags[1] > 0 and flags[2] > 0          # calibrate and recompute branches both hit
+
+
+def test_config2_bf16_llama8b_8k():
+    rep = run_case(synth.config(2), decode_steps=8)
+    assert rep["c_out_err"] < 2e-2
+
+
+@pytest.mark.parametrize("wl", [
+    small("bf16", 8, 2, 64, [777], 16, 100, 5, name="ragged_bf16_d64"),
+    small("fp32", 8, 2, 128, [1031], 16, 96, 3, name="ragged_fp32_d128"),
+    small("bf16", 4, 4, 128, [600], 8, 40, 1, name="mha_g1_k1"),
+    small("bf16", 16, 2, 128, [900], 32, 128, 7, name="g8_two_row_blocks"),
+    small("fp32", 6, 2, 64, [300, 1000, 50, 257], 16, 64, 5, name="varlen_with_short_seq"),
+    small("bf16", 32, 8, 128, [513, 2049, 100, 640], 32, 512, 7, name="varlen_bf16_budget_edge"),
+    small("bf16", 4, 1, 128, [65], 1, 2, 1, name="window1_budget2"),
+], ids=lambda w: w.name)
+def test_shapes_and_ragged_tails(wl):
+    run_case(wl)
+
+
+def test_exact_ties_lower_index_wins():
+    # periodic keys: position j and j + period have identical keys, hence bit-identical votes
+    # on both sides; with k = 1 the scores tie exactly and the lower position must be kept
+    wl = small("bf16", 8, 2, 64, [16 * 40 + 16], 16, 16 + 50, 1, T=0, name="ties")
+    x = synth.make_inputs(wl, 99)
+    K = synth.seq_view(x["k"], wl, 0)
+    P = wl.seq_lens[0] - wl.window
+    period = 40
+    for j in range(period, P):
+        K[:, j] = K[:, j % period]
+    x = to_dev(x)
+    bufs = H.gpu_compress(wl, x)
+    orc = H.oracle_compress(wl, x, 0)
+    got = bufs.indices[0].cpu().numpy()
+    assert np.array_equal(got, orc["idx"])                      # no band: exact
+    sel = got[:, :50]
+    # the retained prefix positions contain whole tie classes from the lowest copy upwards
+    for g in range(2):
+        s = set(sel[g].tolist())
+        for j in s:
+            assert j < period or (j - period) in s
+
+
+def test_full_budget_keeps_everything_and_decode_is_exact_attention():
+    wl = small("bf16", 8, 2, 128, [200, 64], 16, 256, 5, T=2, name="budget_ge_n")
+    x = to_dev(synth.make_inputs(wl, 5))
+    bufs = H.gpu_compress(wl, x)
+    for b in range(2):
+        H.check_compress(wl, x, bufs, b)
+        n = wl.seq_lens[b]
+        idx = bufs.indices[b].cpu().numpy()
+        assert np.array_equal(idx[:, :n], np.tile(np.arange(n), (2, 1))) and np.all(idx[:, n:] == -1)
+    assert torch.all(torch.isinf(bufs.c_lse)) and torch.all(bufs.c_lse < 0)
+    bufs.decode(x["q_dec"][0])
+    torch.cuda.synchronize()
+    for b in range(2):
+        K = H.to64(synth.seq_view(x["k"], wl, b)); V = H.to64(synth.seq_view(x["v"], wl, b))
+        q = H.to64(x["q_dec"][0][b])
+        for h in range(8):
+            full, _ = ref.attention(q[h], K[h // 4], V[h // 4], 128 ** -0.5)
+            assert np.abs(H.to64(bufs.out[b, h]) - full).max() < 2e-2
+    assert not torch.any(bufs.flags == cd.FLAG_CALIBRATED)
+
+
+@pytest.mark.parametrize("dtype,tol", [("fp32", 1e-4), ("bf16", 2e-2)])
+def test_identical_query_calibration_reproduces_full_attention(dtype, tol):
+    # q_cal == q_t  =>  Eq. 1 makes the calibrated output the exact attention over all tokens
+    wl = small(dtype, 8, 2, 64, [1500], 16, 80, 5, T=1, name="identical_query")
+    x = to_dev(synth.make_inputs(wl, 11))
+    q_t = x["q_dec"][0]
+    bufs = H.gpu_compress(wl, x, q_cal=q_t)
+    bufs.decode(q_t)
+    torch.cuda.synchronize()
+    assert torch.all(bufs.flags == cd.FLAG_CALIBRATED)
+    K = H.to64(synth.seq_view(x["k"], wl, 0)); V = H.to64(synth.seq_view(x["v"], wl, 0))
+    q = H.to64(q_t[0])
+    for h in range(8):
+        full, lse = ref.attention(q[h], K[h // 4], V[h // 4], 64 ** -0.5)
+        assert np.abs(H.to64(bufs.out[0, h]) - full).max() < tol
+        both = np.logaddexp(bufs.a_lse[0, h].item(), bufs.c_lse[0, h].item())
+        assert abs(both - lse) < 2e-3
+
+
+def test_decode_with_appended_rows_and_empty_cache():
+    wl = small("bf16", 8, 2, 128, [700, 900], 16, 96, 5, T=6, name="append")
+    x = to_dev(synth.make_inputs(wl, 21))
+    bufs = H.gpu_compress(wl, x, extra_capacity=40)
+    g = torch.Generator(device=DEV).manual_seed(3)
+    rep = {}
+    for t in range(6):
+        # the caller appends one K/V row per step and raises cache_lens
+        for b in range(2):
+            L = int(bufs.cache_lens[b].item())
+            bufs.cache_view("k", b)[:, L] = torch.randn((2, 128), generator=g, device=DEV).bfloat16()
+            bufs.cache_view("v", b)[:, L] = torch.randn((2, 128), generator=g, device=DEV).bfloat16()
+        bufs.cache_lens += 1
+        bufs.decode(x["q_dec"][t])
+        torch.cuda.synchronize()
+        for b in range(2):
+            H.check_decode_step(wl, bufs, x["q_dec"][t], b, report=rep)
+    assert int(bufs.cache_lens[0].item()) == 102
+    # empty cache: out = c_out when calibrated (alpha_j = 1), a_lse = -inf
+    bufs.cache_lens.zero_()
+    p_always = H.params_for(wl, theta1=float("-inf"), theta2=float("-inf"))
+    cd.calidrop_decode(p_always, x["q_dec"][0], bufs.k_c, bufs.v_c, bufs.cache_offsets, bufs.cache_lens,
+                       bufs.max_cache_len, bufs.c_q, bufs.c_out, bufs.c_lse, bufs.out, bufs.a_lse,
+                       bufs.flags, bufs.ws_decode)
+    torch.cuda.synchronize()
+    assert torch.all(torch.isinf(bufs.a_lse)) and torch.all(bufs.flags == cd.FLAG_CALIBRATED)
+    assert (bufs.out.float() - bufs.c_out).abs().max().item() < 2e-2
+
+
+def test_gate_thresholds_exact_on_gpu():
+    # c_q = e1, q_t = (a, b, 0, ...): rho = a / sqrt(a^2 + b^2); 3-4-5 triangles are exact in fp32
+    wl = small("fp32", 2, 1, 64, [40], 4, 8, 1, T=0, name="gate")
+    x = to_dev(synth.make_inputs(wl, 1))
+    bufs = H.gpu_compress(wl, x)
+    bufs.c_q.zero_(); bufs.c_q[..., 0] = 1.0
+
+    def flags_for(a, b, t1, t2):
+        q = torch.zeros((1, 2, 64), device=DEV); q[..., 0] = a; q[..., 1] = b
+        p = H.params_for(wl, theta1=t1, theta2=t2)
+        cd.calidrop_decode(p, q, bufs.k_c, bufs.v_c, bufs.cache_offsets, bufs.cache_lens,
+                           bufs.max_cache_len, bufs.c_q, bufs.c_out, bufs.c_lse, bufs.out,
+                           bufs.a_lse, bufs.flags, bufs.ws_decode)
+        torch.cuda.synchronize()
+        return bufs.flags.cpu().numpy().ravel().tolist()
+
+    f06, f08 = float(np.float32(0.6)), float(np.float32(0.8))
+    assert flags_for(3, 4, 0.7, 0.85) == [2, 2]
+    assert flags_for(4, 3, 0.7, 0.85) == [0, 0]
+    assert flags_for(12, 5, 0.7, 0.85) == [1, 1]
+    assert flags_for(3, 4, f06, 0.85) == [0, 0]        # rho == theta1: strict
+    assert flags_for(4, 3, 0.7, f08) == [0, 0]         # rho == theta2: strict
+    assert flags_for(0, 0, 0.7, 0.85) == [2, 2]        # zero query: rho := 0
+
+
+def test_determinism_bitwise():
+    wl = synth.config(2)
+    wl.seq_lens = [4100]
+    x = to_dev(synth.make_inputs(wl, 4))
+    a = H.gpu_compress(wl, x)
+    b = H.gpu_compress(wl, x)
+    for name in ["indices", "k_c", "v_c", "c_out", "c_lse", "c_q", "cache_lens"]:
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    a.decode(x["q_dec"][0]); b.decode(x["q_dec"][0])
+    torch.cuda.synchronize()
+    assert torch.equal(a.out, b.out) and torch.equal(a.a_lse, b.a_lse)
