@@ -159,8 +159,8 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
           u32x4 vf = ld16(vbase + static_cast<int64_t>(vrow) * D + (i + 16 * dh) * 4);
 #pragma unroll
           for (int xx = 0; xx < 4; ++xx)
-            acc_o[dh * 4 + xx] = __builtin_amdgcn_mfma_f32_16x16x4f32(
-                __builtin_bit_cast(float, vf[xx]), pe, acc_o[dh * 4 + xx], 0, 0, 0);
+            acc_o[dh * 4 + xx] =
+                __builtin_amdgcn_mfma_f32_16x16x4f32(as_f32(vf[xx]), pe, acc_o[dh * 4 + xx], 0, 0, 0);
         }
       }
     }

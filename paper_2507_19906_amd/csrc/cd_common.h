@@ -38,6 +38,10 @@ __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<
 __device__ __forceinline__ void st16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
 __device__ __forceinline__ u32x4 zero16() { return u32x4{0u, 0u, 0u, 0u}; }
 
+// Reinterpret a 32-bit lane value (always pass vector elements through this by-value helper:
+// bit-casting a vector element expression directly reads element 0 with this compiler).
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+
 template <typename T>
 __device__ __forceinline__ void mma_step(f32x4& acc, const u32x4& a, const u32x4& b);
 
@@ -50,8 +54,7 @@ template <>
 __device__ __forceinline__ void mma_step<float>(f32x4& acc, const u32x4& a, const u32x4& b) {
 #pragma unroll
   for (int x = 0; x < 4; ++x)
-    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__builtin_bit_cast(float, a[x]),
-                                               __builtin_bit_cast(float, b[x]), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(as_f32(a[x]), as_f32(b[x]), acc, 0, 0, 0);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
