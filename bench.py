@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the CaliDrop hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input: calidrop_compress
+of a 32-layer Llama-3-8B-shaped stack at 32k context (budget 512, window 32, pooling 7; the
+layers are independent tensors passed as batch entries), followed by T = 256 calibrated decode
+steps (one calidrop_decode call per step over the whole stack).  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+  value                    decode attention GB/s: algorithmic bytes of one decode call divided by
+                           its mean duration (HIP events on the launch stream), with the decode
+                           calls cycling over `--rotate` copies of the compressed cache so that the
+                           working set exceeds the 256 MB Infinity Cache (HBM-honest).
+  compress_us_per_layer    mean calidrop_compress time / layers.
+  roofline                 the dominant kernel (the decode streaming-attention kernel).
+  cpu_baseline             the fp64 numpy oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def decode_bytes(wl, cache_len: int) -> int:
+    """Algorithmic bytes of one decode call: K_c and V_c rows once, plus query, calibration
+    state and output."""
+    E = 2 if wl.dtype == "bf16" else 4
+    kv = 2 * wl.batch * wl.n_kv_heads * cache_len * wl.head_dim * E
+    small = wl.batch * wl.n_q_heads * (wl.head_dim * E + (2 * wl.head_dim + 1) * 4 + wl.head_dim * E)
+    return kv + small
+
+
+def compress_bytes(wl) -> int:
+    """Lower bound for compress: K and V read once."""
+    E = 2 if wl.dtype == "bf16" else 4
+    return 2 * sum(wl.seq_lens) * wl.n_kv_heads * wl.head_dim * E
+
+
+def cpu_baseline(wl, x, kv_heads: int, decode_steps: int):
+    """Time the oracle (as it stands) on layer 0: `kv_heads` KV heads of compress and
+    `decode_steps` decode steps of the whole layer.  Scaled to the metric's units."""
+    import numpy as np
+    import torch
+    from oracle import calidrop_ref as ref
+    from paper_2507_19906_amd import synth
+    G = wl.group
+    to64 = lambda t: t.detach().to("cpu").to(torch.float64).numpy()
+    K = to64(synth.seq_view(x["k"], wl, 0))
+    V = to64(synth.seq_view(x["v"], wl, 0))
+    qw = to64(x["q_win"][0])
+    t0 = time.perf_counter()
+    r = ref.compress(qw[:kv_heads * G], K[:kv_heads], V[:kv_heads], wl.window, wl.budget, wl.pool_kernel)
+    t_comp = time.perf_counter() - t0
+    qd = to64(x["q_dec"][:decode_steps, 0, :kv_heads * G])
+    t0 = time.perf_counter()
+    for t in range(decode_steps):
+        ref.decode(qd[t], r["K_c"], r["V_c"], wl.budget, r["c_q"], r["c_out"], r["c_lse"], wl.theta1, wl.theta2)
+    t_dec = (time.perf_counter() - t0) / decode_steps
+    E = 2
+    dec_bytes = 2 * kv_heads * wl.budget * wl.head_dim * E      # same accounting as the GPU side
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {
+        "value": dec_bytes / t_dec / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"layer 0 of the stack, {kv_heads} of {wl.n_kv_heads} KV heads: one compress "
+                  f"({t_comp:.2f} s) and {decode_steps} decode steps ({t_dec * 1e3:.3f} ms each); "
+                  "fp64 numpy",
+        "compress_us_per_layer": t_comp * 1e6 * wl.n_kv_heads / kv_heads,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--budget", type=int, default=512)
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--rotate", type=int, default=0, help="cache copies cycled by decode (0 = enough for 512 MiB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path exists)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_19906_amd import binding as cd
+    from paper_2507_19906_amd import synth
+
+    if not os.path.exists(cd.LIB_PATH):
+        from paper_2507_19906_amd import build as _build
+        _build.build()
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU path)"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = synth.config(3, layers=args.layers, budget=args.budget, decode_steps=args.decode_steps)
+    x = synth.make_inputs(wl, device=dev)
+    p = cd.make_params(dtype=wl.dtype, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                       head_dim=wl.head_dim, window=wl.window, budget=wl.budget, pool_kernel=wl.pool_kernel,
+                       theta1=wl.theta1, theta2=wl.theta2)
+    bufs = cd.CompressBuffers(p, wl.seq_lens, dev)
+    dbytes = decode_bytes(wl, wl.budget)
+    rotate = args.rotate or max(1, -(-(512 << 20) // dbytes))
+    # extra copies of the compressed cache (same contents, different addresses)
+    k_copies = [bufs.k_c] + [torch.empty_like(bufs.k_c) for _ in range(rotate - 1)]
+    v_copies = [bufs.v_c] + [torch.empty_like(bufs.v_c) for _ in range(rotate - 1)]
+    T = wl.decode_steps
+    stream = torch.cuda.current_stream()
+
+    def decode_call(t, kc, vc):
+        cd.calidrop_decode(p, x["q_dec"][t], kc, vc, bufs.cache_offsets, bufs.cache_lens, bufs.max_cache_len,
+                           bufs.c_q, bufs.c_out, bufs.c_lse, bufs.out, bufs.a_lse, bufs.flags, bufs.ws_decode,
+                           stream)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    comp_ms, dec_ms = [], []
+
+    def one_step(record: bool):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record(stream)
+        bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=stream)
+        e1.record(stream)
+        for t in range(T):
+            decode_call(t, k_copies[t % rotate], v_copies[t % rotate])
+        e2.record(stream)
+        if record:
+            return (e0, e1, e2)
+
+    for _ in range(args.warmup):
+        one_step(False)
+        for i in range(1, rotate):                    # fill the copies once compress has run
+            k_copies[i].copy_(bufs.k_c); v_copies[i].copy_(bufs.v_c)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs = [one_step(True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for e0, e1, e2 in evs:
+        comp_ms.append(e0.elapsed_time(e1))
+        dec_ms.append(e1.elapsed_time(e2) / T)
+    comp = sum(comp_ms) / len(comp_ms)
+    dec = sum(dec_ms) / len(dec_ms)
+
+    # cache-resident variant (single copy: 64 MiB per call stays in the Infinity Cache)
+    e0, e1 = ev(), ev()
+    e0.record(stream)
+    for t in range(T):
+        decode_call(t, bufs.k_c, bufs.v_c)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    dec_res = e0.elapsed_time(e1) / T
+
+    gbps = dbytes / (dec * 1e-3) / 1e9
+    out = {
+        "metric": "decode attn GB/s (% HBM peak) + compress us/layer at 32k ctx, budget 512",
+        "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.batch, "context": wl.seq_lens[0], "budget": wl.budget,
+                   "window": wl.window, "pool_kernel": wl.pool_kernel, "q_heads": wl.n_q_heads,
+                   "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "decode_steps_per_step": T,
+                   "cache_copies_rotated": rotate},
+        "pct_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
+        "decode_us_per_call": dec * 1e3,
+        "decode_GBps_cache_resident": dbytes / (dec_res * 1e-3) / 1e9,
+        "compress_us_per_layer": comp * 1e3 / wl.batch,
+        "compress_GBps_vs_read_kv_once": compress_bytes(wl) / (comp * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "attend_partial_kernel<bf16,128> (decode)",
+                     "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                     "traffic": None,
+                     "note": "duration = mean of HIP-event time over all decode calls of the timed region / calls "
+                             "(includes the small finalize kernel and launch gaps)"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, x, kv_heads=wl.n_kv_heads, decode_steps=64)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
