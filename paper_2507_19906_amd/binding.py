@@ -11,7 +11,8 @@ from typing import Optional
 import torch
 
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG_DIR, "libcalidrop.so")
+# CALIDROP_LIB selects another build of the same library (e.g. a tuning variant)
+LIB_PATH = os.environ.get("CALIDROP_LIB") or os.path.join(_PKG_DIR, "libcalidrop.so")
 
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6
 BF16, FP32 = 0, 1

@@ -67,6 +67,12 @@ float logit_scale(const calidrop_params* p) {
   return p->scale > 0.f ? p->scale : 1.0f / std::sqrt(static_cast<float>(p->head_dim));
 }
 
+// Decode uses the single-workgroup-per-(sequence, KV head) kernel from this many pairs on.
+#ifndef CD_FUSED_MIN_PAIRS
+#define CD_FUSED_MIN_PAIRS 192
+#endif
+constexpr int kFusedMinPairs = CD_FUSED_MIN_PAIRS;
+
 // How the rows of a streaming-attention pass are split over workgroups.
 struct SplitPlan { int rows_per_split, NS; };
 SplitPlan plan_splits(int heads_kv_total, int max_rows) {
@@ -82,7 +88,7 @@ SplitPlan plan_splits(int heads_kv_total, int max_rows) {
 
 struct CompressLayout {
   size_t rowpart, row_lse, vote, score, bitmap, part_o, part_ml, total;
-  int NRB, NCH, W32;
+  int NRB, NCH, W32, chunk_keys;
   SplitPlan sp;
 };
 
@@ -90,7 +96,14 @@ CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, i
   CompressLayout L{};
   const int G = p->n_q_heads / p->n_kv_heads;
   L.NRB = ceil_div(G * p->window, cd::kRowBlock);
-  L.NCH = ceil_div(max_seq_len, cd::kChunkKeys);
+  {  // keys per scoring workgroup: as large as keeps >= ~2048 workgroups in the launch, 256..2048
+    const int64_t groups256 = static_cast<int64_t>(p->batch) * p->n_kv_heads * L.NRB * ceil_div(max_seq_len, cd::kMinChunkKeys);
+    int mult = static_cast<int>(groups256 / 2048);
+    if (mult < 1) mult = 1;
+    if (mult > 8) mult = 8;
+    L.chunk_keys = mult * cd::kMinChunkKeys;
+  }
+  L.NCH = ceil_div(max_seq_len, L.chunk_keys);
   L.W32 = ceil_div(max_seq_len, 64) * 2;
   L.sp = plan_splits(p->batch * p->n_kv_heads, max_seq_len);
   const size_t rows = static_cast<size_t>(p->batch) * p->n_kv_heads * L.NRB * cd::kRowBlock;
@@ -151,7 +164,7 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   sa.q_win = q_win; sa.k = k; sa.seq_off = seq_offsets; sa.total_tokens = total_tokens;
   sa.batch = p->batch; sa.Hq = p->n_q_heads; sa.Hkv = p->n_kv_heads; sa.G = G; sa.w = p->window;
   sa.B = p->budget; sa.R = G * p->window; sa.NRB = L.NRB; sa.NCH = L.NCH; sa.max_seq_len = max_seq_len;
-  sa.pool_k = p->pool_kernel; sa.sl2 = sl2;
+  sa.pool_k = p->pool_kernel; sa.sl2 = sl2; sa.chunk_keys = L.chunk_keys;
   sa.rowpart = reinterpret_cast<float2*>(ws + L.rowpart);
   sa.row_lse = reinterpret_cast<float*>(ws + L.row_lse);
   sa.vote = reinterpret_cast<float*>(ws + L.vote);
@@ -216,6 +229,23 @@ int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, cons
                 const DecodeLayout& L, hipStream_t st) {
   const int G = p->n_q_heads / p->n_kv_heads;
   int rc;
+  // Enough (sequence, KV head) pairs to fill the chip: one workgroup does a pair's whole step.
+  if (p->batch * p->n_kv_heads >= kFusedMinPairs) {
+    cd::DecodeFusedArgs fa{};
+    fa.q = q_t; fa.k = k_c; fa.v = v_c; fa.row_off = cache_offsets; fa.row_len = cache_lens;
+    fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G; fa.max_len = max_cache_len;
+    fa.sl2 = logit_scale(p) * cd::kLog2e; fa.theta1 = p->theta1; fa.theta2 = p->theta2;
+    fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse; fa.out = out; fa.a_lse = a_lse; fa.flags = flags;
+    const int tiles = ceil_div(max_cache_len, cd::kTileRows);
+    const size_t lds_per_wave = static_cast<size_t>(G) * (D + 2) * sizeof(float);
+    int nw = tiles <= 4 ? 4 : 8;
+    while (nw > 4 && nw * lds_per_wave > 64 * 1024) nw /= 2;
+    const dim3 grid(p->n_kv_heads, p->batch);
+    const size_t lds = nw * lds_per_wave;
+    if (nw == 8) hipLaunchKernelGGL((cd::decode_fused_kernel<T, D, 8>), grid, dim3(512), lds, st, fa);
+    else hipLaunchKernelGGL((cd::decode_fused_kernel<T, D, 4>), grid, dim3(256), lds, st, fa);
+    return launch_status("decode_fused");
+  }
   cd::AttendArgs aa{};
   aa.q = q_t; aa.q_is_window = 0; aa.k = k_c; aa.v = v_c; aa.row_off = cache_offsets; aa.row_len = cache_lens;
   aa.bitmap = nullptr; aa.total_tokens = 0; aa.batch = p->batch; aa.Hq = p->n_q_heads; aa.Hkv = p->n_kv_heads;

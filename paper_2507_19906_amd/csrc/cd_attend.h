@@ -46,13 +46,158 @@ __device__ __forceinline__ void attend_geometry(const AttendArgs& a, int b, int&
   }
 }
 
+// Per-wave state and tile loop of the streaming attention.  Lane l = 16 c + i.
+template <typename T, int D>
+struct AttendWave {
+  static constexpr int EPL = Elem<T>::kPer16B;
+  static constexpr int KD = Elem<T>::kStepK;
+  static constexpr int NK = D / KD;
+  static constexpr bool kBf16 = sizeof(T) == 2;
+  static constexpr int NACC = kBf16 ? 8 : D / 16;   // output accumulators per lane (x4 floats)
+
+  u32x4 qf[NK];          // B operand: column i = head i of the group (zero beyond G)
+  f32x4 acc_o[NACC];     // O^T tile: acc_o[x][r] <-> d slot 4c+r, head i
+  float m, l;            // running max (log2 units, shared by the 4 lanes of a head) and this lane's sum share
+
+  __device__ __forceinline__ void init(const T* q_row, bool valid, int c) {
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) qf[kk] = valid ? ld16(q_row + kk * KD + c * EPL) : zero16();
+#pragma unroll
+    for (int x = 0; x < NACC; ++x) acc_o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m = -INFINITY;
+    l = 0.f;
+  }
+
+  __device__ __forceinline__ void load_k(const T* kbase, int row0, int rows, int i, int c, u32x4 (&kf)[2][NK]) const {
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2) {
+      const int krow = min(row0 + 16 * g2 + i, rows - 1);
+      const T* kp = kbase + static_cast<int64_t>(krow) * D + c * EPL;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) kf[g2][kk] = ld16(kp + kk * KD);
+    }
+  }
+
+  // Process the 32-row tiles row_first, row_first + row_step, ... below row_end.  `rows` is
+  // the number of valid rows of the head (loads are clamped to it); `bm` (optional) marks rows
+  // to skip, one bit per row, word index = row / 32.
+  template <bool kPrefetch = true>
+  __device__ __forceinline__ void run(const T* kbase, const T* vbase, const uint32_t* bm, int rows, int row_first,
+                                      int row_end, int row_step, float sl2, int i, int c) {
+    if (row_first >= row_end) return;
+    u32x4 kf[2][NK];
+    load_k(kbase, row_first, rows, i, c, kf);
+    for (int row0 = row_first; row0 < row_end; row0 += row_step) {
+      // V of this tile first, then K of the next tile: both in flight during the QK product
+      u32x4 vf[8];
+      if constexpr (kBf16) {
+        // lane (i, c) loads, for e = 4 g2 + r, the 16-byte piece i of row row0 + 16 g2 + 4 c + r
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int vrow = min(row0 + 16 * (e >> 2) + 4 * c + (e & 3), rows - 1);
+          vf[e] = (i < D / 8) ? ld16(vbase + static_cast<int64_t>(vrow) * D + i * 8) : zero16();
+        }
+      }
+      f32x4 acc_s[2];
+#pragma unroll
+      for (int g2 = 0; g2 < 2; ++g2) {
+        acc_s[g2] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc_s[g2], kf[g2][kk], qf[kk]);
+      }
+      const int next0 = row0 + row_step;
+      if constexpr (kPrefetch) {
+        if (next0 < row_end) load_k(kbase, next0, rows, i, c, kf);
+      }
+      // ---- softmax weights: x[g2][r] <-> row row0 + 16 g2 + 4 c + r, head i -------------
+      const uint32_t skip = bm ? bm[row0 >> 5] : 0u;
+      float x[2][4];
+      float tm = -INFINITY;
+#pragma unroll
+      for (int g2 = 0; g2 < 2; ++g2)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int rr = 16 * g2 + 4 * c + r;
+          const bool live = (row0 + rr < row_end) && !((skip >> rr) & 1u);
+          x[g2][r] = live ? acc_s[g2][r] * sl2 : -INFINITY;
+          tm = fmaxf(tm, x[g2][r]);
+        }
+      tm = col4_max(tm);
+      const float mn = fmaxf(m, tm);
+      const float ms = (mn == -INFINITY) ? 0.f : mn;
+      const float alpha = fast_exp2(m - ms);
+      m = mn;
+      float p[2][4];
+      float ps = 0.f;
+#pragma unroll
+      for (int g2 = 0; g2 < 2; ++g2)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { p[g2][r] = fast_exp2(x[g2][r] - ms); ps += p[g2][r]; }
+      l = l * alpha + ps;
+      if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int xx = 0; xx < NACC; ++xx) acc_o[xx] *= alpha;
+      }
+      // ---- O^T += V^T P^T -----------------------------------------------------------------
+      if constexpr (kBf16) {
+        u32x4 pf;
+        pf[0] = pack_bf16x2(p[0][0], p[0][1]);
+        pf[1] = pack_bf16x2(p[0][2], p[0][3]);
+        pf[2] = pack_bf16x2(p[1][0], p[1][1]);
+        pf[3] = pack_bf16x2(p[1][2], p[1][3]);
+#pragma unroll
+        for (int xx = 0; xx < 8; ++xx) {
+          // A fragment of instruction xx: element xx of each of the 8 loaded pieces (8 rows)
+          u32x4 af;
+#pragma unroll
+          for (int ww = 0; ww < 4; ++ww) {
+            const uint32_t lo = vf[2 * ww][xx >> 1], hi = vf[2 * ww + 1][xx >> 1];
+            af[ww] = (xx & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
+          }
+          mma_step<bf16_t>(acc_o[xx], af, pf);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int vrow = min(row0 + 16 * (e >> 2) + 4 * c + (e & 3), rows - 1);
+          const float pe = p[e >> 2][e & 3];
+#pragma unroll
+          for (int dh = 0; dh < D / 64; ++dh) {
+            u32x4 v4 = ld16(vbase + static_cast<int64_t>(vrow) * D + (i + 16 * dh) * 4);
+#pragma unroll
+            for (int xx = 0; xx < 4; ++xx)
+              acc_o[dh * 4 + xx] =
+                  __builtin_amdgcn_mfma_f32_16x16x4f32(as_f32(v4[xx]), pe, acc_o[dh * 4 + xx], 0, 0, 0);
+          }
+        }
+      }
+      if constexpr (!kPrefetch) {
+        if (next0 < row_end) load_k(kbase, next0, rows, i, c, kf);
+      }
+    }
+  }
+
+  // Publish this wave's (max, sum) and unnormalised outputs for heads < G: s_o [G][D], s_ml [G].
+  __device__ __forceinline__ void publish(float* s_o, float2* s_ml, int G, int i, int c) {
+    const float lsum = col4_sum(l);
+    if (i < G) {
+      if (c == 0) s_ml[i] = make_float2(m, lsum);
+#pragma unroll
+      for (int xx = 0; xx < NACC; ++xx)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int slot = 4 * c + r;      // output row of the tile = d slot
+          int d;
+          if constexpr (kBf16) d = 8 * slot + xx;
+          else d = 4 * (slot + 16 * (xx >> 2)) + (xx & 3);
+          if (d < D) s_o[i * D + d] = acc_o[xx][r];
+        }
+    }
+  }
+};
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
-  constexpr int EPL = Elem<T>::kPer16B;
-  constexpr int KD = Elem<T>::kStepK;
-  constexpr int NK = D / KD;
-  constexpr bool kBf16 = sizeof(T) == 2;
-  constexpr int NACC = kBf16 ? 8 : D / 16;          // output accumulators per lane (x4 floats)
   const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   int rows, head_stride, off0;
   attend_geometry(a, b, rows, head_stride, off0);
@@ -66,123 +211,20 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
   const T* vbase = static_cast<const T*>(a.v) + head_tok * D;
   const uint32_t* bm = a.bitmap ? a.bitmap + static_cast<int64_t>(b * a.Hkv + g) * a.W32 : nullptr;
 
-  // query fragments: B operand, column i = head i of the group (zero beyond G)
-  u32x4 qf[NK];
+  AttendWave<T, D> w;
   {
     const int h = g * a.G + i;
     const T* qp = static_cast<const T*>(a.q);
     if (a.q_is_window) qp += (static_cast<int64_t>(b * a.Hq + h) * a.w + (a.w - 1)) * D;
     else qp += static_cast<int64_t>(b * a.Hq + h) * D;
-#pragma unroll
-    for (int kk = 0; kk < NK; ++kk) qf[kk] = (i < a.G) ? ld16(qp + kk * KD + c * EPL) : zero16();
+    w.init(qp, i < a.G, c);
   }
-
-  f32x4 acc_o[NACC];
-#pragma unroll
-  for (int x = 0; x < NACC; ++x) acc_o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m = -INFINITY, l = 0.f;     // per head (column i); l is this lane's share of the sum
-
-  for (int row0 = row_begin + wv * kTileRows; row0 < row_end; row0 += kAttWaves * kTileRows) {
-    // ---- logits: acc_s[g2][r] <-> row row0 + 16 g2 + 4 c + r, head i ----------------------
-    f32x4 acc_s[2];
-#pragma unroll
-    for (int g2 = 0; g2 < 2; ++g2) {
-      const int krow = min(row0 + 16 * g2 + i, rows - 1);
-      const T* kp = kbase + static_cast<int64_t>(krow) * D + c * EPL;
-      u32x4 kf[NK];
-#pragma unroll
-      for (int kk = 0; kk < NK; ++kk) kf[kk] = ld16(kp + kk * KD);
-      acc_s[g2] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc_s[g2], kf[kk], qf[kk]);
-    }
-    const uint32_t notev = bm ? bm[row0 >> 5] : 0u;
-    float x[2][4];
-    float tm = -INFINITY;
-#pragma unroll
-    for (int g2 = 0; g2 < 2; ++g2)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int rr = 16 * g2 + 4 * c + r;
-        const bool live = (row0 + rr < row_end) && !((notev >> rr) & 1u);
-        x[g2][r] = live ? acc_s[g2][r] * a.sl2 : -INFINITY;
-        tm = fmaxf(tm, x[g2][r]);
-      }
-    tm = col4_max(tm);
-    const float mn = fmaxf(m, tm);
-    const float ms = (mn == -INFINITY) ? 0.f : mn;
-    const float alpha = fast_exp2(m - ms);
-    m = mn;
-    float p[2][4];
-    float ps = 0.f;
-#pragma unroll
-    for (int g2 = 0; g2 < 2; ++g2)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) { p[g2][r] = fast_exp2(x[g2][r] - ms); ps += p[g2][r]; }
-    l = l * alpha + ps;
-    if (__any(alpha != 1.f)) {
-#pragma unroll
-      for (int xx = 0; xx < NACC; ++xx) acc_o[xx] *= alpha;
-    }
-    // ---- O^T += V^T P^T -------------------------------------------------------------------
-    if constexpr (kBf16) {
-      // lane (i, c) loads, for e = 4 g2 + r, the 16-byte piece i of row row0 + 16 g2 + 4 c + r
-      u32x4 vf[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int vrow = min(row0 + 16 * (e >> 2) + 4 * c + (e & 3), rows - 1);
-        vf[e] = (i < D / 8) ? ld16(vbase + static_cast<int64_t>(vrow) * D + i * 8) : zero16();
-      }
-      u32x4 pf;
-      pf[0] = pack_bf16x2(p[0][0], p[0][1]);
-      pf[1] = pack_bf16x2(p[0][2], p[0][3]);
-      pf[2] = pack_bf16x2(p[1][0], p[1][1]);
-      pf[3] = pack_bf16x2(p[1][2], p[1][3]);
-#pragma unroll
-      for (int xx = 0; xx < 8; ++xx) {
-        // A fragment of instruction xx: element xx of each of the 8 loaded pieces (8 rows)
-        u32x4 af;
-#pragma unroll
-        for (int ww = 0; ww < 4; ++ww) {
-          const uint32_t lo = vf[2 * ww][xx >> 1], hi = vf[2 * ww + 1][xx >> 1];
-          af[ww] = (xx & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
-        }
-        mma_step<bf16_t>(acc_o[xx], af, pf);
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int vrow = min(row0 + 16 * (e >> 2) + 4 * c + (e & 3), rows - 1);
-        const float pe = p[e >> 2][e & 3];
-#pragma unroll
-        for (int dh = 0; dh < D / 64; ++dh) {
-          u32x4 vf = ld16(vbase + static_cast<int64_t>(vrow) * D + (i + 16 * dh) * 4);
-#pragma unroll
-          for (int xx = 0; xx < 4; ++xx)
-            acc_o[dh * 4 + xx] =
-                __builtin_amdgcn_mfma_f32_16x16x4f32(as_f32(vf[xx]), pe, acc_o[dh * 4 + xx], 0, 0, 0);
-        }
-      }
-    }
-  }
-  l = col4_sum(l);
+  w.run(kbase, vbase, bm, rows, row_begin + wv * kTileRows, row_end, kAttWaves * kTileRows, a.sl2, i, c);
 
   // ---- merge the 4 waves through LDS and write this split's partial ------------------------
-  __shared__ float s_o[kAttWaves][16][D];
+  __shared__ float s_o[kAttWaves][16 * D];
   __shared__ float2 s_ml[kAttWaves][16];
-  if (i < a.G) {
-    if (c == 0) s_ml[wv][i] = make_float2(m, l);
-#pragma unroll
-    for (int xx = 0; xx < NACC; ++xx)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int slot = 4 * c + r;      // output row of the tile = d slot
-        int d;
-        if constexpr (kBf16) d = 8 * slot + xx;
-        else d = 4 * (slot + 16 * (xx >> 2)) + (xx & 3);
-        if (d < D) s_o[wv][i][d] = acc_o[xx][r];
-      }
-  }
+  w.publish(s_o[wv], s_ml[wv], a.G, i, c);
   __syncthreads();
   for (int t = threadIdx.x; t < a.G * D; t += 256) {
     const int hh = t / D, d = t - hh * D;
@@ -194,7 +236,7 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
 #pragma unroll
     for (int ww = 0; ww < kAttWaves; ++ww) {
       const float sc = fast_exp2(s_ml[ww][hh].x - ms);
-      o += s_o[ww][hh][d] * sc;
+      o += s_o[ww][hh * D + d] * sc;
       ll += s_ml[ww][hh].y * sc;
     }
     const int64_t slot = (static_cast<int64_t>(b * a.Hq + g * a.G + hh)) * a.NS + split;
@@ -294,6 +336,119 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
   if (d == 0) {
     if (a.a_lse) a.a_lse[hd] = lse;
     if (a.flags) a.flags[hd] = flag;
+  }
+}
+
+struct DecodeFusedArgs {
+  const void* q; const void* k; const void* v;
+  const int32_t* row_off; const int32_t* row_len;
+  int batch, Hq, Hkv, G, max_len;
+  float sl2, theta1, theta2;
+  const float* c_q; const float* c_out; const float* c_lse;
+  void* out; float* a_lse; uint8_t* flags;
+};
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) x += __shfl_xor(x, s);
+  return x;
+}
+
+// Whole decode step of one (sequence, KV head) in a single workgroup of NW waves: streaming
+// attention over the live cache rows (Alg. 2 step 1), merge of the waves' partials by
+// Eq. 1-2, cosine gate (step 2) and calibration merge (steps 9-11).  No workspace.
+template <typename T, int D, int NW>
+__global__ __launch_bounds__(NW * 64) void decode_fused_kernel(DecodeFusedArgs a) {
+  const int g = blockIdx.x, b = blockIdx.y;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int i = lane & 15, c = lane >> 4;
+  const int off0 = a.row_off[b];
+  const int cap = a.row_off[b + 1] - off0;
+  const int len = a.row_len[b];
+  const int rows = (len < 0 || len > cap || len > a.max_len) ? 0 : len;
+  const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * cap;
+  const T* kbase = static_cast<const T*>(a.k) + head_tok * D;
+  const T* vbase = static_cast<const T*>(a.v) + head_tok * D;
+  const T* qbase = static_cast<const T*>(a.q) + static_cast<int64_t>(b * a.Hq + g * a.G) * D;
+
+  // Operands of the gate/merge tail, fetched up front so they arrive with the K/V stream
+  // (wave wv finishes head wv; groups larger than the wave count loop and reload).
+  float qd[D / 64], cq[D / 64], co[D / 64];
+  float c_lse0 = -INFINITY;
+  const bool has_tail = wv < a.G;
+  if (has_tail) {
+    const int64_t hd = static_cast<int64_t>(b * a.Hq + g * a.G + wv);
+#pragma unroll
+    for (int u = 0; u < D / 64; ++u) {
+      qd[u] = load_elem<T>(qbase, static_cast<int64_t>(wv) * D + lane + 64 * u);
+      cq[u] = a.c_q[hd * D + lane + 64 * u];
+      co[u] = a.c_out[hd * D + lane + 64 * u];
+    }
+    c_lse0 = a.c_lse[hd];
+  }
+
+  AttendWave<T, D> w;
+  w.init(qbase + static_cast<int64_t>(i) * D, i < a.G, c);
+  w.template run<true>(kbase, vbase, nullptr, rows, wv * kTileRows, rows, NW * kTileRows, a.sl2, i, c);
+
+  extern __shared__ float s_dyn[];                 // [NW][G][D] outputs, then [NW][G] (max, sum)
+  float* s_o = s_dyn;
+  float2* s_ml = reinterpret_cast<float2*>(s_dyn + NW * a.G * D);
+  w.publish(s_o + wv * a.G * D, s_ml + wv * a.G, a.G, i, c);
+  __syncthreads();
+
+  for (int hh = wv; hh < a.G; hh += NW) {           // one wave finishes one head
+    const int64_t hd = static_cast<int64_t>(b * a.Hq + g * a.G + hh);
+    float c_lse = c_lse0;
+    if (hh != wv) {
+#pragma unroll
+      for (int u = 0; u < D / 64; ++u) {
+        qd[u] = load_elem<T>(qbase, static_cast<int64_t>(hh) * D + lane + 64 * u);
+        cq[u] = a.c_q[hd * D + lane + 64 * u];
+        co[u] = a.c_out[hd * D + lane + 64 * u];
+      }
+      c_lse = a.c_lse[hd];
+    }
+    float mm = -INFINITY;
+    for (int ww = 0; ww < NW; ++ww) mm = fmaxf(mm, s_ml[ww * a.G + hh].x);
+    const float ms = (mm == -INFINITY) ? 0.f : mm;
+    float ll = 0.f;
+    float o[D / 64];
+#pragma unroll
+    for (int u = 0; u < D / 64; ++u) o[u] = 0.f;
+    for (int ww = 0; ww < NW; ++ww) {
+      const float2 ml = s_ml[ww * a.G + hh];
+      const float sc = fast_exp2(ml.x - ms);
+      ll += ml.y * sc;
+#pragma unroll
+      for (int u = 0; u < D / 64; ++u) o[u] += s_o[(ww * a.G + hh) * D + lane + 64 * u] * sc;
+    }
+    const bool any = ll > 0.f;
+    const float lse = any ? (mm + fast_log2(ll)) * kLn2 : -INFINITY;
+    float dot = 0.f, nq2 = 0.f, nc2 = 0.f;
+#pragma unroll
+    for (int u = 0; u < D / 64; ++u) {
+      dot += qd[u] * cq[u];
+      nq2 += qd[u] * qd[u];
+      nc2 += cq[u] * cq[u];
+    }
+    dot = wave_sum(dot); nq2 = wave_sum(nq2); nc2 = wave_sum(nc2);
+    float rho = 0.f;
+    if (nq2 > 0.f && nc2 > 0.f) rho = dot / (sqrtf(nq2) * sqrtf(nc2));
+    uint8_t flag = 0;
+    float aj = 0.f;
+    if (rho < a.theta1) flag = 2;
+    else if (rho > a.theta2 && c_lse > -INFINITY) { flag = 1; aj = 1.f / (1.f + __expf(lse - c_lse)); }
+#pragma unroll
+    for (int u = 0; u < D / 64; ++u) {
+      float res = any ? o[u] / ll : 0.f;
+      if (flag == 1) res = (1.f - aj) * res + aj * co[u];
+      store_elem<T>(static_cast<T*>(a.out), hd * D + lane + 64 * u, res);
+    }
+    if (lane == 0) {
+      if (a.a_lse) a.a_lse[hd] = lse;
+      if (a.flags) a.flags[hd] = flag;
+    }
   }
 }
 

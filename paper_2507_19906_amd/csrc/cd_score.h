@@ -15,7 +15,7 @@ namespace cd {
 
 constexpr int kRowBlock = 128;     // query rows per workgroup (8 MFMA tiles of 16)
 constexpr int kRowTiles = 8;
-constexpr int kChunkKeys = 256;    // keys per workgroup in the scoring passes (4 waves x 64)
+constexpr int kMinChunkKeys = 256; // keys per workgroup in the scoring passes: a multiple of this
 
 struct ScoreArgs {
   const void* q_win;
@@ -23,6 +23,7 @@ struct ScoreArgs {
   const int32_t* seq_off;
   int64_t total_tokens;
   int batch, Hq, Hkv, G, w, B, R, NRB, NCH, max_seq_len, pool_k;
+  int chunk_keys;       // keys per workgroup (multiple of 64); each wave takes chunk_keys/4 contiguous keys
   float sl2;            // scale * log2(e)
   float2* rowpart;      // [batch*Hkv*NRB*128][NCH] (max, sum) per chunk
   float* row_lse;       // [batch*Hkv*NRB*128] log2-domain row log-sum-exp
@@ -66,14 +67,16 @@ struct ScoreTile {
     }
   }
 
-  // acc[rt][r] = raw dot product of key (key0 + 4c + r) with query row (16 rt + i).
-  __device__ __forceinline__ void logits(const T* kbase, int key0, int n, int i, int c,
-                                         f32x4 (&acc)[kRowTiles]) const {
+  // Key fragments of the 16-key tile starting at key0 (rows clamped to the sequence).
+  __device__ __forceinline__ void load_k(const T* kbase, int key0, int n, int i, int c, u32x4 (&kf)[NK]) const {
     int krow = min(key0 + i, n - 1);
     const T* kp = kbase + static_cast<int64_t>(krow) * D + c * EPL;
-    u32x4 kf[NK];
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) kf[kk] = ld16(kp + kk * KD);
+  }
+
+  // acc[rt][r] = raw dot product of key (key0 + 4c + r) with query row (16 rt + i).
+  __device__ __forceinline__ void logits(const u32x4 (&kf)[NK], f32x4 (&acc)[kRowTiles]) const {
 #pragma unroll
     for (int rt = 0; rt < kRowTiles; ++rt) {
       acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   if (n <= a.B) return;
-  const int key_base = chunk * kChunkKeys;
+  const int key_base = chunk * a.chunk_keys;
   if (key_base >= n) return;
   const int P = n - a.w;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -107,23 +110,41 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
 #pragma unroll
   for (int rt = 0; rt < kRowTiles; ++rt) { m[rt] = -INFINITY; l[rt] = 0.f; }
 
-  for (int t = 0; t < 4; ++t) {
-    const int key0 = key_base + wv * 64 + t * 16;
-    if (key0 >= n) break;
-    f32x4 acc[kRowTiles];
-    st.logits(kbase, key0, n, i, c, acc);
-    const int kfirst = key0 + 4 * c;
+  const int wave_keys = a.chunk_keys >> 2;
+  const int wave_first = key_base + wv * wave_keys;
+  const int wave_end = min(n, wave_first + wave_keys);
+  if (wave_first < wave_end) {
+    u32x4 kf[ScoreTile<T, D>::NK];
+    st.load_k(kbase, wave_first, n, i, c, kf);
+    for (int key0 = wave_first; key0 < wave_end; key0 += 16) {
+      f32x4 acc[kRowTiles];
+      st.logits(kf, acc);
+      if (key0 + 16 < wave_end) st.load_k(kbase, key0 + 16, n, i, c, kf);   // next tile in flight
+      const int kfirst = key0 + 4 * c;
+      float x[kRowTiles][4];
+      float tm[kRowTiles];
+      bool grow = false;
 #pragma unroll
-    for (int rt = 0; rt < kRowTiles; ++rt) {
-      float x[4];
+      for (int rt = 0; rt < kRowTiles; ++rt) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) x[r] = (kfirst + r <= st.lim[rt]) ? acc[rt][r] * a.sl2 : -INFINITY;
-      float tm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-      float mn = fmaxf(m[rt], tm);
-      float ms = (mn == -INFINITY) ? 0.f : mn;
-      float s = fast_exp2(x[0] - ms) + fast_exp2(x[1] - ms) + fast_exp2(x[2] - ms) + fast_exp2(x[3] - ms);
-      l[rt] = l[rt] * fast_exp2(m[rt] - ms) + s;
-      m[rt] = mn;
+        for (int r = 0; r < 4; ++r) x[rt][r] = (kfirst + r <= st.lim[rt]) ? acc[rt][r] * a.sl2 : -INFINITY;
+        tm[rt] = fmaxf(fmaxf(x[rt][0], x[rt][1]), fmaxf(x[rt][2], x[rt][3]));
+        grow |= tm[rt] > m[rt];
+      }
+      if (__any(grow)) {                 // some row's running maximum rises: rescale its sum
+#pragma unroll
+        for (int rt = 0; rt < kRowTiles; ++rt) {
+          const float mn = fmaxf(m[rt], tm[rt]);
+          const float ms = (mn == -INFINITY) ? 0.f : mn;
+          l[rt] *= fast_exp2(m[rt] - ms);
+          m[rt] = mn;
+        }
+      }
+#pragma unroll
+      for (int rt = 0; rt < kRowTiles; ++rt) {
+        const float ms = (m[rt] == -INFINITY) ? 0.f : m[rt];
+        l[rt] += (fast_exp2(x[rt][0] - ms) + fast_exp2(x[rt][1] - ms)) + (fast_exp2(x[rt][2] - ms) + fast_exp2(x[rt][3] - ms));
+      }
     }
   }
   // merge the four lanes that hold the same row (different keys), then the four waves
@@ -154,7 +175,7 @@ __global__ __launch_bounds__(256) void rowstats_merge_kernel(ScoreArgs a) {
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   if (n <= a.B) return;
-  const int nch = (n + kChunkKeys - 1) / kChunkKeys;
+  const int nch = (n + a.chunk_keys - 1) / a.chunk_keys;
   float m = -INFINITY, l = 0.f;
   for (int ch = lane; ch < nch; ch += 64) {
     float2 v = a.rowpart[gr * a.NCH + ch];
@@ -177,7 +198,7 @@ __global__ __launch_bounds__(256) void score_votes_kernel(ScoreArgs a) {
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   if (n <= a.B) return;
   const int P = n - a.w;
-  const int key_base = chunk * kChunkKeys;
+  const int key_base = chunk * a.chunk_keys;
   if (key_base >= P) return;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int i = lane & 15, c = lane >> 4;
@@ -191,11 +212,16 @@ __global__ __launch_bounds__(256) void score_votes_kernel(ScoreArgs a) {
 #pragma unroll
   for (int rt = 0; rt < kRowTiles; ++rt) lse[rt] = a.row_lse[static_cast<int64_t>(y) * kRowBlock + rt * 16 + i];
 
-  for (int t = 0; t < 4; ++t) {
-    const int key0 = key_base + wv * 64 + t * 16;
-    if (key0 >= P) break;
+  const int wave_keys = a.chunk_keys >> 2;
+  const int wave_first = key_base + wv * wave_keys;
+  const int wave_end = min(P, wave_first + wave_keys);
+  if (wave_first >= wave_end) return;
+  u32x4 kf[ScoreTile<T, D>::NK];
+  st.load_k(kbase, wave_first, n, i, c, kf);
+  for (int key0 = wave_first; key0 < wave_end; key0 += 16) {
     f32x4 acc[kRowTiles];
-    st.logits(kbase, key0, n, i, c, acc);
+    st.logits(kf, acc);
+    if (key0 + 16 < wave_end) st.load_k(kbase, key0 + 16, n, i, c, kf);     // next tile in flight
     float v[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int rt = 0; rt < kRowTiles; ++rt) {

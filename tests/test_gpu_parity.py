@@ -62,6 +62,30 @@ def test_shapes_and_ragged_tails(wl):
     run_case(wl)
 
 
+@pytest.mark.parametrize("dtype,D,budget", [("bf16", 128, 64), ("fp32", 64, 200), ("bf16", 64, 300),
+                                            ("bf16", 128, 600)])
+def test_many_sequences_single_workgroup_decode(dtype, D, budget):
+    # >= 192 (sequence, KV head) pairs: decode runs as one workgroup per pair (4, 8 or 16 waves)
+    g = torch.Generator().manual_seed(budget)
+    lens = torch.randint(budget // 2, 3 * budget, (100,), generator=g).tolist()
+    wl = small(dtype, 8, 2, D, lens, 16, budget, 5, T=3, name=f"many_seqs_{dtype}_{D}_{budget}")
+    x = to_dev(synth.make_inputs(wl, 17))
+    bufs = H.gpu_compress(wl, x, extra_capacity=8)
+    rep = {}
+    seqs = [0, 1, 37, 99, int(np.argmin(lens)), int(np.argmax(lens))]
+    for b in seqs:
+        H.check_compress(wl, x, bufs, b, report=rep)
+    for t in range(3):
+        if t == 2:      # ragged live lengths: append rows to some sequences, empty one
+            bufs.cache_lens[1::2] += 5
+            bufs.cache_lens[37] = 0
+        bufs.decode(x["q_dec"][t])
+        torch.cuda.synchronize()
+        for b in seqs:
+            H.check_decode_step(wl, bufs, x["q_dec"][t], b, report=rep)
+    print(wl.name, {k: v for k, v in rep.items() if k != "flags"}, flush=True)
+
+
 def test_exact_ties_lower_index_wins():
     # periodic keys: position j and j + period have identical keys, hence bit-identical votes
     # on both sides; with k = 1 the scores tie exactly and the lower position must be kept
