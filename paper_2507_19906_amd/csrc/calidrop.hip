@@ -180,25 +180,32 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
     if ((rc = launch_status("rowstats_merge"))) return rc;
     hipLaunchKernelGGL((cd::score_votes_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
     if ((rc = launch_status("score_votes"))) return rc;
-    hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
-    if ((rc = launch_status("pool_scores"))) return rc;
   }
 
+  // Pooling + selection + gather.  Heads whose pooled scores fit in LDS are pooled inside the
+  // selection kernel; longer ones go through the pooled-score buffer in the workspace.
   cd::SelectArgs se{};
-  se.seq_off = seq_offsets; se.total_tokens = total_tokens; se.batch = p->batch; se.Hkv = p->n_kv_heads;
-  se.w = p->window; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
-  se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
+  se.seq_off = seq_offsets; se.cache_off = cache_offsets; se.total_tokens = total_tokens; se.batch = p->batch;
+  se.Hkv = p->n_kv_heads; se.w = p->window; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
+  se.NRB = L.NRB; se.pool_k = p->pool_kernel; se.row_bytes = D * static_cast<int>(sizeof(T));
+  se.vote = sa.vote; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
   se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
-  hipLaunchKernelGGL(cd::select_topk_kernel, dim3(bg), dim3(cd::kSelThreads), 0, st, se);
-  if ((rc = launch_status("select_topk"))) return rc;
-
-  cd::GatherArgs ga{};
-  ga.k = k; ga.v = v; ga.k_c = k_c; ga.v_c = v_c; ga.seq_off = seq_offsets; ga.cache_off = cache_offsets;
-  ga.indices = indices; ga.total_tokens = total_tokens; ga.batch = p->batch; ga.Hkv = p->n_kv_heads;
-  ga.B = p->budget; ga.max_seq_len = max_seq_len; ga.row_bytes = D * static_cast<int>(sizeof(T));
-  const int vecs = p->budget * (ga.row_bytes / 16);
-  hipLaunchKernelGGL(cd::gather_kv_kernel, dim3(ceil_div(vecs, 256), bg), dim3(256), 0, st, ga);
-  if ((rc = launch_status("gather_kv"))) return rc;
+  se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
+  const int max_prefix = max_seq_len - p->window;
+  if (max_prefix <= cd::kSelMaxLdsKeys) {
+    const size_t lds = max_seq_len > p->budget ? static_cast<size_t>(max_prefix) * sizeof(uint32_t) : 0;
+    if (lds > 48 * 1024) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cd::select_gather_kernel<true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(cd::select_gather_kernel<true>, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
+  } else {
+    hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
+    if ((rc = launch_status("pool_scores"))) return rc;
+    hipLaunchKernelGGL(cd::select_gather_kernel<false>, dim3(bg), dim3(cd::kSelThreads), 0, st, se);
+  }
+  if ((rc = launch_status("select_gather"))) return rc;
 
   cd::AttendArgs aa{};
   aa.q = q_cal ? q_cal : q_win; aa.q_is_window = q_cal ? 0 : 1;

@@ -5,9 +5,10 @@
 //   pass 2 (score_votes):    S recomputed, p = exp2(s - lse_row), column sums over the G*w
 //           rows of the KV head -> vote[j] for prefix columns j < P.
 //   pool_scores: 1-D average pooling of the votes.
-// Tile orientation: S^T = K Q^T, i.e. keys are the A rows and query rows the B columns, so a
-// lane owns one query row per 16-row tile (cheap running row statistics) and 4 keys.
-// A workgroup owns a block of up to 128 query rows (8 tiles) and a chunk of kChunkKeys keys.
+// A workgroup owns a block of up to 128 query rows and a chunk of keys; its four waves own 32
+// rows each and share the key tiles through LDS.  Pass 1 forms S^T = K Q^T (a lane owns one
+// query row per tile: running row statistics stay in registers); pass 2 forms S = Q K^T (a
+// lane owns one key: the column sum over rows is an in-lane sum plus a 4-lane tree).
 #pragma once
 #include "cd_common.h"
 
@@ -42,52 +43,80 @@ __device__ __forceinline__ int seq_len_checked(const int32_t* seq_off, int b, in
   return n;
 }
 
+// Streams the keys of one workgroup's chunk through LDS: global -> registers (two stages in
+// flight) -> LDS (two buffers), so that the four waves, which own 32 query rows each, all read
+// every key tile from LDS instead of each loading it from memory.  LDS rows are 16-byte chunks
+// with chunk' = chunk ^ (key & 7), which makes both the row-wise writes and the column-wise
+// fragment reads bank-conflict free.
 template <typename T, int D>
-struct ScoreTile {
+struct KeyStream {
   static constexpr int EPL = Elem<T>::kPer16B;
   static constexpr int KD = Elem<T>::kStepK;
   static constexpr int NK = D / KD;
+  static constexpr int kStageKeys = sizeof(T) == 2 ? 64 : 32;
+  static constexpr int KT = kStageKeys / 16;                       // key tiles per stage
+  static constexpr int CH = D * static_cast<int>(sizeof(T)) / 16;  // 16-byte chunks per key row
+  static constexpr int NLD = kStageKeys * CH / 256;                // loads per thread per stage
+  static constexpr int kStageBytes = kStageKeys * CH * 16;
 
-  u32x4 qf[kRowTiles][NK];
-  int lim[kRowTiles];      // last visible key position of this lane's row in tile rt (-1: none)
+  // registers of one in-flight stage
+  struct Regs { u32x4 v[NLD]; };
 
-  // Fragments of the row block's queries: lane (i, c) holds row 16*rt + i.
-  __device__ __forceinline__ void load_q(const ScoreArgs& a, int b, int g, int rb, int P, int i, int c) {
-    const T* q = static_cast<const T*>(a.q_win);
+  __device__ __forceinline__ static void load(Regs& r, const T* kbase, int key0, int n) {
+    const char* base = reinterpret_cast<const char*>(kbase);
 #pragma unroll
-    for (int rt = 0; rt < kRowTiles; ++rt) {
-      int rho = rb * kRowBlock + rt * 16 + i;
-      bool valid = rho < a.R;
-      int hh = valid ? rho / a.w : 0;
-      int wi = valid ? rho - hh * a.w : 0;
+    for (int u = 0; u < NLD; ++u) {
+      const int slot = threadIdx.x + u * 256;          // (key, chunk) in row-major order
+      const int key = min(key0 + slot / CH, n - 1);
+      r.v[u] = ld16(base + static_cast<int64_t>(key) * (CH * 16) + (slot % CH) * 16);
+    }
+  }
+  __device__ __forceinline__ static void store(const Regs& r, char* lds) {
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) {
+      const int slot = threadIdx.x + u * 256;
+      const int key = slot / CH, ch = slot % CH;
+      st16(lds + key * (CH * 16) + ((ch ^ (key & 7)) * 16), r.v[u]);
+    }
+  }
+  // fragment of key tile kt for mma step kk: lane (i, c) gets key 16 kt + i, chunk 4 kk + c
+  __device__ __forceinline__ static u32x4 frag(const char* lds, int kt, int kk, int i, int c) {
+    const int key = 16 * kt + i;
+    return ld16(lds + key * (CH * 16) + (((4 * kk + c) ^ (key & 7)) * 16));
+  }
+};
+
+// Query fragments of the 32 rows a wave owns: lane (i, c) holds row 16 rt + i of the wave.
+template <typename T, int D>
+struct WaveQueries {
+  static constexpr int EPL = Elem<T>::kPer16B;
+  static constexpr int KD = Elem<T>::kStepK;
+  static constexpr int NK = D / KD;
+  u32x4 qf[2][NK];
+  int lim[2];        // last visible key position of row (rt, i), -1 for padding rows
+  bool any_rows;     // wave-uniform: this wave owns at least one real row
+
+  __device__ __forceinline__ void load(const ScoreArgs& a, int b, int g, int rb, int wv, int P, int i, int c) {
+    const T* q = static_cast<const T*>(a.q_win);
+    any_rows = rb * kRowBlock + wv * 32 < a.R;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      const int rho = rb * kRowBlock + wv * 32 + rt * 16 + i;
+      const bool valid = rho < a.R;
+      const int hh = valid ? rho / a.w : 0;
+      const int wi = valid ? rho - hh * a.w : 0;
       const T* qp = q + (static_cast<int64_t>(b * a.Hq + g * a.G + hh) * a.w + wi) * D + c * EPL;
 #pragma unroll
       for (int kk = 0; kk < NK; ++kk) qf[rt][kk] = valid ? ld16(qp + kk * KD) : zero16();
       lim[rt] = valid ? P + wi : -1;
     }
   }
-
-  // Key fragments of the 16-key tile starting at key0 (rows clamped to the sequence).
-  __device__ __forceinline__ void load_k(const T* kbase, int key0, int n, int i, int c, u32x4 (&kf)[NK]) const {
-    int krow = min(key0 + i, n - 1);
-    const T* kp = kbase + static_cast<int64_t>(krow) * D + c * EPL;
-#pragma unroll
-    for (int kk = 0; kk < NK; ++kk) kf[kk] = ld16(kp + kk * KD);
-  }
-
-  // acc[rt][r] = raw dot product of key (key0 + 4c + r) with query row (16 rt + i).
-  __device__ __forceinline__ void logits(const u32x4 (&kf)[NK], f32x4 (&acc)[kRowTiles]) const {
-#pragma unroll
-    for (int rt = 0; rt < kRowTiles; ++rt) {
-      acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc[rt], kf[kk], qf[rt][kk]);
-    }
-  }
 };
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
+  using KS = KeyStream<T, D>;
+  constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys;
   const int chunk = blockIdx.x;
   const int y = blockIdx.y;
   const int rb = y % a.NRB;
@@ -99,68 +128,114 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
   if (n <= a.B) return;
   const int key_base = chunk * a.chunk_keys;
   if (key_base >= n) return;
+  const int key_end = min(n, key_base + a.chunk_keys);
+  const int nstages = (key_end - key_base + SK - 1) / SK;
   const int P = n - a.w;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int i = lane & 15, c = lane >> 4;
   const T* kbase = static_cast<const T*>(a.k) + (static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n) * D;
 
-  ScoreTile<T, D> st;
-  st.load_q(a, b, g, rb, P, i, c);
-  float m[kRowTiles], l[kRowTiles];
-#pragma unroll
-  for (int rt = 0; rt < kRowTiles; ++rt) { m[rt] = -INFINITY; l[rt] = 0.f; }
+  __shared__ __attribute__((aligned(16))) char s_k[2][KS::kStageBytes];
+  WaveQueries<T, D> wq;
+  wq.load(a, b, g, rb, wv, P, i, c);
+  float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
 
-  const int wave_keys = a.chunk_keys >> 2;
-  const int wave_first = key_base + wv * wave_keys;
-  const int wave_end = min(n, wave_first + wave_keys);
-  if (wave_first < wave_end) {
-    u32x4 kf[ScoreTile<T, D>::NK];
-    st.load_k(kbase, wave_first, n, i, c, kf);
-    for (int key0 = wave_first; key0 < wave_end; key0 += 16) {
-      f32x4 acc[kRowTiles];
-      st.logits(kf, acc);
-      if (key0 + 16 < wave_end) st.load_k(kbase, key0 + 16, n, i, c, kf);   // next tile in flight
-      const int kfirst = key0 + 4 * c;
-      float x[kRowTiles][4];
-      float tm[kRowTiles];
+  typename KS::Regs r0, r1;
+  KS::load(r0, kbase, key_base, n);
+  if (nstages > 1) KS::load(r1, kbase, key_base + SK, n);
+  KS::store(r0, s_k[0]);
+  __syncthreads();
+
+  // one stage: S^T tiles (keys x rows) of this wave's 32 rows against the stage's keys
+  auto compute = [&](const char* lds, int key0) {
+    if (!wq.any_rows) return;
+    f32x4 acc[KT][2];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      u32x4 kf[NK];
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) kf[kk] = KS::frag(lds, kt, kk, i, c);
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+        acc[kt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc[kt][rt], kf[kk], wq.qf[rt][kk]);
+      }
+    }
+    // acc[kt][rt][r] <-> key key0 + 16 kt + 4 c + r, row (rt, i)
+    if (key0 + SK <= P) {
+      // every key of the stage is a prefix key: visible to all rows, no masking
+      float tm[2];
       bool grow = false;
 #pragma unroll
-      for (int rt = 0; rt < kRowTiles; ++rt) {
+      for (int rt = 0; rt < 2; ++rt) {
+        float t = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) x[rt][r] = (kfirst + r <= st.lim[rt]) ? acc[rt][r] * a.sl2 : -INFINITY;
-        tm[rt] = fmaxf(fmaxf(x[rt][0], x[rt][1]), fmaxf(x[rt][2], x[rt][3]));
+        for (int kt = 0; kt < KT; ++kt)
+          t = fmaxf(t, fmaxf(fmaxf(acc[kt][rt][0], acc[kt][rt][1]), fmaxf(acc[kt][rt][2], acc[kt][rt][3])));
+        tm[rt] = t * a.sl2;
         grow |= tm[rt] > m[rt];
       }
       if (__any(grow)) {                 // some row's running maximum rises: rescale its sum
 #pragma unroll
-        for (int rt = 0; rt < kRowTiles; ++rt) {
+        for (int rt = 0; rt < 2; ++rt) {
           const float mn = fmaxf(m[rt], tm[rt]);
-          const float ms = (mn == -INFINITY) ? 0.f : mn;
-          l[rt] *= fast_exp2(m[rt] - ms);
+          l[rt] *= fast_exp2(m[rt] - mn);            // m = -inf only while l = 0: exp2(-inf) = 0
           m[rt] = mn;
         }
       }
 #pragma unroll
-      for (int rt = 0; rt < kRowTiles; ++rt) {
-        const float ms = (m[rt] == -INFINITY) ? 0.f : m[rt];
-        l[rt] += (fast_exp2(x[rt][0] - ms) + fast_exp2(x[rt][1] - ms)) + (fast_exp2(x[rt][2] - ms) + fast_exp2(x[rt][3] - ms));
+      for (int rt = 0; rt < 2; ++rt) {
+        const float nm = -m[rt];
+        float s = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+          s += (fast_exp2(fmaf(acc[kt][rt][0], a.sl2, nm)) + fast_exp2(fmaf(acc[kt][rt][1], a.sl2, nm))) +
+               (fast_exp2(fmaf(acc[kt][rt][2], a.sl2, nm)) + fast_exp2(fmaf(acc[kt][rt][3], a.sl2, nm)));
+        l[rt] += s;
+      }
+    } else {
+      // stage reaches into the window: causal mask per row, and the end of the sequence
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+          const int kfirst = key0 + 16 * kt + 4 * c;
+          float x[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) x[r] = (kfirst + r <= wq.lim[rt]) ? acc[kt][rt][r] * a.sl2 : -INFINITY;
+          const float tm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+          const float mn = fmaxf(m[rt], tm);
+          const float ms = (mn == -INFINITY) ? 0.f : mn;
+          l[rt] = l[rt] * fast_exp2(m[rt] - ms) +
+                  ((fast_exp2(x[0] - ms) + fast_exp2(x[1] - ms)) + (fast_exp2(x[2] - ms) + fast_exp2(x[3] - ms)));
+          m[rt] = mn;
+        }
       }
     }
+  };
+
+  for (int s = 0; s < nstages; s += 2) {
+    // even stage: buffer 0 holds stage s; r1 holds (or is receiving) stage s+1
+    if (s + 2 < nstages) KS::load(r0, kbase, key_base + (s + 2) * SK, n);
+    compute(s_k[0], key_base + s * SK);
+    if (s + 1 < nstages) KS::store(r1, s_k[1]);
+    __syncthreads();
+    if (s + 1 >= nstages) break;
+    // odd stage: buffer 1 holds stage s+1; r0 holds stage s+2
+    if (s + 3 < nstages) KS::load(r1, kbase, key_base + (s + 3) * SK, n);
+    compute(s_k[1], key_base + (s + 1) * SK);
+    if (s + 2 < nstages) KS::store(r0, s_k[0]);
+    __syncthreads();
   }
-  // merge the four lanes that hold the same row (different keys), then the four waves
-  __shared__ float2 sm[4][kRowBlock];
+
+  // merge the four lanes that hold the same row (different keys) and write the chunk partial
 #pragma unroll
-  for (int rt = 0; rt < kRowTiles; ++rt) {
+  for (int rt = 0; rt < 2; ++rt) {
     merge_ml(m[rt], l[rt], __shfl_xor(m[rt], 16), __shfl_xor(l[rt], 16));
     merge_ml(m[rt], l[rt], __shfl_xor(m[rt], 32), __shfl_xor(l[rt], 32));
-    if (c == 0) sm[wv][rt * 16 + i] = make_float2(m[rt], l[rt]);
-  }
-  __syncthreads();
-  if (threadIdx.x < kRowBlock) {
-    float mm = sm[0][threadIdx.x].x, ll = sm[0][threadIdx.x].y;
-#pragma unroll
-    for (int ww = 1; ww < 4; ++ww) merge_ml(mm, ll, sm[ww][threadIdx.x].x, sm[ww][threadIdx.x].y);
-    a.rowpart[(static_cast<int64_t>(y) * kRowBlock + threadIdx.x) * a.NCH + chunk] = make_float2(mm, ll);
+    if (c == 0)
+      a.rowpart[(static_cast<int64_t>(y) * kRowBlock + wv * 32 + rt * 16 + i) * a.NCH + chunk] = make_float2(m[rt], l[rt]);
   }
 }
 
@@ -183,11 +258,14 @@ __global__ __launch_bounds__(256) void rowstats_merge_kernel(ScoreArgs a) {
   }
 #pragma unroll
   for (int s = 1; s < 64; s <<= 1) merge_ml(m, l, __shfl_xor(m, s), __shfl_xor(l, s));
-  if (lane == 0) a.row_lse[gr] = (l > 0.f) ? m + fast_log2(l) : INFINITY;
+  const int rho = (y % a.NRB) * kRowBlock + static_cast<int>(gr % kRowBlock);    // row inside the KV head
+  if (lane == 0) a.row_lse[gr] = (l > 0.f && rho < a.R) ? m + fast_log2(l) : INFINITY;   // padding rows: +inf
 }
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void score_votes_kernel(ScoreArgs a) {
+  using KS = KeyStream<T, D>;
+  constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys;
   const int chunk = blockIdx.x;
   const int y = blockIdx.y;
   const int rb = y % a.NRB;
@@ -200,42 +278,71 @@ __global__ __launch_bounds__(256) void score_votes_kernel(ScoreArgs a) {
   const int P = n - a.w;
   const int key_base = chunk * a.chunk_keys;
   if (key_base >= P) return;
+  const int key_end = min(P, key_base + a.chunk_keys);
+  const int nstages = (key_end - key_base + SK - 1) / SK;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int i = lane & 15, c = lane >> 4;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
   const T* kbase = static_cast<const T*>(a.k) + head_tok * D;
   float* vote = a.vote + static_cast<int64_t>(rb) * a.total_tokens * a.Hkv + head_tok;
 
-  ScoreTile<T, D> st;
-  st.load_q(a, b, g, rb, P, i, c);
-  float lse[kRowTiles];
+  __shared__ __attribute__((aligned(16))) char s_k[2][KS::kStageBytes];
+  __shared__ float s_v[2][4][SK];                  // per-wave partial votes of a stage
+  WaveQueries<T, D> wq;
+  wq.load(a, b, g, rb, wv, P, i, c);
+  // S tiles are rows x keys here: lane (i, c) holds key i and rows 16 rt + 4 c + r of the wave
+  float lse[2][4];
 #pragma unroll
-  for (int rt = 0; rt < kRowTiles; ++rt) lse[rt] = a.row_lse[static_cast<int64_t>(y) * kRowBlock + rt * 16 + i];
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      lse[rt][r] = a.row_lse[static_cast<int64_t>(y) * kRowBlock + wv * 32 + rt * 16 + 4 * c + r];   // padding rows: +inf
 
-  const int wave_keys = a.chunk_keys >> 2;
-  const int wave_first = key_base + wv * wave_keys;
-  const int wave_end = min(P, wave_first + wave_keys);
-  if (wave_first >= wave_end) return;
-  u32x4 kf[ScoreTile<T, D>::NK];
-  st.load_k(kbase, wave_first, n, i, c, kf);
-  for (int key0 = wave_first; key0 < wave_end; key0 += 16) {
-    f32x4 acc[kRowTiles];
-    st.logits(kf, acc);
-    if (key0 + 16 < wave_end) st.load_k(kbase, key0 + 16, n, i, c, kf);     // next tile in flight
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
+  typename KS::Regs r0, r1;
+  KS::load(r0, kbase, key_base, n);
+  if (nstages > 1) KS::load(r1, kbase, key_base + SK, n);
+  KS::store(r0, s_k[0]);
+  __syncthreads();
+
+  auto compute = [&](const char* lds, float (*sv)[SK]) {
 #pragma unroll
-    for (int rt = 0; rt < kRowTiles; ++rt) {
+    for (int kt = 0; kt < KT; ++kt) {
+      u32x4 kf[NK];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) v[r] += fast_exp2(acc[rt][r] * a.sl2 - lse[rt]);   // padded rows: lse = +inf -> 0
+      for (int kk = 0; kk < NK; ++kk) kf[kk] = KS::frag(lds, kt, kk, i, c);
+      float v = 0.f;
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc, wq.qf[rt][kk], kf[kk]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v += fast_exp2(fmaf(acc[r], a.sl2, -lse[rt][r]));
+      }
+      v = col4_sum(v);                             // over the 4 row groups c: fixed tree
+      if (c == 0) sv[wv][16 * kt + i] = v;
     }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) v[r] = row16_sum(v[r]);
-    if (i == 0) {
-      const int kfirst = key0 + 4 * c;
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (kfirst + r < P) vote[kfirst + r] = v[r];
+  };
+  // after the stage barrier: add the four waves' partial votes in wave order and store
+  auto flush = [&](const float (*sv)[SK], int key0) {
+    if (threadIdx.x < SK) {
+      const int key = key0 + threadIdx.x;
+      if (key < P) vote[key] = ((sv[0][threadIdx.x] + sv[1][threadIdx.x]) + sv[2][threadIdx.x]) + sv[3][threadIdx.x];
     }
+  };
+
+  for (int s = 0; s < nstages; s += 2) {
+    if (s + 2 < nstages) KS::load(r0, kbase, key_base + (s + 2) * SK, n);
+    compute(s_k[0], s_v[0]);
+    if (s + 1 < nstages) KS::store(r1, s_k[1]);
+    __syncthreads();
+    flush(s_v[0], key_base + s * SK);
+    if (s + 1 >= nstages) break;
+    if (s + 3 < nstages) KS::load(r1, kbase, key_base + (s + 3) * SK, n);
+    compute(s_k[1], s_v[1]);
+    if (s + 2 < nstages) KS::store(r0, s_k[0]);
+    __syncthreads();
+    flush(s_v[1], key_base + (s + 1) * SK);
   }
 }
 
