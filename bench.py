@@ -91,6 +91,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--rotate", type=int, default=0, help="cache copies cycled by decode (0 = enough for 512 MiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy 4 times (calibrates the profiler's HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path exists)",
@@ -107,6 +109,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU path)"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.copy_probe:     # known traffic: 1 GiB read + 1 GiB written per launch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     wl = synth.config(3, layers=args.layers, budget=args.budget, decode_steps=args.decode_steps)
     x = synth.make_inputs(wl, device=dev)

@@ -83,8 +83,14 @@ size_t calidrop_compress_workspace_bytes(const calidrop_params* p, int64_t total
 /* Bytes of device workspace calidrop_decode needs (0 on invalid params).                     */
 size_t calidrop_decode_workspace_bytes(const calidrop_params* p, int32_t max_cache_len);
 
+/* Inspection switch (process-wide, default off).  When on, calidrop_compress also stores the
+ * pooled scores in the SCORE workspace region for every sequence; when off that region is only
+ * written for prompts too long for the in-LDS selection.  Costs one extra pass of stores.      */
+void calidrop_set_inspection(int enabled);
+
 /* Named regions inside the compress workspace, for inspection by tests and tools after the
- * stream has finished.  Layouts:
+ * stream has finished (SCORE needs calidrop_set_inspection(1) before the compress call).
+ * Layouts:
  *   ROW_LSE   float [batch][Hkv][NRB*128]: per window-query row, log2 of its softmax
  *             denominator over all visible keys (logits in log2 units); rows of a KV head are
  *             ordered (query head in group, window position); NRB = ceil(G*w / 128).

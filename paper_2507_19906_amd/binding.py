@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.calidrop_last_error.argtypes = []
         L.calidrop_version.restype = ctypes.c_int
         L.calidrop_version.argtypes = []
+        L.calidrop_set_inspection.restype = None
+        L.calidrop_set_inspection.argtypes = [ctypes.c_int]
         L.calidrop_compress_workspace_bytes.restype = sz
         L.calidrop_compress_workspace_bytes.argtypes = [pp, i64, i32]
         L.calidrop_decode_workspace_bytes.restype = sz
@@ -91,6 +93,10 @@ def lib() -> ctypes.CDLL:
 
 def calidrop_last_error() -> str:
     return lib().calidrop_last_error().decode()
+
+
+def calidrop_set_inspection(enabled: bool) -> None:
+    lib().calidrop_set_inspection(1 if enabled else 0)
 
 
 def _check(status: int) -> None:

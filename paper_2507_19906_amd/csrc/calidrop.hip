@@ -3,6 +3,7 @@
 // machine without a GPU.
 #include "../../include/calidrop.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -16,6 +17,7 @@
 namespace {
 
 thread_local char g_err[512] = "";
+std::atomic<int> g_inspection{0};   // calidrop_set_inspection
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -191,15 +193,24 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   se.vote = sa.vote; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
   se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
   se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
+#ifdef CD_SELECT_TIMING
+  se.dbg = reinterpret_cast<long long*>(ws + L.rowpart);
+#endif
   const int max_prefix = max_seq_len - p->window;
-  if (max_prefix <= cd::kSelMaxLdsKeys) {
-    const size_t lds = max_seq_len > p->budget ? static_cast<size_t>(max_prefix) * sizeof(uint32_t) : 0;
+  se.write_scores = g_inspection.load(std::memory_order_relaxed);
+  if (max_prefix <= cd::kSelMaxLdsKeys && p->budget <= cd::kSelMaxLdsKeys && p->pool_kernel <= cd::kSelMaxPool) {
+    // dynamic LDS: staged votes (padded), later reused for the retained indices
+    size_t lds = static_cast<size_t>(p->budget) * sizeof(int32_t);
+    if (max_seq_len > p->budget) {
+      const size_t votes = (static_cast<size_t>(max_prefix) + max_prefix / 32 + 1) * sizeof(float);
+      if (votes > lds) lds = votes;
+    }
     if (lds > 48 * 1024) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cd::select_gather_kernel<true>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cd::select_gather_lds_kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(cd::select_gather_kernel<true>, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
+    hipLaunchKernelGGL(cd::select_gather_lds_kernel, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
   } else {
     hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
     if ((rc = launch_status("pool_scores"))) return rc;
@@ -279,6 +290,7 @@ extern "C" {
 
 const char* calidrop_last_error(void) { return g_err; }
 int calidrop_version(void) { return 100; }
+void calidrop_set_inspection(int enabled) { g_inspection.store(enabled ? 1 : 0, std::memory_order_relaxed); }
 
 size_t calidrop_compress_workspace_bytes(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len) {
   if (check_params(p) != CALIDROP_OK || check_sizes(p, total_tokens, max_seq_len) != CALIDROP_OK) return 0;

@@ -46,8 +46,9 @@ __device__ __forceinline__ int seq_len_checked(const int32_t* seq_off, int b, in
 // Streams the keys of one workgroup's chunk through LDS: global -> registers (two stages in
 // flight) -> LDS (two buffers), so that the four waves, which own 32 query rows each, all read
 // every key tile from LDS instead of each loading it from memory.  LDS rows are 16-byte chunks
-// with chunk' = chunk ^ (key & 7), which makes both the row-wise writes and the column-wise
-// fragment reads bank-conflict free.
+// stored at chunk' = chunk ^ swz(key), chosen so that 16 consecutive lanes always touch 16
+// different 16-byte bank groups of a 256-byte window, both for the row-wise writes (lanes =
+// consecutive chunks) and for the column-wise fragment reads (lanes = consecutive keys).
 template <typename T, int D>
 struct KeyStream {
   static constexpr int EPL = Elem<T>::kPer16B;
@@ -58,6 +59,8 @@ struct KeyStream {
   static constexpr int CH = D * static_cast<int>(sizeof(T)) / 16;  // 16-byte chunks per key row
   static constexpr int NLD = kStageKeys * CH / 256;                // loads per thread per stage
   static constexpr int kStageBytes = kStageKeys * CH * 16;
+  static_assert(CH == 8 || CH == 16 || CH == 32, "row size not covered by the LDS swizzle");
+  __device__ __forceinline__ static int swz(int key) { return CH == 8 ? ((key >> 1) & 7) : (key & 15); }
 
   // registers of one in-flight stage
   struct Regs { u32x4 v[NLD]; };
@@ -76,13 +79,13 @@ struct KeyStream {
     for (int u = 0; u < NLD; ++u) {
       const int slot = threadIdx.x + u * 256;
       const int key = slot / CH, ch = slot % CH;
-      st16(lds + key * (CH * 16) + ((ch ^ (key & 7)) * 16), r.v[u]);
+      st16(lds + key * (CH * 16) + ((ch ^ swz(key)) * 16), r.v[u]);
     }
   }
   // fragment of key tile kt for mma step kk: lane (i, c) gets key 16 kt + i, chunk 4 kk + c
   __device__ __forceinline__ static u32x4 frag(const char* lds, int kt, int kk, int i, int c) {
     const int key = 16 * kt + i;
-    return ld16(lds + key * (CH * 16) + (((4 * kk + c) ^ (key & 7)) * 16));
+    return ld16(lds + key * (CH * 16) + (((4 * kk + c) ^ swz(key)) * 16));
   }
 };
 

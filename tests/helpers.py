@@ -34,6 +34,7 @@ def gpu_compress(wl, x, q_cal=None, extra_capacity=0, **over):
     p = params_for(wl, **over)
     dev = x["k"].device
     bufs = cd.CompressBuffers(p, wl.seq_lens, dev, extra_capacity=extra_capacity)
+    cd.calidrop_set_inspection(True)          # the parity checks read the pooled scores
     bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], q_cal=q_cal)
     torch.cuda.synchronize()
     return bufs

@@ -24,7 +24,8 @@ def test_header_symbols_are_exported():
     names = set(re.findall(r"\b(calidrop_[a-z_]+)\s*\(", hdr))
     assert {"calidrop_compress", "calidrop_decode", "calidrop_last_error",
             "calidrop_compress_workspace_bytes", "calidrop_decode_workspace_bytes",
-            "calidrop_compress_workspace_region", "calidrop_version"} <= names
+            "calidrop_compress_workspace_region", "calidrop_version",
+            "calidrop_set_inspection"} <= names
     L = cd.lib()
     for n in names:
         assert hasattr(L, n), n
