@@ -89,8 +89,8 @@ SplitPlan plan_splits(int heads_kv_total, int max_rows) {
 }
 
 struct CompressLayout {
-  size_t rowpart, row_lse, vote, score, bitmap, part_o, part_ml, total;
-  int NRB, NCH, W32, chunk_keys;
+  size_t rowpart, row_lse, vote, score, bitmap, cal_logit, part_o, part_ml, total;
+  int NRB, NCH, W32, chunk_keys, zstride;
   SplitPlan sp;
 };
 
@@ -116,6 +116,8 @@ CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, i
   L.vote = off;    off += round256(toks * L.NRB * sizeof(float));
   L.score = off;   off += round256(toks * sizeof(float));
   L.bitmap = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.W32 * sizeof(uint32_t));
+  L.zstride = ceil_div(max_seq_len, 32) * 32;
+  L.cal_logit = off; off += round256(static_cast<size_t>(p->batch) * p->n_q_heads * L.zstride * sizeof(float));
   const size_t slots = static_cast<size_t>(p->batch) * p->n_q_heads * L.sp.NS;
   L.part_o = off;  off += round256(slots * p->head_dim * sizeof(float));
   L.part_ml = off; off += round256(slots * sizeof(float2));
@@ -171,6 +173,15 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   sa.row_lse = reinterpret_cast<float*>(ws + L.row_lse);
   sa.vote = reinterpret_cast<float*>(ws + L.vote);
   sa.score = reinterpret_cast<float*>(ws + L.score);
+  // default calibration query = last window query: the vote pass exports its logits
+#ifdef CD_NO_CAL_EXPORT
+  const bool no_export = true;
+#else
+  const bool no_export = false;
+#endif
+  sa.cal_logit = (no_export || q_cal || G > cd::kMaxCalHeads || p->window % 4 != 0)
+                     ? nullptr : reinterpret_cast<float*>(ws + L.cal_logit);
+  sa.zstride = L.zstride;
 
   const int bg = p->batch * p->n_kv_heads;
   if (max_seq_len > p->budget) {       // otherwise no sequence can need eviction
@@ -224,10 +235,13 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   aa.total_tokens = total_tokens; aa.batch = p->batch; aa.Hq = p->n_q_heads; aa.Hkv = p->n_kv_heads; aa.G = G;
   aa.w = p->window; aa.B = p->budget; aa.max_len = max_seq_len; aa.W32 = L.W32;
   aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = sl2;
+  aa.cal_logit = sa.cal_logit; aa.zstride = L.zstride;
   aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
   aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
   if (max_seq_len > p->budget) {
-    hipLaunchKernelGGL((cd::attend_partial_kernel<T, D>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0, st, aa);
+    const dim3 grid_a(L.sp.NS, p->n_kv_heads, p->batch);
+    if (aa.cal_logit) hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, true>), grid_a, dim3(256), 0, st, aa);
+    else hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false>), grid_a, dim3(256), 0, st, aa);
     if ((rc = launch_status("attend_partial(calibration)"))) return rc;
   }
   cd::FinalArgs fa{};
@@ -269,9 +283,11 @@ int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, cons
   aa.bitmap = nullptr; aa.total_tokens = 0; aa.batch = p->batch; aa.Hq = p->n_q_heads; aa.Hkv = p->n_kv_heads;
   aa.G = G; aa.w = p->window; aa.B = p->budget; aa.max_len = max_cache_len; aa.W32 = 0;
   aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = logit_scale(p) * cd::kLog2e;
+  aa.cal_logit = nullptr; aa.zstride = 0;
   aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
   aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
-  hipLaunchKernelGGL((cd::attend_partial_kernel<T, D>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0, st, aa);
+  hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0,
+                     st, aa);
   if ((rc = launch_status("attend_partial(decode)"))) return rc;
   cd::FinalArgs fa{};
   fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = cache_offsets; fa.row_len = cache_lens;

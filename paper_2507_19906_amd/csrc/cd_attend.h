@@ -27,6 +27,8 @@ struct AttendArgs {
   int batch, Hq, Hkv, G, w, B, max_len, W32, rows_per_split, NS;
   int q_is_window;            // 1: q points at q_win and the last window row is the query
   float sl2;                  // scale * log2(e)
+  const float* cal_logit;     // calibration mode: [batch*Hq][zstride] precomputed log2-unit logits, or NULL
+  int zstride;
   float* part_o;              // [batch][Hq][NS][D]
   float2* part_ml;            // [batch][Hq][NS]  (max in log2 units, sum)
 };
@@ -81,12 +83,23 @@ struct AttendWave {
   // Process the 32-row tiles row_first, row_first + row_step, ... below row_end.  `rows` is
   // the number of valid rows of the head (loads are clamped to it); `bm` (optional) marks rows
   // to skip, one bit per row, word index = row / 32.
-  template <bool kPrefetch = true>
+  // Logits of rows row0 + 16 g2 + 4 c + r (r = 0..3) of head i, precomputed by the scoring pass.
+  __device__ __forceinline__ static void load_z(const float* zhead, int row0, int c, bool valid, f32x4 (&z)[2]) {
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2)
+      z[g2] = valid ? *reinterpret_cast<const f32x4*>(zhead + row0 + 16 * g2 + 4 * c) : f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // kLogits: the logits come from `zhead` (this lane's head, log2 units) instead of K Q^T.
+  template <bool kPrefetch = true, bool kLogits = false>
   __device__ __forceinline__ void run(const T* kbase, const T* vbase, const uint32_t* bm, int rows, int row_first,
-                                      int row_end, int row_step, float sl2, int i, int c) {
+                                      int row_end, int row_step, float sl2, int i, int c,
+                                      const float* zhead = nullptr, bool zvalid = false) {
     if (row_first >= row_end) return;
     u32x4 kf[2][NK];
-    load_k(kbase, row_first, rows, i, c, kf);
+    f32x4 zf[2];
+    if constexpr (kLogits) load_z(zhead, row_first, c, zvalid, zf);
+    else load_k(kbase, row_first, rows, i, c, kf);
     for (int row0 = row_first; row0 < row_end; row0 += row_step) {
       // V of this tile first, then K of the next tile: both in flight during the QK product
       u32x4 vf[8];
@@ -99,15 +112,21 @@ struct AttendWave {
         }
       }
       f32x4 acc_s[2];
-#pragma unroll
-      for (int g2 = 0; g2 < 2; ++g2) {
-        acc_s[g2] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc_s[g2], kf[g2][kk], qf[kk]);
-      }
       const int next0 = row0 + row_step;
-      if constexpr (kPrefetch) {
-        if (next0 < row_end) load_k(kbase, next0, rows, i, c, kf);
+      if constexpr (kLogits) {
+        acc_s[0] = zf[0];
+        acc_s[1] = zf[1];
+        if (next0 < row_end) load_z(zhead, next0, c, zvalid, zf);
+      } else {
+#pragma unroll
+        for (int g2 = 0; g2 < 2; ++g2) {
+          acc_s[g2] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc_s[g2], kf[g2][kk], qf[kk]);
+        }
+        if constexpr (kPrefetch) {
+          if (next0 < row_end) load_k(kbase, next0, rows, i, c, kf);
+        }
       }
       // ---- softmax weights: x[g2][r] <-> row row0 + 16 g2 + 4 c + r, head i -------------
       const uint32_t skip = bm ? bm[row0 >> 5] : 0u;
@@ -119,7 +138,7 @@ struct AttendWave {
         for (int r = 0; r < 4; ++r) {
           const int rr = 16 * g2 + 4 * c + r;
           const bool live = (row0 + rr < row_end) && !((skip >> rr) & 1u);
-          x[g2][r] = live ? acc_s[g2][r] * sl2 : -INFINITY;
+          x[g2][r] = live ? (kLogits ? acc_s[g2][r] : acc_s[g2][r] * sl2) : -INFINITY;
           tm = fmaxf(tm, x[g2][r]);
         }
       tm = col4_max(tm);
@@ -171,7 +190,7 @@ struct AttendWave {
           }
         }
       }
-      if constexpr (!kPrefetch) {
+      if constexpr (!kPrefetch && !kLogits) {
         if (next0 < row_end) load_k(kbase, next0, rows, i, c, kf);
       }
     }
@@ -196,7 +215,8 @@ struct AttendWave {
   }
 };
 
-template <typename T, int D>
+// kLogits: calibration mode with the logits precomputed by the scoring pass (K is not read).
+template <typename T, int D, bool kLogits>
 __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
   const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   int rows, head_stride, off0;
@@ -219,7 +239,14 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
     else qp += static_cast<int64_t>(b * a.Hq + h) * D;
     w.init(qp, i < a.G, c);
   }
-  w.run(kbase, vbase, bm, rows, row_begin + wv * kTileRows, row_end, kAttWaves * kTileRows, a.sl2, i, c);
+  if constexpr (kLogits) {
+    // padding rows of the last tile hold whatever the workspace held: they are masked before use
+    const float* zhead = a.cal_logit + static_cast<int64_t>(b * a.Hq + g * a.G + i) * a.zstride;
+    w.template run<true, true>(kbase, vbase, bm, rows, row_begin + wv * kTileRows, row_end, kAttWaves * kTileRows,
+                               a.sl2, i, c, zhead, i < a.G);
+  } else {
+    w.run(kbase, vbase, bm, rows, row_begin + wv * kTileRows, row_end, kAttWaves * kTileRows, a.sl2, i, c);
+  }
 
   // ---- merge the 4 waves through LDS and write this split's partial ------------------------
   __shared__ float s_o[kAttWaves][16 * D];

@@ -16,6 +16,10 @@ namespace cd {
 
 constexpr int kRowBlock = 128;     // query rows per workgroup (8 MFMA tiles of 16)
 constexpr int kRowTiles = 8;
+#ifndef CD_VOTES_WAVES
+#define CD_VOTES_WAVES 4          // waves per SIMD the vote kernel is compiled for (bf16)
+#endif
+constexpr int kMaxCalHeads = 8;    // largest GQA group whose calibration logits the vote pass exports
 constexpr int kMinChunkKeys = 256; // keys per workgroup in the scoring passes: a multiple of this
 
 struct ScoreArgs {
@@ -30,6 +34,8 @@ struct ScoreArgs {
   float* row_lse;       // [batch*Hkv*NRB*128] log2-domain row log-sum-exp
   float* vote;          // [NRB][total_tokens*Hkv]
   float* score;         // [total_tokens*Hkv]
+  float* cal_logit;     // [batch*Hq][zstride] log2-unit logits of the last window query, or NULL
+  int zstride;
 };
 
 // Length of sequence b as the kernels use it: 0 when the offsets break the host-side contract
@@ -266,7 +272,7 @@ __global__ __launch_bounds__(256) void rowstats_merge_kernel(ScoreArgs a) {
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void score_votes_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(256, sizeof(T) == 2 ? CD_VOTES_WAVES : 2) void score_votes_kernel(ScoreArgs a) {
   using KS = KeyStream<T, D>;
   constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys;
   const int chunk = blockIdx.x;
@@ -291,6 +297,7 @@ __global__ __launch_bounds__(256) void score_votes_kernel(ScoreArgs a) {
 
   __shared__ __attribute__((aligned(16))) char s_k[2][KS::kStageBytes];
   __shared__ float s_v[2][4][SK];                  // per-wave partial votes of a stage
+  __shared__ float s_z[2][kMaxCalHeads][SK];       // exported calibration logits of a stage, per head
   WaveQueries<T, D> wq;
   wq.load(a, b, g, rb, wv, P, i, c);
   // S tiles are rows x keys here: lane (i, c) holds key i and rows 16 rt + 4 c + r of the wave
@@ -301,13 +308,28 @@ __global__ __launch_bounds__(256) void score_votes_kernel(ScoreArgs a) {
     for (int r = 0; r < 4; ++r)
       lse[rt][r] = a.row_lse[static_cast<int64_t>(y) * kRowBlock + wv * 32 + rt * 16 + 4 * c + r];   // padding rows: +inf
 
+  // Rows that are the last window query of a head (the default calibration query, Alg. 1
+  // step 5) also export their logits, so that the calibration pass need not read K again.
+  // (the export needs w % 4 == 0, so that such a row is always slot r = 3 of its lane)
+  int cal_head[2];                      // head in group whose last window row is this lane's (rt, r = 3), or -1
+  bool cal_lane = false;
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int rho = rb * kRowBlock + wv * 32 + rt * 16 + 4 * c + 3;
+    const bool is_cal = a.cal_logit != nullptr && rho < a.R && (rho % a.w) == a.w - 1;
+    cal_head[rt] = is_cal ? rho / a.w : -1;
+    cal_lane |= is_cal;
+  }
+  const bool cal_wave = __any(cal_lane);
+  float* zrow = a.cal_logit ? a.cal_logit + static_cast<int64_t>(b * a.Hq + g * a.G) * a.zstride : nullptr;
+
   typename KS::Regs r0, r1;
   KS::load(r0, kbase, key_base, n);
   if (nstages > 1) KS::load(r1, kbase, key_base + SK, n);
   KS::store(r0, s_k[0]);
   __syncthreads();
 
-  auto compute = [&](const char* lds, float (*sv)[SK]) {
+  auto compute = [&](const char* lds, float (*sv)[SK], float (*sz)[SK]) {
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
       u32x4 kf[NK];
@@ -321,31 +343,40 @@ __global__ __launch_bounds__(256) void score_votes_kernel(ScoreArgs a) {
         for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc, wq.qf[rt][kk], kf[kk]);
 #pragma unroll
         for (int r = 0; r < 4; ++r) v += fast_exp2(fmaf(acc[r], a.sl2, -lse[rt][r]));
+        if (cal_wave && cal_head[rt] >= 0) sz[cal_head[rt]][16 * kt + i] = acc[3] * a.sl2;
       }
       v = col4_sum(v);                             // over the 4 row groups c: fixed tree
       if (c == 0) sv[wv][16 * kt + i] = v;
     }
   };
-  // after the stage barrier: add the four waves' partial votes in wave order and store
-  auto flush = [&](const float (*sv)[SK], int key0) {
+  // after the stage barrier: add the four waves' partial votes in wave order and store; the
+  // second wave stores the exported logits, one coalesced row per head
+  auto flush = [&](const float (*sv)[SK], const float (*sz)[SK], int key0) {
     if (threadIdx.x < SK) {
       const int key = key0 + threadIdx.x;
       if (key < P) vote[key] = ((sv[0][threadIdx.x] + sv[1][threadIdx.x]) + sv[2][threadIdx.x]) + sv[3][threadIdx.x];
+    } else if (zrow != nullptr && threadIdx.x >= 64 && threadIdx.x < 64 + SK) {
+      const int t = threadIdx.x - 64;
+      const int key = key0 + t;
+      if (key < P)
+        for (int hh = 0; hh < a.G; ++hh)
+          if ((hh * a.w + a.w - 1) / kRowBlock == rb)      // heads whose last window row is in this row block
+            zrow[static_cast<int64_t>(hh) * a.zstride + key] = sz[hh][t];
     }
   };
 
   for (int s = 0; s < nstages; s += 2) {
     if (s + 2 < nstages) KS::load(r0, kbase, key_base + (s + 2) * SK, n);
-    compute(s_k[0], s_v[0]);
+    compute(s_k[0], s_v[0], s_z[0]);
     if (s + 1 < nstages) KS::store(r1, s_k[1]);
     __syncthreads();
-    flush(s_v[0], key_base + s * SK);
+    flush(s_v[0], s_z[0], key_base + s * SK);
     if (s + 1 >= nstages) break;
     if (s + 3 < nstages) KS::load(r1, kbase, key_base + (s + 3) * SK, n);
-    compute(s_k[1], s_v[1]);
+    compute(s_k[1], s_v[1], s_z[1]);
     if (s + 2 < nstages) KS::store(r0, s_k[0]);
     __syncthreads();
-    flush(s_v[1], key_base + (s + 1) * SK);
+    flush(s_v[1], s_z[1], key_base + (s + 1) * SK);
   }
 }
 
