@@ -28,6 +28,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per decode launch measured with rocprofv3 counters on the default workload
+# (profiles/decode_fused_cfg3_B512_pmc_hbm_bytes.md): FETCH_SIZE 33490 KiB x 2.0 + WRITE_SIZE 272 KiB
+DECODE_TRAFFIC_BYTES_PMC = int(33490 * 1024 * 2.0 + 272 * 1024)
 
 
 def decode_bytes(wl, cache_len: int) -> int:
@@ -91,6 +94,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--rotate", type=int, default=0, help="cache copies cycled by decode (0 = enough for 512 MiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the additional budget-2048 decode measurement")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy 4 times (calibrates the profiler's HBM byte counters)")
     args = ap.parse_args()
@@ -175,7 +179,40 @@ def main():
     torch.cuda.synchronize()
     dec_res = e0.elapsed_time(e1) / T
 
+    # decode at budget 2048 (256 MiB per call): the same kernel where a launch carries enough
+    # bytes for the fixed in-kernel latency (~4 us) to stop dominating
+    big = None
+    if args.budget == 512 and args.layers == 32 and not args.no_extra:
+        wl2 = synth.config(3, layers=args.layers, budget=2048, decode_steps=1)
+        p2 = cd.make_params(dtype=wl2.dtype, batch=wl2.batch, n_q_heads=wl2.n_q_heads, n_kv_heads=wl2.n_kv_heads,
+                            head_dim=wl2.head_dim, window=wl2.window, budget=wl2.budget, pool_kernel=wl2.pool_kernel,
+                            theta1=wl2.theta1, theta2=wl2.theta2)
+        b2 = cd.CompressBuffers(p2, wl2.seq_lens, dev)
+        b2.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=stream)
+        kc2 = [b2.k_c, b2.k_c.clone(), b2.k_c.clone()]
+        vc2 = [b2.v_c, b2.v_c.clone(), b2.v_c.clone()]
+        def call2(t):
+            cd.calidrop_decode(p2, x["q_dec"][t % T], kc2[t % 3], vc2[t % 3], b2.cache_offsets, b2.cache_lens,
+                               b2.max_cache_len, b2.c_q, b2.c_out, b2.c_lse, b2.out, b2.a_lse, b2.flags,
+                               b2.ws_decode, stream)
+        for t in range(6):
+            call2(t)
+        e0, e1 = ev(), ev()
+        e0.record(stream)
+        for t in range(60):
+            call2(t)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us2 = e0.elapsed_time(e1) * 1e3 / 60
+        big = {"budget": 2048, "bytes_per_call": decode_bytes(wl2, 2048), "us_per_call": us2,
+               "GBps": decode_bytes(wl2, 2048) / us2 / 1e3,
+               "pct_hbm_peak": 100.0 * decode_bytes(wl2, 2048) / us2 / 1e3 / HBM_PEAK_GBPS}
+        del b2, kc2, vc2
+
     gbps = dbytes / (dec * 1e-3) / 1e9
+    # window scoring (the two MFMA passes of compress): 2*Hq*w*n*D flop per layer and pass
+    score_flop = 2.0 * wl.n_q_heads * wl.window * wl.seq_lens[0] * wl.head_dim * wl.batch
+    default_cfg = args.budget == 512 and args.layers == 32
     out = {
         "metric": "decode attn GB/s (% HBM peak) + compress us/layer at 32k ctx, budget 512",
         "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -187,14 +224,21 @@ def main():
                    "cache_copies_rotated": rotate},
         "pct_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
         "decode_us_per_call": dec * 1e3,
+        "decode_bytes_per_call": dbytes,
         "decode_GBps_cache_resident": dbytes / (dec_res * 1e-3) / 1e9,
+        "decode_at_budget_2048": big,
         "compress_us_per_layer": comp * 1e3 / wl.batch,
         "compress_GBps_vs_read_kv_once": compress_bytes(wl) / (comp * 1e-3) / 1e9,
-        "roofline": {"bound": "hbm", "kernel": "attend_partial_kernel<bf16,128> (decode)",
+        "compress_pct_of_16.8us_bound": 100.0 * (compress_bytes(wl) / wl.batch / (HBM_PEAK_GBPS * 1e3)) / (comp * 1e3 / wl.batch),
+        "scoring_algorithmic_TFLOP": score_flop / 1e12,
+        "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel<bf16,128,8>",
                      "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
-                     "traffic": None,
-                     "note": "duration = mean of HIP-event time over all decode calls of the timed region / calls "
-                             "(includes the small finalize kernel and launch gaps)"},
+                     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of this kernel on this workload,
+                     # scaled by the counters' readings for a plain 1 GiB copy (x2.0 / x1.0)
+                     "traffic": DECODE_TRAFFIC_BYTES_PMC if default_cfg else None,
+                     "duration_us": dec * 1e3,
+                     "note": "duration = HIP-event time over all decode calls of the timed region / calls; "
+                             "one kernel per call"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, kv_heads=wl.n_kv_heads, decode_steps=64)

@@ -15,7 +15,8 @@
  *   - All data pointers are DEVICE pointers owned by the caller (for example a torch
  *     tensor's data_ptr()); they must stay alive until `stream` has executed the enqueued
  *     work.  `p` and the returned strings are HOST memory.  The library keeps no pointer
- *     after a call returns and holds no state except a thread-local error string.
+ *     after a call returns; its only state is a thread-local error string and the
+ *     process-wide inspection switch below.
  *   - Calls validate their arguments on the host first (no HIP call is made before
  *     validation passes), then enqueue kernels on `stream` (a hipStream_t; NULL = default
  *     stream) and return without synchronising.  They never allocate or free device memory.

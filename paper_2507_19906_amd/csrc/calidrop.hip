@@ -174,12 +174,7 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   sa.vote = reinterpret_cast<float*>(ws + L.vote);
   sa.score = reinterpret_cast<float*>(ws + L.score);
   // default calibration query = last window query: the vote pass exports its logits
-#ifdef CD_NO_CAL_EXPORT
-  const bool no_export = true;
-#else
-  const bool no_export = false;
-#endif
-  sa.cal_logit = (no_export || q_cal || G > cd::kMaxCalHeads || p->window % 4 != 0)
+  sa.cal_logit = (q_cal || G > cd::kMaxCalHeads || p->window % 4 != 0)
                      ? nullptr : reinterpret_cast<float*>(ws + L.cal_logit);
   sa.zstride = L.zstride;
 
@@ -204,9 +199,6 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   se.vote = sa.vote; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
   se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
   se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
-#ifdef CD_SELECT_TIMING
-  se.dbg = reinterpret_cast<long long*>(ws + L.rowpart);
-#endif
   const int max_prefix = max_seq_len - p->window;
   se.write_scores = g_inspection.load(std::memory_order_relaxed);
   if (max_prefix <= cd::kSelMaxLdsKeys && p->budget <= cd::kSelMaxLdsKeys && p->pool_kernel <= cd::kSelMaxPool) {
@@ -225,7 +217,7 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   } else {
     hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
     if ((rc = launch_status("pool_scores"))) return rc;
-    hipLaunchKernelGGL(cd::select_gather_kernel<false>, dim3(bg), dim3(cd::kSelThreads), 0, st, se);
+    hipLaunchKernelGGL(cd::select_gather_kernel, dim3(bg), dim3(cd::kSelThreads), 0, st, se);
   }
   if ((rc = launch_status("select_gather"))) return rc;
 

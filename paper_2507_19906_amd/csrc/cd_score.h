@@ -16,9 +16,7 @@ namespace cd {
 
 constexpr int kRowBlock = 128;     // query rows per workgroup (8 MFMA tiles of 16)
 constexpr int kRowTiles = 8;
-#ifndef CD_VOTES_WAVES
-#define CD_VOTES_WAVES 4          // waves per SIMD the vote kernel is compiled for (bf16)
-#endif
+#define CD_VOTES_WAVES 4          // waves per SIMD the bf16 vote kernel is compiled for
 constexpr int kMaxCalHeads = 8;    // largest GQA group whose calibration logits the vote pass exports
 constexpr int kMinChunkKeys = 256; // keys per workgroup in the scoring passes: a multiple of this
 

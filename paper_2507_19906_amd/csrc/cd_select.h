@@ -8,9 +8,9 @@
 // rule - and emits positions in ascending order.  Integer work only: bit-exact and
 // deterministic.
 //
-// Two variants of the key storage: when the P pooled scores of a head fit in LDS the kernel
-// pools the votes itself and keeps the keys in LDS for all five sweeps; otherwise the keys are
-// read from the pooled-score buffer that pool_scores_kernel wrote.
+// Two variants: select_gather_lds_kernel (prefix up to 32768 positions: pools the votes itself,
+// keys in registers) and select_gather_kernel (longer prefixes: keys read from the pooled-score
+// buffer that pool_scores_kernel wrote).
 #pragma once
 #include "cd_common.h"
 #include "cd_score.h"
@@ -35,20 +35,11 @@ struct SelectArgs {
   int32_t* cache_lens;     // [batch]
   uint32_t* bitmap;        // [batch*Hkv][W32]: bit set = position is NOT evicted
   const void* k; const void* v; void* k_c; void* v_c;
-#ifdef CD_SELECT_TIMING
-  long long* dbg;          // tuning builds only: phase timestamps of workgroup 0
-#endif
 };
 
-#ifdef CD_SELECT_TIMING
-#define CD_STAMP(slot) do { __syncthreads(); if (blockIdx.x == 0 && threadIdx.x == 0) a.dbg[slot] = wall_clock64(); } while (0)
-#else
-#define CD_STAMP(slot) do { } while (0)
-#endif
-
-template <bool kLdsKeys>
+// Variant for prefixes too long for LDS: the pooled scores are read from the buffer that
+// pool_scores_kernel wrote, position j of a sweep handled by thread j mod 1024.
 __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a) {
-  extern __shared__ uint32_t s_keys[];          // kLdsKeys: pooled scores of this head
   const int bg = blockIdx.x;
   const int g = bg % a.Hkv;
   const int b = bg / a.Hkv;
@@ -64,69 +55,13 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
   __shared__ uint32_t s_prefix, s_remaining;
   __shared__ uint32_t wave_cnt[kSelThreads / 64];
 
-  CD_STAMP(0);
   if (n <= a.B) {                       // nothing to evict: keep every position
     for (int r = tid; r < a.B; r += kSelThreads) idx[r] = (r < n) ? r : -1;
   } else {
     const int P = n - a.w;
     const int k_sel = a.B - a.w;
     const uint32_t* gkey = reinterpret_cast<const uint32_t*>(a.score) + head_tok;
-    if constexpr (kLdsKeys) {
-      // Stage the votes of the head in LDS (row-block partials added first, fixed order), then
-      // score[j] = (1/k) * sum_{d=-k/2..k/2} vote[j+d] with zeros outside [0, P), summed left
-      // to right at every position; scores go to registers first because they overwrite the
-      // votes in place.
-      float* s_vote = reinterpret_cast<float*>(s_keys);
-      const int64_t plane = a.total_tokens * a.Hkv;
-      const float* vsrc = a.vote + head_tok;
-      constexpr int kPerThread = kSelMaxLdsKeys / kSelThreads;
-      float sc[kPerThread];
-#pragma unroll
-      for (int u = 0; u < kPerThread; ++u) {          // all loads of a thread in flight together
-        const int j = tid + u * kSelThreads;
-        float val = 0.f;
-        if (j < P) {
-          val = vsrc[j];
-          for (int rb = 1; rb < a.NRB; ++rb) val += vsrc[rb * plane + j];
-        }
-        sc[u] = val;
-      }
-#pragma unroll
-      for (int u = 0; u < kPerThread; ++u) {
-        const int j = tid + u * kSelThreads;
-        if (j < P) s_vote[j] = sc[u];
-      }
-      __syncthreads();
-      const int half = a.pool_k / 2;
-      const float kf = static_cast<float>(a.pool_k);
-#pragma unroll
-      for (int u = 0; u < kPerThread; ++u) {
-        const int j = tid + u * kSelThreads;
-        float sum = 0.f;
-        if (j < P) {
-          for (int d = -half; d <= half; ++d) {
-            const int jj = j + d;
-            sum += (jj >= 0 && jj < P) ? s_vote[jj] : 0.f;
-          }
-        }
-        sc[u] = sum / kf;
-      }
-      __syncthreads();
-#pragma unroll
-      for (int u = 0; u < kPerThread; ++u) {
-        const int j = tid + u * kSelThreads;
-        if (j < P) {
-          s_keys[j] = __builtin_bit_cast(uint32_t, sc[u]);
-          a.score[head_tok + j] = sc[u];
-        }
-      }
-      __syncthreads();
-    }
-    CD_STAMP(1);
-    auto key_at = [&](int j) -> uint32_t {
-      if constexpr (kLdsKeys) return s_keys[j];
-      else return gkey[j];
-    };
+    auto key_at = [&](int j) -> uint32_t { return gkey[j]; };
 
     // ---- radix select: 4 digits of 8 bits, most significant first -----------------------
     uint32_t prefix = 0;            // bits decided so far (the high bits of the threshold)
@@ -178,7 +113,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
       remaining = s_remaining;
       __syncthreads();
     }
-    CD_STAMP(2);
     const uint32_t thr = prefix;          // bit pattern of the k_sel-th largest score
     const uint32_t need_eq = remaining;   // how many entries equal to thr are kept (>= 1)
 
@@ -218,7 +152,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
       __syncthreads();
     }
     for (int r = tid; r < a.w; r += kSelThreads) idx[k_sel + r] = P + r;   // the window is always kept
-    CD_STAMP(3);
   }
 
   // ---- gather: K_c[g][r] = K[g][idx[g][r]], V likewise; 16 bytes per thread per step -------
@@ -257,7 +190,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
       if (t < total) { st16(kdst + dof, kk[u]); st16(vdst + dof, vv[u]); }
     }
   }
-  CD_STAMP(4);
 }
 
 // LDS variant for prefixes of up to kSelMaxLdsKeys positions.  Thread t owns positions
@@ -286,7 +218,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
   constexpr int PER = kSelPerThread;
   auto pad = [](int j) { return j + (j >> 5); };
 
-  CD_STAMP(0);
   if (n <= a.B) {                       // nothing to evict: keep every position
     for (int r = tid; r < a.B; r += kSelThreads) {
       idx[r] = (r < n) ? r : -1;
@@ -358,7 +289,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
         }
       }
     }
-    CD_STAMP(1);
     // ---- radix select: 4 digits of 8 bits, most significant first ---------------------------
     uint32_t prefix = 0;            // bits decided so far (the high bits of the threshold)
     uint32_t remaining = k_sel;     // rank of the threshold among the keys matching `prefix`
@@ -408,7 +338,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
       remaining = s_remaining;
       __syncthreads();
     }
-    CD_STAMP(2);
     const uint32_t thr = prefix;          // bit pattern of the k_sel-th largest score
     const uint32_t need_eq = remaining;   // how many entries equal to thr are kept (>= 1)
 
@@ -447,7 +376,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
     }
     if (j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + tid] = word;
     for (int r = tid; r < a.w; r += kSelThreads) { idx[k_sel + r] = P + r; s_idx[k_sel + r] = P + r; }
-    CD_STAMP(3);
   }
 
   // ---- gather: K_c[g][r] = K[g][idx[g][r]], V likewise; 16 bytes per thread per copy ---------
@@ -481,7 +409,6 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
       if (t < total) { st16(kdst + dof, kk[u]); st16(vdst + dof, vv[u]); }
     }
   }
-  CD_STAMP(4);
 }
 
 }  // namespace cd
