@@ -10,6 +10,9 @@
  *   calidrop_decode    - decode side, Alg. 2: attention of the current query over
  *                        KV_compress, cosine gate against C_q, and the Eq. 1-2 merge with the
  *                        calibration state.
+ *   calidrop_recalibrate - the recomputation branch of Alg. 2 (steps 3-8) for the heads that
+ *                        calidrop_decode flagged: refresh the calibration state from KV_evict
+ *                        with the current query and calibrate the step's output.
  *
  * Conventions shared by every entry point
  *   - All data pointers are DEVICE pointers owned by the caller (for example a torch
@@ -57,8 +60,11 @@ typedef enum { CALIDROP_BF16 = 0, CALIDROP_FP32 = 1 } calidrop_dtype;
 enum {
   CALIDROP_FLAG_NONE = 0,       /* theta1 <= rho <= theta2: plain compressed attention     */
   CALIDROP_FLAG_CALIBRATED = 1, /* rho > theta2: output merged with C_out by Eq. 1         */
-  CALIDROP_FLAG_RECOMPUTE = 2   /* rho < theta1: caller should recompute the calibration
-                                   state; the output is the plain compressed attention     */
+  CALIDROP_FLAG_RECOMPUTE = 2,  /* rho < theta1: the calibration state is stale; the output is
+                                   the plain compressed attention until calidrop_recalibrate
+                                   has processed the head                                  */
+  CALIDROP_FLAG_RECOMPUTED = 3  /* set by calidrop_recalibrate: state recomputed with the
+                                   current query and the output calibrated with it         */
 };
 
 typedef struct {
@@ -172,6 +178,34 @@ int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, 
                     int32_t max_cache_len, const float* c_q, const float* c_out,
                     const float* c_lse, void* out, float* a_lse, uint8_t* flags,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * calidrop_recalibrate - the rho < theta1 branch of Alg. 2 (steps 3-8), for the heads that the
+ * preceding calidrop_decode call of the same step flagged CALIDROP_FLAG_RECOMPUTE.
+ *
+ * For every such (sequence b, query head h), with KV head g = h / G and KV_evict = the prefix
+ * rows of the prompt (positions < n_b - w) that are not listed in indices[b][g]:
+ *   c_lse[h] = log sum_{t in evict} exp(scale q_t[h].K_t),  c_out[h] = Att(q_t[h], K_evict, V_evict)
+ *   (the current query is used, as the text of Sec. 3.2 says), c_q[h] = q_t[h]           (steps 5-7)
+ *   out[h] = alpha_i out[h] + alpha_j c_out[h] with alpha_j = 1/(1+exp(a_lse[h] - c_lse[h]))  (step 8)
+ *   flags[h] = CALIDROP_FLAG_RECOMPUTED.
+ * Heads with any other flag, and their state, are left untouched.  Sequences with nothing evicted
+ * (n_b <= B) get c_q = q_t, c_lse = -inf, c_out = 0 and an unchanged output.  KV groups without a
+ * flagged head are not streamed at all.
+ *
+ * Arguments: q_t, out, a_lse, flags as passed to / written by calidrop_decode for this step (out
+ * and flags are updated in place; flags must not be NULL here); k, v, seq_offsets, total_tokens,
+ * max_seq_len and indices as in calidrop_compress (the prompt K/V must still be resident: this is
+ * where the "offloaded" evicted cache is read from); c_q, c_out, c_lse the calibration state,
+ * updated in place; workspace >= calidrop_recalibrate_workspace_bytes(p, max_seq_len) bytes,
+ * 256-byte aligned.
+ */
+size_t calidrop_recalibrate_workspace_bytes(const calidrop_params* p, int32_t max_seq_len);
+int calidrop_recalibrate(const calidrop_params* p, const void* q_t, const void* k, const void* v,
+                         const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
+                         const int32_t* indices, uint8_t* flags, const float* a_lse, void* out,
+                         float* c_q, float* c_out, float* c_lse, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /* Host string describing the last error on the calling thread ("" if none). Never NULL.      */
 const char* calidrop_last_error(void);

@@ -198,7 +198,7 @@ def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=Non
 # --------------------------------------------------------------------------------------------
 # Alg. 2 (decode side), one sequence, one step
 # --------------------------------------------------------------------------------------------
-FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE = 0, 1, 2
+FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE, FLAG_RECOMPUTED = 0, 1, 2, 3
 
 
 def cosine(a, b):
@@ -246,3 +246,39 @@ def decode(q_t, K_c, V_c, length, c_q, c_out, c_lse, theta1, theta2, scale=None)
         else:
             out[h] = o_a
     return out, a_lse, flags, rhos
+
+
+def recalibrate(q_t, K, V, idx, flags, a_lse, out, c_q, c_out, c_lse, w, scale=None):
+    """Alg. 2 steps 3-8 (the rho < theta1 branch) for the heads that `decode` flagged.
+
+    The evicted K/V are the prefix rows of the prompt tensors K, V [Hkv][n][D] that are not in
+    idx [Hkv][B] (KV_evict = KV_full minus KV_compress, frozen at prefill).  For every head with
+    flag FLAG_RECOMPUTE: C_weight and C_out are recomputed with the CURRENT query (the prose of
+    Sec. 3.2; the listing prints Q_{-1} but then sets C_q = Q_t), C_q = Q_t, and the output is
+    calibrated by Eq. 1: out = alpha_i * out + alpha_j * C_out.  `out`, `a_lse` are what decode
+    returned for this step.  Returns new (out, flags, c_q, c_out, c_lse); inputs are not modified."""
+    q_t = np.asarray(q_t, F)
+    K = np.asarray(K, F)
+    V = np.asarray(V, F)
+    Hq, D = q_t.shape
+    Hkv, n, _ = K.shape
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    out = np.array(out, F)
+    flags = np.array(flags, np.uint8)
+    c_q, c_out, c_lse = np.array(c_q, F), np.array(c_out, F), np.array(c_lse, F)
+    P = n - w
+    for h in range(Hq):
+        if flags[h] != FLAG_RECOMPUTE:
+            continue
+        g = h // G
+        keep = np.asarray(idx[g])
+        mask = np.ones(max(P, 0), bool)
+        mask[keep[(keep >= 0) & (keep < P)]] = False
+        ev = np.nonzero(mask)[0]
+        c_out[h], c_lse[h] = attention(q_t[h], K[g][ev], V[g][ev], scale)     # steps 5-6
+        c_q[h] = q_t[h]                                                       # step 7
+        out[h], _ = merge(out[h], a_lse[h], c_out[h], c_lse[h])               # step 8 (Eq. 1)
+        flags[h] = FLAG_RECOMPUTED
+    return out, flags, c_q, c_out, c_lse

@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("CALIDROP_LIB") or os.path.join(_PKG_DIR, "libcalidrop
 
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6
 BF16, FP32 = 0, 1
-FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE = 0, 1, 2
+FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE, FLAG_RECOMPUTED = 0, 1, 2, 3
 REGION_ROW_LSE, REGION_SCORE = 0, 1
 
 
@@ -87,6 +87,10 @@ def lib() -> ctypes.CDLL:
         L.calidrop_decode.restype = ctypes.c_int
         L.calidrop_decode.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz,
                                       vp]
+        L.calidrop_recalibrate_workspace_bytes.restype = sz
+        L.calidrop_recalibrate_workspace_bytes.argtypes = [pp, i32]
+        L.calidrop_recalibrate.restype = ctypes.c_int
+        L.calidrop_recalibrate.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -160,6 +164,22 @@ def calidrop_decode(p: Params, q_t, k_c, v_c, cache_offsets, cache_lens, max_cac
         _ptr(workspace), ws_bytes, _stream(stream)))
 
 
+def calidrop_recalibrate_workspace_bytes(p: Params, max_seq_len: int) -> int:
+    n = lib().calidrop_recalibrate_workspace_bytes(ctypes.byref(p), max_seq_len)
+    if n == 0:
+        raise CalidropError(EINVAL, calidrop_last_error())
+    return n
+
+
+def calidrop_recalibrate(p: Params, q_t, k, v, seq_offsets, total_tokens: int, max_seq_len: int, indices,
+                         flags, a_lse, out, c_q, c_out, c_lse, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().calidrop_recalibrate(
+        ctypes.byref(p), _ptr(q_t), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
+        _ptr(indices), _ptr(flags), _ptr(a_lse), _ptr(out), _ptr(c_q), _ptr(c_out), _ptr(c_lse),
+        _ptr(workspace), ws_bytes, _stream(stream)))
+
+
 # ---- device-memory plumbing (allocation only) ----------------------------------------------
 class CompressBuffers:
     """Output and workspace tensors for calidrop_compress / calidrop_decode, allocated with
@@ -201,6 +221,15 @@ class CompressBuffers:
         calidrop_decode(self.p, q_t, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
                         max_cache_len or self.max_cache_len, self.c_q, self.c_out, self.c_lse,
                         self.out, self.a_lse, self.flags, self.ws_decode, stream)
+
+    def recalibrate(self, q_t, k, v, seq_offsets, stream=None):
+        """Recomputation branch for the heads the last decode() flagged (updates out/flags/state)."""
+        if getattr(self, "ws_recal", None) is None:
+            self.ws_recal = torch.empty(calidrop_recalibrate_workspace_bytes(self.p, self.max_seq_len),
+                                        dtype=torch.uint8, device=self.out.device)
+        calidrop_recalibrate(self.p, q_t, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
+                             self.indices, self.flags, self.a_lse, self.out, self.c_q, self.c_out,
+                             self.c_lse, self.ws_recal, stream)
 
     def region(self, region: int) -> torch.Tensor:
         off, nbytes = calidrop_compress_workspace_region(self.p, self.total_tokens,

@@ -292,6 +292,56 @@ int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, cons
   return launch_status("attend_finalize(decode)");
 }
 
+struct RecalLayout { size_t bitmap, part_o, part_ml, total; int W32; SplitPlan sp; };
+
+RecalLayout recal_layout(const calidrop_params* p, int32_t max_seq_len) {
+  RecalLayout L{};
+  L.W32 = ceil_div(max_seq_len, 64) * 2;
+  L.sp = plan_splits(p->batch * p->n_kv_heads, max_seq_len);
+  const size_t slots = static_cast<size_t>(p->batch) * p->n_q_heads * L.sp.NS;
+  size_t off = 0;
+  L.bitmap = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.W32 * sizeof(uint32_t));
+  L.part_o = off;  off += round256(slots * p->head_dim * sizeof(float));
+  L.part_ml = off; off += round256(slots * sizeof(float2));
+  L.total = off;
+  return L;
+}
+
+template <typename T, int D>
+int recal_impl(const calidrop_params* p, const void* q_t, const void* k, const void* v, const int32_t* seq_offsets,
+               int64_t total_tokens, int32_t max_seq_len, const int32_t* indices, uint8_t* flags, const float* a_lse,
+               void* out, float* c_q, float* c_out, float* c_lse, char* ws, const RecalLayout& L, hipStream_t st) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  int rc;
+  cd::BitmapArgs ba{};
+  ba.seq_off = seq_offsets; ba.indices = indices; ba.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
+  ba.total_tokens = total_tokens; ba.batch = p->batch; ba.Hkv = p->n_kv_heads; ba.B = p->budget;
+  ba.max_seq_len = max_seq_len; ba.W32 = L.W32;
+  hipLaunchKernelGGL(cd::bitmap_from_indices_kernel, dim3(p->batch * p->n_kv_heads), dim3(256), 0, st, ba);
+  if ((rc = launch_status("bitmap_from_indices"))) return rc;
+
+  cd::AttendArgs aa{};
+  aa.q = q_t; aa.q_is_window = 0; aa.k = k; aa.v = v; aa.row_off = seq_offsets; aa.row_len = nullptr;
+  aa.bitmap = ba.bitmap; aa.total_tokens = total_tokens; aa.batch = p->batch; aa.Hq = p->n_q_heads;
+  aa.Hkv = p->n_kv_heads; aa.G = G; aa.w = p->window; aa.B = p->budget; aa.max_len = max_seq_len; aa.W32 = L.W32;
+  aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = logit_scale(p) * cd::kLog2e;
+  aa.cal_logit = nullptr; aa.zstride = 0; aa.only_flagged = flags;
+  aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
+  aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+  hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0,
+                     st, aa);
+  if ((rc = launch_status("attend_partial(recalibrate)"))) return rc;
+
+  cd::FinalArgs fa{};
+  fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = seq_offsets; fa.row_len = nullptr;
+  fa.total_tokens = total_tokens; fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G;
+  fa.w = p->window; fa.B = p->budget; fa.max_len = max_seq_len; fa.rows_per_split = L.sp.rows_per_split;
+  fa.NS = L.sp.NS; fa.calib_mode = 2; fa.q_is_window = 0; fa.q = q_t;
+  fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse; fa.out = out; fa.a_lse = const_cast<float*>(a_lse); fa.flags = flags;
+  hipLaunchKernelGGL((cd::attend_finalize_kernel<T, D>), dim3(p->n_q_heads, p->batch), dim3(D), 0, st, fa);
+  return launch_status("attend_finalize(recalibrate)");
+}
+
 }  // namespace
 
 extern "C" {
@@ -390,6 +440,45 @@ int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, 
 #define CD_DISPATCH(T, D)                                                                                      \
   return decode_impl<T, D>(p, q_t, k_c, v_c, cache_offsets, cache_lens, max_cache_len, c_q, c_out, c_lse, out, \
                            a_lse, flags, ws, L, st)
+  if (p->dtype == CALIDROP_BF16) {
+    if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
+    CD_DISPATCH(cd::bf16_t, 64);
+  }
+  if (p->head_dim == 128) CD_DISPATCH(float, 128);
+  CD_DISPATCH(float, 64);
+#undef CD_DISPATCH
+}
+
+size_t calidrop_recalibrate_workspace_bytes(const calidrop_params* p, int32_t max_seq_len) {
+  if (check_params(p) != CALIDROP_OK) return 0;
+  if (max_seq_len < 1) { fail(CALIDROP_ESHAPE, "max_seq_len must be >= 1"); return 0; }
+  return recal_layout(p, max_seq_len).total;
+}
+
+int calidrop_recalibrate(const calidrop_params* p, const void* q_t, const void* k, const void* v,
+                         const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
+                         const int32_t* indices, uint8_t* flags, const float* a_lse, void* out, float* c_q,
+                         float* c_out, float* c_lse, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_params(p))) return rc;
+  if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
+  const struct { const void* ptr; const char* name; } req[] = {
+      {q_t, "q_t"}, {k, "k"}, {v, "v"}, {seq_offsets, "seq_offsets"}, {indices, "indices"}, {flags, "flags"},
+      {a_lse, "a_lse"}, {out, "out"}, {c_q, "c_q"}, {c_out, "c_out"}, {c_lse, "c_lse"}};
+  for (const auto& r : req)
+    if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
+  for (const auto& r : req)
+    if (r.ptr != flags && !aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  const RecalLayout L = recal_layout(p, max_seq_len);
+  if (!workspace || workspace_bytes < L.total)
+    return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
+                L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+#define CD_DISPATCH(T, D)                                                                                        \
+  return recal_impl<T, D>(p, q_t, k, v, seq_offsets, total_tokens, max_seq_len, indices, flags, a_lse, out, c_q, \
+                          c_out, c_lse, ws, L, st)
   if (p->dtype == CALIDROP_BF16) {
     if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
     CD_DISPATCH(cd::bf16_t, 64);

@@ -29,6 +29,7 @@ struct AttendArgs {
   float sl2;                  // scale * log2(e)
   const float* cal_logit;     // calibration mode: [batch*Hq][zstride] precomputed log2-unit logits, or NULL
   int zstride;
+  const uint8_t* only_flagged; // optional [batch][Hq]: skip KV groups in which no head carries flag 2
   float* part_o;              // [batch][Hq][NS][D]
   float2* part_ml;            // [batch][Hq][NS]  (max in log2 units, sum)
 };
@@ -223,6 +224,11 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
   attend_geometry(a, b, rows, head_stride, off0);
   const int row_begin = split * a.rows_per_split;
   if (row_begin >= rows) return;
+  if (a.only_flagged) {
+    bool any = false;
+    for (int hh = 0; hh < a.G; ++hh) any |= a.only_flagged[b * a.Hq + g * a.G + hh] == 2;
+    if (!any) return;
+  }
   const int row_end = min(rows, row_begin + a.rows_per_split);
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int i = lane & 15, c = lane >> 4;
@@ -281,7 +287,7 @@ struct FinalArgs {
   const void* q;                 // query tensor (see AttendArgs)
   // calibration mode outputs / decode mode inputs
   float* c_q; float* c_out; float* c_lse;
-  // decode outputs
+  // decode outputs (recalibration mode, calib_mode = 2: out, a_lse and flags are inputs too)
   void* out; float* a_lse; uint8_t* flags;
 };
 
@@ -306,6 +312,7 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
   const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const int g = h / a.G;
   __shared__ float red[4];
+  if (a.calib_mode == 2 && a.flags[b * a.Hq + h] != 2) return;      // only heads flagged for recomputation
   int rows;
   if (a.calib_mode) {
     int off0;
@@ -338,6 +345,15 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
   if (a.calib_mode) {
     a.c_q[hd * D + d] = qd;
     a.c_out[hd * D + d] = o_n;
+    if (a.calib_mode == 2) {
+      // Alg. 2 steps 7-8: the state now belongs to the current query; calibrate this step's output
+      const float a_lse = a.a_lse[hd];
+      const float aj = any ? 1.f / (1.f + __expf(a_lse - lse)) : 0.f;
+      const float o_a = load_elem<T>(static_cast<const T*>(a.out), hd * D + d);
+      store_elem<T>(static_cast<T*>(a.out), hd * D + d, (1.f - aj) * o_a + aj * o_n);
+      __syncthreads();                 // every thread has read the flag before it changes
+      if (d == 0) a.flags[hd] = 3;
+    }
     if (d == 0) a.c_lse[hd] = lse;
     return;
   }
@@ -363,6 +379,30 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
   if (d == 0) {
     if (a.a_lse) a.a_lse[hd] = lse;
     if (a.flags) a.flags[hd] = flag;
+  }
+}
+
+struct BitmapArgs {
+  const int32_t* seq_off; const int32_t* indices; uint32_t* bitmap;
+  int64_t total_tokens;
+  int batch, Hkv, B, max_seq_len, W32;
+};
+
+// Rebuild the not-evicted bitmap of every (sequence, KV head) from the retained index list.
+__global__ __launch_bounds__(256) void bitmap_from_indices_kernel(BitmapArgs a) {
+  const int bg = blockIdx.x;
+  const int b = bg / a.Hkv;
+  int off0;
+  const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
+  uint32_t* bm = a.bitmap + static_cast<int64_t>(bg) * a.W32;
+  const int words = (n + 31) / 32;
+  for (int wd = threadIdx.x; wd < words; wd += 256) bm[wd] = 0u;
+  __threadfence();
+  __syncthreads();
+  const int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
+  for (int r = threadIdx.x; r < a.B; r += 256) {
+    const int pos = idx[r];
+    if (pos >= 0 && pos < n) atomicOr(&bm[pos >> 5], 1u << (pos & 31));
   }
 }
 

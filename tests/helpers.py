@@ -172,3 +172,41 @@ def check_decode_step(wl, bufs, q_t, b, heads=None, theta=None, report=None, len
     assert err <= TOL_OUT[dt], f"decode out max-abs error {err}"
     assert err_l <= TOL_LSE[dt], f"a_lse max-abs error {err_l}"
     return report
+
+
+def check_recalibrate(wl, x, bufs, q_t, b, before, heads=None, report=None):
+    """The recomputation branch just executed on the GPU (bufs updated in place) vs the oracle's
+    Alg. 2 steps 3-8 applied to the state `before` = dict(out, a_lse, flags, c_q, c_out, c_lse)
+    that the GPU held after decode (all widened to fp64)."""
+    report = {} if report is None else report
+    dt = wl.dtype
+    G = wl.group
+    heads = list(range(wl.n_kv_heads)) if heads is None else list(heads)
+    qh = [g * G + j for g in heads for j in range(G)]
+    K = to64(synth.seq_view(x["k"], wl, b))[heads]
+    V = to64(synth.seq_view(x["v"], wl, b))[heads]
+    idx = bufs.indices[b].cpu().numpy()[heads]
+    out, flags, c_q, c_out, c_lse = ref.recalibrate(
+        to64(q_t[b])[qh], K, V, idx, before["flags"][b][qh], before["a_lse"][b][qh], before["out"][b][qh],
+        before["c_q"][b][qh], before["c_out"][b][qh], before["c_lse"][b][qh], wl.window)
+    g_flags = bufs.flags[b].cpu().numpy()[qh]
+    assert np.array_equal(g_flags, flags), (g_flags, flags)
+    g_out, g_cq = to64(bufs.out[b])[qh], to64(bufs.c_q[b])[qh]
+    g_co, g_cl = to64(bufs.c_out[b])[qh], to64(bufs.c_lse[b])[qh]
+    assert np.array_equal(g_cq, c_q)
+    fin = np.isfinite(c_lse)
+    assert np.array_equal(np.isfinite(g_cl), fin)
+    e_out, e_co = np.abs(g_out - out).max(), np.abs(g_co - c_out).max()
+    e_cl = np.abs(g_cl - c_lse)[fin].max() if fin.any() else 0.0
+    report["recal_out_err"] = max(report.get("recal_out_err", 0), e_out)
+    report["recal_c_out_err"] = max(report.get("recal_c_out_err", 0), e_co)
+    report["recal_c_lse_err"] = max(report.get("recal_c_lse_err", 0), e_cl)
+    report["recal_heads"] = report.get("recal_heads", 0) + int((flags == ref.FLAG_RECOMPUTED).sum())
+    assert e_out <= TOL_OUT[dt] and e_co <= TOL_OUT[dt] and e_cl <= TOL_LSE[dt], (e_out, e_co, e_cl)
+    return report
+
+
+def snapshot_state(bufs):
+    """fp64 host copies of everything calidrop_recalibrate reads or updates."""
+    return dict(out=to64(bufs.out), a_lse=to64(bufs.a_lse), flags=bufs.flags.cpu().numpy().copy(),
+                c_q=to64(bufs.c_q), c_out=to64(bufs.c_out), c_lse=to64(bufs.c_lse))

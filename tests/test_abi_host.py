@@ -25,7 +25,7 @@ def test_header_symbols_are_exported():
     assert {"calidrop_compress", "calidrop_decode", "calidrop_last_error",
             "calidrop_compress_workspace_bytes", "calidrop_decode_workspace_bytes",
             "calidrop_compress_workspace_region", "calidrop_version",
-            "calidrop_set_inspection"} <= names
+            "calidrop_set_inspection", "calidrop_recalibrate", "calidrop_recalibrate_workspace_bytes"} <= names
     L = cd.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -111,3 +111,15 @@ def test_bad_struct_size_null_align_workspace():
                              needd, None) == cd.EINVAL
     with pytest.raises(cd.CalidropError):
         cd.calidrop_compress_workspace_bytes(good(head_dim=100), 16384, 8192)
+    # recalibrate
+    needr = cd.calidrop_recalibrate_workspace_bytes(p, 8192)
+    assert needr > 0 and needr % 256 == 0
+    args = [A, A, A, A, 16384, 8192, A, A, A, A, A, A, A]
+    assert L.calidrop_recalibrate(ctypes.byref(p), *args, A, needr - 1, None) == cd.EWORKSPACE
+    args[7] = None                                          # flags is required here
+    assert L.calidrop_recalibrate(ctypes.byref(p), *args, A, needr, None) == cd.EINVAL
+    assert "flags is NULL" in cd.calidrop_last_error()
+    args[7] = A; args[1] = A + 4
+    assert L.calidrop_recalibrate(ctypes.byref(p), *args, A, needr, None) == cd.EALIGN
+    assert L.calidrop_recalibrate(ctypes.byref(good(head_dim=96)), A, A, A, A, 16384, 8192, A, A, A, A, A, A, A, A,
+                                  needr, None) == cd.EUNSUPPORTED

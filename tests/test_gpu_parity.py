@@ -214,3 +214,58 @@ def test_determinism_bitwise():
     a.decode(x["q_dec"][0]); b.decode(x["q_dec"][0])
     torch.cuda.synchronize()
     assert torch.equal(a.out, b.out) and torch.equal(a.a_lse, b.a_lse)
+
+
+@pytest.mark.parametrize("wl", [
+    synth.config(1),
+    small("bf16", 8, 2, 128, [900, 40, 2100], 16, 128, 5, T=10, name="recal_varlen_bf16"),
+    small("bf16", 16, 2, 64, [1200], 32, 200, 7, T=6, name="recal_g8_d64"),
+], ids=lambda w: w.name)
+def test_full_decode_loop_with_recomputation(wl):
+    # Alg. 2 end to end: decode, then the recomputation branch for the heads it flagged, state
+    # carried across steps on the GPU; every step is checked against the oracle on the same state
+    x = to_dev(synth.make_inputs(wl, 31))
+    bufs = H.gpu_compress(wl, x)
+    rep = {}
+    for t in range(wl.decode_steps):
+        q_t = x["q_dec"][t]
+        bufs.decode(q_t)
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_decode_step(wl, bufs, q_t, b, report=rep)
+        before = H.snapshot_state(bufs)
+        bufs.recalibrate(q_t, x["k"], x["v"], x["seq_offsets"])
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
+        assert not torch.any(bufs.flags == cd.FLAG_RECOMPUTE)
+    flags = np.bincount(rep.pop("flags"), minlength=4)
+    print(wl.name, rep, flags.tolist(), flush=True)
+    assert rep["recal_heads"] > 0 and flags[1] > 0        # both branches were exercised
+
+
+def test_recomputation_yields_exact_full_attention():
+    # after recomputation with the current query, the calibrated output is the attention over
+    # the whole prompt (Eq. 1 with the true query on both parts)
+    wl = small("fp32", 8, 2, 64, [1500], 16, 80, 5, T=1, name="recal_exact")
+    x = to_dev(synth.make_inputs(wl, 12))
+    bufs = H.gpu_compress(wl, x)
+    q_t = -x["q_win"][:, :, -1].contiguous()                 # rho = -1: every head is flagged
+    bufs.decode(q_t)
+    torch.cuda.synchronize()
+    assert torch.all(bufs.flags == cd.FLAG_RECOMPUTE)
+    bufs.recalibrate(q_t, x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    assert torch.all(bufs.flags == cd.FLAG_RECOMPUTED)
+    K = H.to64(synth.seq_view(x["k"], wl, 0)); V = H.to64(synth.seq_view(x["v"], wl, 0))
+    q = H.to64(q_t[0])
+    for h in range(8):
+        full, _ = ref.attention(q[h], K[h // 4], V[h // 4], 64 ** -0.5)
+        assert np.abs(H.to64(bufs.out[0, h]) - full).max() < 1e-4
+    # untouched when nothing is flagged: a second call is a no-op
+    snap = H.snapshot_state(bufs)
+    bufs.recalibrate(q_t, x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    after = H.snapshot_state(bufs)
+    for key in snap:
+        assert np.array_equal(snap[key], after[key]), key

@@ -374,3 +374,45 @@ def test_always_calibrate_thresholds():
     _, _, flags, _ = ref.decode(q_t, r["K_c"], r["V_c"], 16, r["c_q"], r["c_out"], r["c_lse"],
                                 -np.inf, -np.inf)
     assert np.all(flags == ref.FLAG_CALIBRATED)
+
+
+def test_recompute_branch_gives_exact_attention_and_refreshes_state():
+    # Alg. 2 steps 3-8: after recomputation with the current query the calibrated output is the
+    # exact attention over all prompt tokens (Eq. 1 with the true query on both sides)
+    q_win, K, V = rand_case(n=60, w=6, D=16)
+    r = ref.compress(q_win, K, V, 6, 18, 3)
+    q_t = -q_win[:, -1] + 0.1 * RNG.standard_normal((4, 16))          # rho ~ -1 < theta1
+    out, a_lse, flags, rho = ref.decode(q_t, r["K_c"], r["V_c"], 18, r["c_q"], r["c_out"], r["c_lse"], 0.7, 0.85)
+    assert np.all(flags == ref.FLAG_RECOMPUTE)
+    out2, flags2, c_q, c_out, c_lse = ref.recalibrate(q_t, K, V, r["idx"], flags, a_lse, out, r["c_q"], r["c_out"],
+                                                      r["c_lse"], 6)
+    assert np.all(flags2 == ref.FLAG_RECOMPUTED)
+    np.testing.assert_array_equal(c_q, q_t)
+    for h in range(4):
+        g = h // 2
+        np.testing.assert_allclose(out2[h], sdpa64(q_t[h], K[g], V[g], 0.25), atol=1e-13)
+        ev = np.array(sorted(set(range(54)) - set(r["idx"][g])))
+        np.testing.assert_allclose(c_out[h], sdpa64(q_t[h], K[g][ev], V[g][ev], 0.25), atol=1e-13)
+        np.testing.assert_allclose(c_lse[h], logsumexp(0.25 * K[g][ev] @ q_t[h]), atol=1e-13)
+    # the refreshed state calibrates the same query exactly on the next step (rho = 1)
+    out3, _, flags3, rho3 = ref.decode(q_t, r["K_c"], r["V_c"], 18, c_q, c_out, c_lse, 0.7, 0.85)
+    assert np.all(flags3 == ref.FLAG_CALIBRATED)
+    np.testing.assert_allclose(out3, out2, atol=1e-13)
+    # heads that were not flagged are left alone
+    flags_mixed = flags.copy(); flags_mixed[1] = ref.FLAG_NONE
+    o4, f4, cq4, co4, cl4 = ref.recalibrate(q_t, K, V, r["idx"], flags_mixed, a_lse, out, r["c_q"], r["c_out"],
+                                            r["c_lse"], 6)
+    np.testing.assert_array_equal(o4[1], out[1]); np.testing.assert_array_equal(cq4[1], r["c_q"][1])
+    assert f4[1] == ref.FLAG_NONE and f4[0] == ref.FLAG_RECOMPUTED
+
+
+def test_recompute_with_nothing_evicted_is_a_noop_on_the_output():
+    q_win, K, V = rand_case(n=20)
+    r = ref.compress(q_win, K, V, 4, 32, 5)
+    q_t = -q_win[:, -1]
+    out, a_lse, flags, _ = ref.decode(q_t, r["K_c"], r["V_c"], 20, r["c_q"], r["c_out"], r["c_lse"], 0.7, 0.85)
+    out2, flags2, c_q, c_out, c_lse = ref.recalibrate(q_t, K, V, r["idx"], flags, a_lse, out, r["c_q"], r["c_out"],
+                                                      r["c_lse"], 4)
+    np.testing.assert_array_equal(out2, out)
+    assert np.all(c_lse == -np.inf) and np.all(flags2 == ref.FLAG_RECOMPUTED)
+    np.testing.assert_array_equal(c_q, q_t)
