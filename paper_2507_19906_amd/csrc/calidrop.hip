@@ -69,20 +69,22 @@ float logit_scale(const calidrop_params* p) {
   return p->scale > 0.f ? p->scale : 1.0f / std::sqrt(static_cast<float>(p->head_dim));
 }
 
-// Decode uses the single-workgroup-per-(sequence, KV head) kernel from this many pairs on.
-#ifndef CD_FUSED_MIN_PAIRS
-#define CD_FUSED_MIN_PAIRS 192
-#endif
-constexpr int kFusedMinPairs = CD_FUSED_MIN_PAIRS;
+// Decode runs as one workgroup per (sequence, KV head) - one launch, no workspace - unless there
+// are too few pairs to fill the chip AND the cache is long enough for a row split to pay for the
+// second launch.
+constexpr int kFusedMinPairs = 192;
+constexpr int kFusedMaxRowsFewPairs = 2048;
 
 // How the rows of a streaming-attention pass are split over workgroups.
 struct SplitPlan { int rows_per_split, NS; };
 SplitPlan plan_splits(int heads_kv_total, int max_rows) {
-  const int kTargetGroups = 2048;                      // ~8 workgroups per compute unit
+  const int kTargetGroups = 4096;                      // ~16 workgroups per compute unit
+  const int kMaxSplits = 32;                           // the merge of the partials is sequential
   const int kMinRows = cd::kTileRows * cd::kAttWaves;  // one tile per wave
   if (max_rows < 1) max_rows = 1;
   int want = ceil_div(kTargetGroups, heads_kv_total);
   if (want < 1) want = 1;
+  if (want > kMaxSplits) want = kMaxSplits;
   int rps = ceil_div(ceil_div(max_rows, want), kMinRows) * kMinRows;
   if (rps < kMinRows) rps = kMinRows;
   return SplitPlan{rps, ceil_div(max_rows, rps)};
@@ -98,9 +100,9 @@ CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, i
   CompressLayout L{};
   const int G = p->n_q_heads / p->n_kv_heads;
   L.NRB = ceil_div(G * p->window, cd::kRowBlock);
-  {  // keys per scoring workgroup: as large as keeps >= ~2048 workgroups in the launch, 256..2048
+  {  // keys per scoring workgroup: as large as keeps >= ~4096 workgroups in the launch, 256..2048
     const int64_t groups256 = static_cast<int64_t>(p->batch) * p->n_kv_heads * L.NRB * ceil_div(max_seq_len, cd::kMinChunkKeys);
-    int mult = static_cast<int>(groups256 / 2048);
+    int mult = static_cast<int>(groups256 / 4096);
     if (mult < 1) mult = 1;
     if (mult > 8) mult = 8;
     L.chunk_keys = mult * cd::kMinChunkKeys;
@@ -208,12 +210,17 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
       const size_t votes = (static_cast<size_t>(max_prefix) + max_prefix / 32 + 1) * sizeof(float);
       if (votes > lds) lds = votes;
     }
+    const int nt = max_prefix <= 256 * cd::kSelPerThread ? 256 : (max_prefix <= 512 * cd::kSelPerThread ? 512 : 1024);
+    const void* fn = nt == 256   ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<256>)
+                     : nt == 512 ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<512>)
+                                 : reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<1024>);
     if (lds > 48 * 1024) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cd::select_gather_lds_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(cd::select_gather_lds_kernel, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
+    if (nt == 256) hipLaunchKernelGGL(cd::select_gather_lds_kernel<256>, dim3(bg), dim3(256), lds, st, se);
+    else if (nt == 512) hipLaunchKernelGGL(cd::select_gather_lds_kernel<512>, dim3(bg), dim3(512), lds, st, se);
+    else hipLaunchKernelGGL(cd::select_gather_lds_kernel<1024>, dim3(bg), dim3(1024), lds, st, se);
   } else {
     hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
     if ((rc = launch_status("pool_scores"))) return rc;
@@ -254,7 +261,7 @@ int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, cons
   const int G = p->n_q_heads / p->n_kv_heads;
   int rc;
   // Enough (sequence, KV head) pairs to fill the chip: one workgroup does a pair's whole step.
-  if (p->batch * p->n_kv_heads >= kFusedMinPairs) {
+  if (p->batch * p->n_kv_heads >= kFusedMinPairs || max_cache_len <= kFusedMaxRowsFewPairs) {
     cd::DecodeFusedArgs fa{};
     fa.q = q_t; fa.k = k_c; fa.v = v_c; fa.row_off = cache_offsets; fa.row_len = cache_lens;
     fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G; fa.max_len = max_cache_len;

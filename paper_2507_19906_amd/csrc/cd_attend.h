@@ -326,10 +326,18 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
   (void)g;
   const int ns = (rows + a.rows_per_split - 1) / a.rows_per_split;
   const int64_t slot0 = static_cast<int64_t>(b * a.Hq + h) * a.NS;
+  const int64_t hd = static_cast<int64_t>(b * a.Hq + h);
+  // operands of the tail are fetched now, together with the partials (one round trip, not five)
+  const T* qp = static_cast<const T*>(a.q);
+  const float qd = a.q_is_window ? load_elem<T>(qp, (hd * a.w + (a.w - 1)) * D + d) : load_elem<T>(qp, hd * D + d);
+  float cq = 0.f, co = 0.f, c_lse_in = -INFINITY;
+  if (a.calib_mode == 0) { cq = a.c_q[hd * D + d]; co = a.c_out[hd * D + d]; c_lse_in = a.c_lse[hd]; }
   float mm = -INFINITY;
+#pragma unroll 8
   for (int s = 0; s < ns; ++s) mm = fmaxf(mm, a.part_ml[slot0 + s].x);
   const float ms = (mm == -INFINITY) ? 0.f : mm;
   float o = 0.f, ll = 0.f;
+#pragma unroll 8
   for (int s = 0; s < ns; ++s) {
     const float2 ml = a.part_ml[slot0 + s];
     const float sc = fast_exp2(ml.x - ms);
@@ -339,9 +347,6 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
   const bool any = ll > 0.f;
   const float o_n = any ? o / ll : 0.f;
   const float lse = any ? (mm + fast_log2(ll)) * kLn2 : -INFINITY;     // natural-log units
-  const T* qp = static_cast<const T*>(a.q);
-  const int64_t hd = static_cast<int64_t>(b * a.Hq + h);
-  const float qd = a.q_is_window ? load_elem<T>(qp, (hd * a.w + (a.w - 1)) * D + d) : load_elem<T>(qp, hd * D + d);
   if (a.calib_mode) {
     a.c_q[hd * D + d] = qd;
     a.c_out[hd * D + d] = o_n;
@@ -358,13 +363,12 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
     return;
   }
   // decode: rho = cos(q_t, c_q) in fp32
-  const float cq = a.c_q[hd * D + d];
   const float dot = block_sum(qd * cq, red, D);
   const float nq2 = block_sum(qd * qd, red, D);
   const float nc2 = block_sum(cq * cq, red, D);
   float rho = 0.f;
   if (nq2 > 0.f && nc2 > 0.f) rho = dot / (sqrtf(nq2) * sqrtf(nc2));
-  const float c_lse = a.c_lse[hd];
+  const float c_lse = c_lse_in;
   uint8_t flag = 0;
   float res = o_n;
   if (rho < a.theta1) {
@@ -373,7 +377,7 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
     flag = 1;
     // alpha_j = sigmoid(c_lse - a_lse); a_lse = -inf (empty cache) gives alpha_j = 1
     const float aj = 1.f / (1.f + __expf(lse - c_lse));
-    res = (1.f - aj) * o_n + aj * a.c_out[hd * D + d];
+    res = (1.f - aj) * o_n + aj * co;
   }
   store_elem<T>(static_cast<T*>(a.out), hd * D + d, res);
   if (d == 0) {

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
 
   __shared__ uint32_t hist[256];
   __shared__ uint32_t s_prefix, s_remaining;
-  __shared__ uint32_t wave_cnt[kSelThreads / 64];
+  __shared__ uint32_t wave_gt[kSelThreads / 64], wave_eq[kSelThreads / 64];
 
   if (n <= a.B) {                       // nothing to evict: keep every position
     for (int r = tid; r < a.B; r += kSelThreads) idx[r] = (r < n) ? r : -1;
@@ -72,16 +72,21 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
       {
-        // run-length compressed updates: scores share their leading digits, so a thread's
-        // consecutive keys mostly fall in the same bin; only bin changes touch the histogram
+        // run-length compressed updates (scores share their leading digits); 8 independent
+        // loads per thread are in flight at a time
         uint32_t run_bin = 0, run_len = 0;
-        for (int j = tid; j < P; j += kSelThreads) {
-          const uint32_t u = key_at(j);
-          if ((u & himask) == prefix) {
-            const uint32_t bin = (u >> shift) & 0xFF;
-            if (bin != run_bin && run_len) { atomicAdd(&hist[run_bin], run_len); run_len = 0; }
-            run_bin = bin;
-            ++run_len;
+        for (int j0 = tid; j0 < P; j0 += 8 * kSelThreads) {
+          uint32_t u[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) u[q] = (j0 + q * kSelThreads < P) ? key_at(j0 + q * kSelThreads) : 0u;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            if (j0 + q * kSelThreads < P && (u[q] & himask) == prefix) {
+              const uint32_t bin = (u[q] >> shift) & 0xFF;
+              if (bin != run_bin && run_len) { atomicAdd(&hist[run_bin], run_len); run_len = 0; }
+              run_bin = bin;
+              ++run_len;
+            }
           }
         }
         if (run_len) atomicAdd(&hist[run_bin], run_len);
@@ -116,40 +121,54 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
     const uint32_t thr = prefix;          // bit pattern of the k_sel-th largest score
     const uint32_t need_eq = remaining;   // how many entries equal to thr are kept (>= 1)
 
-    // ---- ordered compaction + retained bitmap -------------------------------------------
+    // ---- ordered compaction + retained bitmap: wave w owns the contiguous positions
+    //      [w*seg, (w+1)*seg); one counting sweep, one barrier, one emitting sweep --------------
     uint32_t* bm = a.bitmap + static_cast<int64_t>(bg) * a.W32;
-    uint32_t run_gt = 0, run_eq = 0;      // counts over all earlier positions
-    const int n_round = (n + kSelThreads - 1) / kSelThreads * kSelThreads;
-    for (int base = 0; base < n_round; base += kSelThreads) {
-      const int j = base + tid;
-      const uint32_t u = (j < P) ? key_at(j) : 0u;
-      const bool gt = (j < P) && (u > thr);
-      const bool eq = (j < P) && (u == thr);
-      const uint64_t mgt = __ballot(gt), meq = __ballot(eq);
-      const uint64_t below = (1ull << lane) - 1ull;
-      if (lane == 0) wave_cnt[wv] = __popcll(mgt) | (__popcll(meq) << 16);
-      __syncthreads();
-      uint32_t pre_gt = run_gt + __popcll(mgt & below);
-      uint32_t pre_eq = run_eq + __popcll(meq & below);
-      uint32_t tot_gt = 0, tot_eq = 0;
+    constexpr int NWV = kSelThreads / 64;
+    const int seg = ((n + NWV - 1) / NWV + 63) / 64 * 64;
+    const int seg_lo = wv * seg, seg_hi = min(n, seg_lo + seg);
+    const int key_hi = min(P, seg_hi);    // candidates of this wave: prefix positions of its segment
+    uint32_t cnt_gt = 0, cnt_eq = 0;
+    for (int base = seg_lo; base < seg_hi; base += 4 * 64) {
+      uint32_t u[4];
 #pragma unroll
-      for (int ww = 0; ww < kSelThreads / 64; ++ww) {
-        const uint32_t cnt = wave_cnt[ww];
-        if (ww < wv) { pre_gt += cnt & 0xFFFFu; pre_eq += cnt >> 16; }
-        tot_gt += cnt & 0xFFFFu;
-        tot_eq += cnt >> 16;
+      for (int q = 0; q < 4; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? key_at(j) : 0u; }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int j = base + q * 64 + lane;
+        cnt_gt += __popcll(__ballot(j < key_hi && u[q] > thr));
+        cnt_eq += __popcll(__ballot(j < key_hi && u[q] == thr));
       }
-      const bool keep = gt || (eq && pre_eq < need_eq);
-      if (keep) idx[pre_gt + min(pre_eq, need_eq)] = j;
-      // bit = not evicted: selected prefix positions and everything from the window on
-      const uint64_t mk = __ballot(keep || j >= P);
-      if (lane == 0 && base + wv * 64 < n) {
-        bm[(base + wv * 64) >> 5] = static_cast<uint32_t>(mk);
-        bm[((base + wv * 64) >> 5) + 1] = static_cast<uint32_t>(mk >> 32);
+    }
+    if (lane == 0) { wave_gt[wv] = cnt_gt; wave_eq[wv] = cnt_eq; }
+    __syncthreads();
+    uint32_t pre_gt = 0, pre_eq = 0;      // counts over all earlier positions (wave-uniform)
+    for (int ww = 0; ww < wv; ++ww) { pre_gt += wave_gt[ww]; pre_eq += wave_eq[ww]; }
+    const uint64_t below = (1ull << lane) - 1ull;
+    for (int base = seg_lo; base < seg_hi; base += 4 * 64) {
+      uint32_t u[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? key_at(j) : 0u; }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int j = base + q * 64 + lane;
+        if (base + q * 64 < seg_hi) {
+          const bool gt = j < key_hi && u[q] > thr;
+          const bool eq = j < key_hi && u[q] == thr;
+          const uint64_t mgt = __ballot(gt), meq = __ballot(eq);
+          const uint32_t my_eq = pre_eq + __popcll(meq & below);
+          const bool keep = gt || (eq && my_eq < need_eq);
+          if (keep) idx[pre_gt + __popcll(mgt & below) + min(my_eq, need_eq)] = j;
+          // bit = not evicted: selected prefix positions and everything from the window on
+          const uint64_t mk = __ballot(keep || j >= P);
+          if (lane == 0) {
+            bm[(base + q * 64) >> 5] = static_cast<uint32_t>(mk);
+            bm[((base + q * 64) >> 5) + 1] = static_cast<uint32_t>(mk >> 32);
+          }
+          pre_gt += __popcll(mgt);
+          pre_eq += __popcll(meq);
+        }
       }
-      run_gt += tot_gt;
-      run_eq += tot_eq;
-      __syncthreads();
     }
     for (int r = tid; r < a.w; r += kSelThreads) idx[k_sel + r] = P + r;   // the window is always kept
   }
@@ -192,12 +211,14 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
   }
 }
 
-// LDS variant for prefixes of up to kSelMaxLdsKeys positions.  Thread t owns positions
+// LDS variant for prefixes of up to 32 * NT positions (NT = 256, 512 or 1024 threads; the
+// smaller workgroups let two or four heads share a compute unit).  Thread t owns positions
 // 32t..32t+31: their pooled scores live in its registers for the radix passes and the
 // compaction, and their retained bits are exactly bitmap word t.  The votes are staged once in
 // LDS (padded by one word per 32 so that the stride-32 accesses do not collide), and the same
 // LDS later holds the retained indices for the gather.
-__global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectArgs a) {
+template <int NT>
+__global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
   extern __shared__ uint32_t s_sel[];
   float* s_vote = reinterpret_cast<float*>(s_sel);
   int32_t* s_idx = reinterpret_cast<int32_t*>(s_sel);      // reused after pooling
@@ -214,12 +235,12 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
 
   __shared__ uint32_t hist[256];
   __shared__ uint32_t s_prefix, s_remaining;
-  __shared__ uint32_t wave_tot[kSelThreads / 64];
+  __shared__ uint32_t wave_tot[NT / 64];
   constexpr int PER = kSelPerThread;
   auto pad = [](int j) { return j + (j >> 5); };
 
   if (n <= a.B) {                       // nothing to evict: keep every position
-    for (int r = tid; r < a.B; r += kSelThreads) {
+    for (int r = tid; r < a.B; r += NT) {
       idx[r] = (r < n) ? r : -1;
       if (r < n) s_idx[r] = r;
     }
@@ -233,7 +254,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
       float tmp[PER];
 #pragma unroll
       for (int u = 0; u < PER; ++u) {               // all loads of a thread in flight together
-        const int j = tid + u * kSelThreads;
+        const int j = tid + u * NT;
         float val = 0.f;
         if (j < P) {
           val = vsrc[j];
@@ -243,7 +264,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
       }
 #pragma unroll
       for (int u = 0; u < PER; ++u) {
-        const int j = tid + u * kSelThreads;
+        const int j = tid + u * NT;
         if (j < P) s_vote[pad(j)] = tmp[u];
       }
     }
@@ -284,7 +305,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
         float* dst = a.score + head_tok;
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
-          const int j = tid + u * kSelThreads;
+          const int j = tid + u * NT;
           if (j < P) dst[j] = __builtin_bit_cast(float, s_sel[pad(j)]);
         }
       }
@@ -375,7 +396,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
       word |= ((keep || !in) ? 1u : 0u) << u;       // bit = not evicted (window and beyond count as kept)
     }
     if (j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + tid] = word;
-    for (int r = tid; r < a.w; r += kSelThreads) { idx[k_sel + r] = P + r; s_idx[k_sel + r] = P + r; }
+    for (int r = tid; r < a.w; r += NT) { idx[k_sel + r] = P + r; s_idx[k_sel + r] = P + r; }
   }
 
   // ---- gather: K_c[g][r] = K[g][idx[g][r]], V likewise; 16 bytes per thread per copy ---------
@@ -391,11 +412,11 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
   char* vdst = static_cast<char*>(a.v_c) + dst_head;
   constexpr int kBatch = 8;              // independent row copies in flight per thread
   const int total = len * vec_per_row;
-  for (int t0 = tid; t0 < total; t0 += kBatch * kSelThreads) {
+  for (int t0 = tid; t0 < total; t0 += kBatch * NT) {
     u32x4 kk[kBatch], vv[kBatch];
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
-      const int t = t0 + u * kSelThreads;
+      const int t = t0 + u * NT;
       if (t < total) {
         const int64_t so = static_cast<int64_t>(s_idx[t / vec_per_row]) * a.row_bytes + (t % vec_per_row) * 16;
         kk[u] = ld16(ksrc + so);
@@ -404,7 +425,7 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_lds_kernel(SelectAr
     }
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
-      const int t = t0 + u * kSelThreads;
+      const int t = t0 + u * NT;
       const int64_t dof = static_cast<int64_t>(t / vec_per_row) * a.row_bytes + (t % vec_per_row) * 16;
       if (t < total) { st16(kdst + dof, kk[u]); st16(vdst + dof, vv[u]); }
     }
