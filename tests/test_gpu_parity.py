@@ -269,3 +269,82 @@ def test_recomputation_yields_exact_full_attention():
     after = H.snapshot_state(bufs)
     for key in snap:
         assert np.array_equal(snap[key], after[key]), key
+
+
+def test_random_small_configurations():
+    # seeded sweep over shapes, dtypes, windows, budgets, pooling widths, scales and lengths,
+    # including the edge cases one evicted token (n = B + 1), budget = window + 1, pooling
+    # wider than the in-LDS limit, and a non-default logit scale
+    rng = np.random.default_rng(7)
+    cases = [
+        dict(dtype="bf16", Hq=4, Hkv=2, D=64, lens=[34], w=4, B=33, k=3),          # n = B + 1
+        dict(dtype="fp32", Hq=2, Hkv=2, D=64, lens=[200], w=7, B=8, k=1),           # B = w + 1, odd w
+        dict(dtype="bf16", Hq=8, Hkv=1, D=128, lens=[700], w=12, B=100, k=17),      # k beyond the LDS variant
+        dict(dtype="fp32", Hq=16, Hkv=1, D=64, lens=[300, 90], w=8, B=64, k=5),     # G = 16
+        dict(dtype="bf16", Hq=12, Hkv=4, D=128, lens=[257, 1025], w=20, B=96, k=9, scale=0.05),
+    ]
+    for _ in range(8):
+        Hkv = int(rng.choice([1, 2, 4]))
+        G = int(rng.choice([1, 2, 4, 8]))
+        w = int(rng.integers(1, 40))
+        B = w + int(rng.integers(1, 200))
+        lens = [int(rng.integers(2, 1500)) for _ in range(int(rng.integers(1, 4)))]
+        cases.append(dict(dtype=str(rng.choice(["bf16", "fp32"])), Hq=Hkv * G, Hkv=Hkv, D=int(rng.choice([64, 128])),
+                          lens=lens, w=w, B=B, k=int(rng.choice([1, 3, 5, 7, 11]))))
+    for i, c in enumerate(cases):
+        wl = small(c["dtype"], c["Hq"], c["Hkv"], c["D"], c["lens"], c["w"], c["B"], c["k"], T=2, name=f"rand{i}")
+        x = to_dev(synth.make_inputs(wl, 100 + i))
+        over = {"scale": c["scale"]} if "scale" in c else {}
+        bufs = H.gpu_compress(wl, x, **over)
+        rep = {}
+        for b in range(wl.batch):
+            if "scale" in c:        # the oracle helpers use the default scale: check this one directly
+                n = wl.seq_lens[b]
+                K = H.to64(synth.seq_view(x["k"], wl, b)); V = H.to64(synth.seq_view(x["v"], wl, b))
+                orc = ref.compress(H.to64(x["q_win"][b]), K, V, wl.window, wl.budget, wl.pool_kernel, scale=c["scale"])
+                assert np.array_equal(bufs.indices[b].cpu().numpy()[:, :min(n, wl.budget)], orc["idx"])
+                assert np.abs(H.to64(bufs.c_out[b]) - orc["c_out"]).max() < 2e-2
+                assert np.abs(H.to64(bufs.c_lse[b]) - orc["c_lse"]).max() < 2e-3
+            else:
+                H.check_compress(wl, x, bufs, b, report=rep)
+        if "scale" not in c:
+            for t in range(2):
+                bufs.decode(x["q_dec"][t])
+                torch.cuda.synchronize()
+                for b in range(wl.batch):
+                    H.check_decode_step(wl, bufs, x["q_dec"][t], b, report=rep)
+        print(wl.name, c, {k: v for k, v in rep.items() if k != "flags"}, flush=True)
+
+
+def test_decode_under_hip_graph_replay():
+    # the decode entry point allocates nothing and records no memset: a captured graph of
+    # several steps must reproduce the eager results on every replay
+    wl = small("bf16", 8, 2, 128, [600] * 100, 16, 128, 5, T=4, name="graph")
+    x = to_dev(synth.make_inputs(wl, 77))
+    bufs = H.gpu_compress(wl, x)
+    outs = [torch.empty_like(bufs.out) for _ in range(4)]
+    eager = []
+    for t in range(4):
+        bufs.decode(x["q_dec"][t])
+        torch.cuda.synchronize()
+        eager.append((bufs.out.clone(), bufs.a_lse.clone(), bufs.flags.clone()))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        for t in range(4):                       # warm-up on the capture stream
+            bufs.decode(x["q_dec"][t], stream=side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for t in range(4):
+                bufs.decode(x["q_dec"][t], stream=torch.cuda.current_stream())
+                outs[t].copy_(bufs.out)
+    for rep_i in range(3):
+        for o in outs:
+            o.zero_()
+        bufs.out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t in range(4):
+            assert torch.equal(outs[t], eager[t][0]), (rep_i, t)
+        assert torch.equal(bufs.a_lse, eager[3][1]) and torch.equal(bufs.flags, eager[3][2])
