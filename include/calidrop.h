@@ -68,7 +68,8 @@ enum {
 };
 
 typedef struct {
-  uint32_t struct_size; /* = sizeof(calidrop_params); checked                               */
+  uint32_t struct_size; /* = sizeof(calidrop_params); also accepted: 48, the layout without
+                           calib_size (calib_size is then 0)                                  */
   int32_t dtype;        /* calidrop_dtype                                                   */
   int32_t batch;        /* sequences; a stack of layers is passed as batch = layers * seqs   */
   int32_t n_q_heads;    /* Hq                                                               */
@@ -80,6 +81,10 @@ typedef struct {
   float scale;          /* logit scale; 0 selects 1/sqrt(D)                                  */
   float theta1, theta2; /* Alg. 2 thresholds, theta1 <= theta2, compared strictly in fp32;
                            (-inf, -inf) calibrates whenever a calibration state exists       */
+  int32_t calib_size;   /* m >= 0, the "calibration size" of Sec. 5.3: only the m evicted tokens
+                           of highest pooled score (ties to the lower position) form the
+                           calibration / offload set, the others are dropped; 0 = every evicted
+                           token                                                              */
 } calidrop_params;
 
 /* Bytes of device workspace calidrop_compress needs for these shapes (0 on invalid params).
@@ -126,7 +131,8 @@ int calidrop_compress_workspace_region(const calidrop_params* p, int64_t total_t
  *        KV_evict and stays where it is, in the caller's k / v.
  *     6. for each query head h of the group, with q = q_cal[h] (default Q_{-1}, the last
  *        window query): c_lse[h] = log sum_{t in evict} exp(scale q.K_t) (= log C_weight),
- *        c_out[h] = Att(q, K_evict, V_evict), c_q[h] = q.
+ *        c_out[h] = Att(q, K_evict, V_evict), c_q[h] = q.  With calib_size = m > 0 "evict"
+ *        here means the calibration set: the m evicted positions of highest score.
  *
  * Arguments
  *   q_win         [batch][Hq][w][D] dtype: the last w prompt queries (as used by attention).
@@ -143,6 +149,10 @@ int calidrop_compress_workspace_region(const calidrop_params* p, int64_t total_t
  *   cache_lens    out [batch] int32 = min(B, n_b).
  *   indices       out [batch][Hkv][B] int32: retained prompt positions, ascending; -1 padded
  *                 when n_b < B.
+ *   cal_indices   out [batch][Hkv][calib_size] int32: positions of the calibration set, ascending,
+ *                 -1 padded (fewer than calib_size evicted tokens, or n_b <= B).  These are the
+ *                 rows a caller would offload.  Required when calib_size > 0, ignored (may be
+ *                 NULL) when calib_size = 0.
  *   c_q, c_out    out [batch][Hq][D] fp32.   c_lse  out [batch][Hq] fp32.
  *   workspace     >= calidrop_compress_workspace_bytes(p, total_tokens, max_seq_len) bytes,
  *                 256-byte aligned; contents need no initialisation.
@@ -150,8 +160,9 @@ int calidrop_compress_workspace_region(const calidrop_params* p, int64_t total_t
 int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k, const void* v,
                       const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
                       const void* q_cal, void* k_c, void* v_c, const int32_t* cache_offsets,
-                      int32_t* cache_lens, int32_t* indices, float* c_q, float* c_out,
-                      float* c_lse, void* workspace, size_t workspace_bytes, void* stream);
+                      int32_t* cache_lens, int32_t* indices, int32_t* cal_indices, float* c_q,
+                      float* c_out, float* c_lse, void* workspace, size_t workspace_bytes,
+                      void* stream);
 
 /*
  * calidrop_decode - Alg. 2 for one decode step of `batch` sequences.
@@ -184,7 +195,8 @@ int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, 
  * preceding calidrop_decode call of the same step flagged CALIDROP_FLAG_RECOMPUTE.
  *
  * For every such (sequence b, query head h), with KV head g = h / G and KV_evict = the prefix
- * rows of the prompt (positions < n_b - w) that are not listed in indices[b][g]:
+ * rows of the prompt (positions < n_b - w) that are not listed in indices[b][g] - or, when
+ * calib_size > 0, exactly the rows listed in cal_indices[b][g]:
  *   c_lse[h] = log sum_{t in evict} exp(scale q_t[h].K_t),  c_out[h] = Att(q_t[h], K_evict, V_evict)
  *   (the current query is used, as the text of Sec. 3.2 says), c_q[h] = q_t[h]           (steps 5-7)
  *   out[h] = alpha_i out[h] + alpha_j c_out[h] with alpha_j = 1/(1+exp(a_lse[h] - c_lse[h]))  (step 8)
@@ -195,17 +207,18 @@ int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, 
  *
  * Arguments: q_t, out, a_lse, flags as passed to / written by calidrop_decode for this step (out
  * and flags are updated in place; flags must not be NULL here); k, v, seq_offsets, total_tokens,
- * max_seq_len and indices as in calidrop_compress (the prompt K/V must still be resident: this is
- * where the "offloaded" evicted cache is read from); c_q, c_out, c_lse the calibration state,
+ * max_seq_len, indices and cal_indices as in / from calidrop_compress (the prompt K/V must still
+ * be resident: this is where the "offloaded" evicted cache is read from; cal_indices is required
+ * when calib_size > 0 and ignored otherwise); c_q, c_out, c_lse the calibration state,
  * updated in place; workspace >= calidrop_recalibrate_workspace_bytes(p, max_seq_len) bytes,
  * 256-byte aligned.
  */
 size_t calidrop_recalibrate_workspace_bytes(const calidrop_params* p, int32_t max_seq_len);
 int calidrop_recalibrate(const calidrop_params* p, const void* q_t, const void* k, const void* v,
                          const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
-                         const int32_t* indices, uint8_t* flags, const float* a_lse, void* out,
-                         float* c_q, float* c_out, float* c_lse, void* workspace,
-                         size_t workspace_bytes, void* stream);
+                         const int32_t* indices, const int32_t* cal_indices, uint8_t* flags,
+                         const float* a_lse, void* out, float* c_q, float* c_out, float* c_lse,
+                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* Host string describing the last error on the calling thread ("" if none). Never NULL.      */
 const char* calidrop_last_error(void);

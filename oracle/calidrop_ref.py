@@ -140,8 +140,12 @@ def calibration_state(q_cal, K, V, evicted, G, scale):
     return q_cal.copy(), c_out, c_lse
 
 
-def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=None):
+def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=None, calib_size=0):
     """Alg. 1 steps 3-8 for one sequence.
+
+    calib_size = m > 0 keeps only the m evicted tokens of highest importance (pooled score, ties
+    to the lower position) for calibration and offloading - the "calibration size" of Sec. 5.3;
+    every other evicted token is dropped for good.  m = 0 keeps every evicted token.
 
     q_win [Hq][w][D] last w prompt queries; K, V [Hkv][n][D]; B = KV budget (window included);
     k = pooling kernel; q_cal [Hq][D] calibration query (default Q_{-1} = q_win[:, -1]).
@@ -182,11 +186,15 @@ def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=Non
         idx_g = np.concatenate([sel, np.arange(P, n)])
         mask = np.ones(P, bool)
         mask[sel] = False
+        ev = np.nonzero(mask)[0]                     # KV_evict = KV_full minus KV_compress
+        if calib_size > 0 and calib_size < len(ev):  # Sec. 5.3: rank the evicted tokens by importance
+            order = np.argsort(-score[ev], kind="stable")
+            ev = np.sort(ev[order[:calib_size]])
         idx.append(idx_g)
         votes.append(vote)
         scores.append(score)
         margins.append(margin)
-        evicted.append(np.nonzero(mask)[0])          # KV_evict = KV_full \ KV_compress
+        evicted.append(ev)
     idx = np.stack(idx)
     K_c = np.stack([K[g][idx[g]] for g in range(Hkv)])
     V_c = np.stack([V[g][idx[g]] for g in range(Hkv)])
@@ -248,7 +256,7 @@ def decode(q_t, K_c, V_c, length, c_q, c_out, c_lse, theta1, theta2, scale=None)
     return out, a_lse, flags, rhos
 
 
-def recalibrate(q_t, K, V, idx, flags, a_lse, out, c_q, c_out, c_lse, w, scale=None):
+def recalibrate(q_t, K, V, idx, flags, a_lse, out, c_q, c_out, c_lse, w, scale=None, cal_idx=None):
     """Alg. 2 steps 3-8 (the rho < theta1 branch) for the heads that `decode` flagged.
 
     The evicted K/V are the prefix rows of the prompt tensors K, V [Hkv][n][D] that are not in
@@ -256,7 +264,9 @@ def recalibrate(q_t, K, V, idx, flags, a_lse, out, c_q, c_out, c_lse, w, scale=N
     flag FLAG_RECOMPUTE: C_weight and C_out are recomputed with the CURRENT query (the prose of
     Sec. 3.2; the listing prints Q_{-1} but then sets C_q = Q_t), C_q = Q_t, and the output is
     calibrated by Eq. 1: out = alpha_i * out + alpha_j * C_out.  `out`, `a_lse` are what decode
-    returned for this step.  Returns new (out, flags, c_q, c_out, c_lse); inputs are not modified."""
+    returned for this step.  With a calibration size (Sec. 5.3) only the offloaded subset exists:
+    cal_idx [Hkv][m] lists its positions (-1 padded) and replaces "every evicted token".
+    Returns new (out, flags, c_q, c_out, c_lse); inputs are not modified."""
     q_t = np.asarray(q_t, F)
     K = np.asarray(K, F)
     V = np.asarray(V, F)
@@ -277,6 +287,9 @@ def recalibrate(q_t, K, V, idx, flags, a_lse, out, c_q, c_out, c_lse, w, scale=N
         mask = np.ones(max(P, 0), bool)
         mask[keep[(keep >= 0) & (keep < P)]] = False
         ev = np.nonzero(mask)[0]
+        if cal_idx is not None:
+            ci = np.asarray(cal_idx[g])
+            ev = ci[ci >= 0]
         c_out[h], c_lse[h] = attention(q_t[h], K[g][ev], V[g][ev], scale)     # steps 5-6
         c_q[h] = q_t[h]                                                       # step 7
         out[h], _ = merge(out[h], a_lse[h], c_out[h], c_lse[h])               # step 8 (Eq. 1)

@@ -41,17 +41,18 @@ class Params(ctypes.Structure):
         ("scale", ctypes.c_float),
         ("theta1", ctypes.c_float),
         ("theta2", ctypes.c_float),
+        ("calib_size", ctypes.c_int32),
     ]
 
 
 def make_params(*, dtype, batch, n_q_heads, n_kv_heads, head_dim, window, budget, pool_kernel,
-                scale=0.0, theta1=0.7, theta2=0.85) -> Params:
+                scale=0.0, theta1=0.7, theta2=0.85, calib_size=0) -> Params:
     if isinstance(dtype, torch.dtype):
         dtype = BF16 if dtype == torch.bfloat16 else FP32
     elif isinstance(dtype, str):
         dtype = BF16 if dtype == "bf16" else FP32
     return Params(ctypes.sizeof(Params), dtype, batch, n_q_heads, n_kv_heads, head_dim, window,
-                  budget, pool_kernel, scale, theta1, theta2)
+                  budget, pool_kernel, scale, theta1, theta2, calib_size)
 
 
 _lib = None
@@ -82,7 +83,7 @@ def lib() -> ctypes.CDLL:
         L.calidrop_compress_workspace_region.argtypes = [pp, i64, i32, i32, ctypes.POINTER(sz),
                                                          ctypes.POINTER(sz)]
         L.calidrop_compress.restype = ctypes.c_int
-        L.calidrop_compress.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp,
+        L.calidrop_compress.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp,
                                         vp, vp, vp, sz, vp]
         L.calidrop_decode.restype = ctypes.c_int
         L.calidrop_decode.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz,
@@ -90,7 +91,7 @@ def lib() -> ctypes.CDLL:
         L.calidrop_recalibrate_workspace_bytes.restype = sz
         L.calidrop_recalibrate_workspace_bytes.argtypes = [pp, i32]
         L.calidrop_recalibrate.restype = ctypes.c_int
-        L.calidrop_recalibrate.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.calidrop_recalibrate.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -146,13 +147,13 @@ def calidrop_compress_workspace_region(p: Params, total_tokens: int, max_seq_len
 
 
 def calidrop_compress(p: Params, q_win, k, v, seq_offsets, total_tokens: int, max_seq_len: int,
-                      q_cal, k_c, v_c, cache_offsets, cache_lens, indices, c_q, c_out, c_lse,
+                      q_cal, k_c, v_c, cache_offsets, cache_lens, indices, cal_indices, c_q, c_out, c_lse,
                       workspace, stream=None) -> None:
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().calidrop_compress(
         ctypes.byref(p), _ptr(q_win), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
         _ptr(q_cal), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens), _ptr(indices),
-        _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
+        _ptr(cal_indices), _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 def calidrop_decode(p: Params, q_t, k_c, v_c, cache_offsets, cache_lens, max_cache_len: int, c_q,
@@ -172,12 +173,12 @@ def calidrop_recalibrate_workspace_bytes(p: Params, max_seq_len: int) -> int:
 
 
 def calidrop_recalibrate(p: Params, q_t, k, v, seq_offsets, total_tokens: int, max_seq_len: int, indices,
-                         flags, a_lse, out, c_q, c_out, c_lse, workspace, stream=None) -> None:
+                         cal_indices, flags, a_lse, out, c_q, c_out, c_lse, workspace, stream=None) -> None:
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().calidrop_recalibrate(
         ctypes.byref(p), _ptr(q_t), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
-        _ptr(indices), _ptr(flags), _ptr(a_lse), _ptr(out), _ptr(c_q), _ptr(c_out), _ptr(c_lse),
-        _ptr(workspace), ws_bytes, _stream(stream)))
+        _ptr(indices), _ptr(cal_indices), _ptr(flags), _ptr(a_lse), _ptr(out), _ptr(c_q), _ptr(c_out),
+        _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 # ---- device-memory plumbing (allocation only) ----------------------------------------------
@@ -199,6 +200,8 @@ class CompressBuffers:
         self.v_c = torch.zeros(nb * Hkv * cap * D, dtype=dt, device=device)
         self.cache_lens = torch.zeros(nb, dtype=torch.int32, device=device)
         self.indices = torch.zeros((nb, Hkv, B), dtype=torch.int32, device=device)
+        self.cal_indices = (torch.zeros((nb, Hkv, p.calib_size), dtype=torch.int32, device=device)
+                            if p.calib_size > 0 else None)
         self.c_q = torch.zeros((nb, Hq, D), dtype=torch.float32, device=device)
         self.c_out = torch.zeros((nb, Hq, D), dtype=torch.float32, device=device)
         self.c_lse = torch.zeros((nb, Hq), dtype=torch.float32, device=device)
@@ -215,7 +218,8 @@ class CompressBuffers:
     def compress(self, q_win, k, v, seq_offsets, q_cal=None, stream=None):
         calidrop_compress(self.p, q_win, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
                           q_cal, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
-                          self.indices, self.c_q, self.c_out, self.c_lse, self.ws_compress, stream)
+                          self.indices, self.cal_indices, self.c_q, self.c_out, self.c_lse,
+                          self.ws_compress, stream)
 
     def decode(self, q_t, stream=None, max_cache_len=None):
         calidrop_decode(self.p, q_t, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
@@ -228,8 +232,8 @@ class CompressBuffers:
             self.ws_recal = torch.empty(calidrop_recalibrate_workspace_bytes(self.p, self.max_seq_len),
                                         dtype=torch.uint8, device=self.out.device)
         calidrop_recalibrate(self.p, q_t, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
-                             self.indices, self.flags, self.a_lse, self.out, self.c_q, self.c_out,
-                             self.c_lse, self.ws_recal, stream)
+                             self.indices, self.cal_indices, self.flags, self.a_lse, self.out, self.c_q,
+                             self.c_out, self.c_lse, self.ws_recal, stream)
 
     def region(self, region: int) -> torch.Tensor:
         off, nbytes = calidrop_compress_workspace_region(self.p, self.total_tokens,

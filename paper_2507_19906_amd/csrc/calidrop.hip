@@ -31,11 +31,21 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+constexpr uint32_t kParamsSizeV1 = 48;      // layout up to theta2, without calib_size
+
+// Copies the caller's struct (either known layout) into `q` with every field defined.
+int load_params(const calidrop_params* in, calidrop_params* q) {
+  if (!in) return fail(CALIDROP_EINVAL, "params is NULL");
+  if (in->struct_size != sizeof(calidrop_params) && in->struct_size != kParamsSizeV1)
+    return fail(CALIDROP_EINVAL, "params.struct_size is %u, this library expects %zu (or %u)", in->struct_size,
+                sizeof(calidrop_params), kParamsSizeV1);
+  std::memset(q, 0, sizeof(*q));
+  std::memcpy(q, in, in->struct_size);
+  q->struct_size = sizeof(calidrop_params);
+  return CALIDROP_OK;
+}
+
 int check_params(const calidrop_params* p) {
-  if (!p) return fail(CALIDROP_EINVAL, "params is NULL");
-  if (p->struct_size != sizeof(calidrop_params))
-    return fail(CALIDROP_EINVAL, "params.struct_size is %u, this library expects %zu", p->struct_size,
-                sizeof(calidrop_params));
   if (p->dtype != CALIDROP_BF16 && p->dtype != CALIDROP_FP32)
     return fail(CALIDROP_EUNSUPPORTED, "dtype %d is not CALIDROP_BF16 or CALIDROP_FP32", p->dtype);
   if (p->batch < 1) return fail(CALIDROP_EINVAL, "batch must be >= 1 (got %d)", p->batch);
@@ -57,6 +67,7 @@ int check_params(const calidrop_params* p) {
     return fail(CALIDROP_EINVAL, "scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))");
   if (std::isnan(p->theta1) || std::isnan(p->theta2) || p->theta1 > p->theta2)
     return fail(CALIDROP_EINVAL, "thresholds must satisfy theta1 <= theta2 and not be NaN");
+  if (p->calib_size < 0) return fail(CALIDROP_EINVAL, "calib_size must be >= 0 (got %d)", p->calib_size);
   {  // launch grids put (sequence, KV head, row block) on one grid axis of at most 65535
     const int64_t nrb = (static_cast<int64_t>(p->n_q_heads / p->n_kv_heads) * p->window + cd::kRowBlock - 1) / cd::kRowBlock;
     if (static_cast<int64_t>(p->batch) * p->n_kv_heads * nrb > 65535 || p->n_q_heads > 65535)
@@ -161,7 +172,8 @@ template <typename T, int D>
 int compress_impl(const calidrop_params* p, const void* q_win, const void* k, const void* v,
                   const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, const void* q_cal,
                   void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
-                  float* c_q, float* c_out, float* c_lse, char* ws, const CompressLayout& L, hipStream_t st) {
+                  int32_t* cal_indices, float* c_q, float* c_out, float* c_lse, char* ws, const CompressLayout& L,
+                  hipStream_t st) {
   const int G = p->n_q_heads / p->n_kv_heads;
   const float sl2 = logit_scale(p) * cd::kLog2e;
   int rc;
@@ -199,6 +211,7 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   se.Hkv = p->n_kv_heads; se.w = p->window; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
   se.NRB = L.NRB; se.pool_k = p->pool_kernel; se.row_bytes = D * static_cast<int>(sizeof(T));
   se.vote = sa.vote; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
+  se.calib = p->calib_size; se.cal_indices = cal_indices;
   se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
   se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
   const int max_prefix = max_seq_len - p->window;
@@ -316,12 +329,14 @@ RecalLayout recal_layout(const calidrop_params* p, int32_t max_seq_len) {
 
 template <typename T, int D>
 int recal_impl(const calidrop_params* p, const void* q_t, const void* k, const void* v, const int32_t* seq_offsets,
-               int64_t total_tokens, int32_t max_seq_len, const int32_t* indices, uint8_t* flags, const float* a_lse,
-               void* out, float* c_q, float* c_out, float* c_lse, char* ws, const RecalLayout& L, hipStream_t st) {
+               int64_t total_tokens, int32_t max_seq_len, const int32_t* indices, const int32_t* cal_indices,
+               uint8_t* flags, const float* a_lse, void* out, float* c_q, float* c_out, float* c_lse, char* ws,
+               const RecalLayout& L, hipStream_t st) {
   const int G = p->n_q_heads / p->n_kv_heads;
   int rc;
   cd::BitmapArgs ba{};
-  ba.seq_off = seq_offsets; ba.indices = indices; ba.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
+  ba.seq_off = seq_offsets; ba.indices = indices; ba.cal_indices = cal_indices;
+  ba.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap); ba.calib = p->calib_size;
   ba.total_tokens = total_tokens; ba.batch = p->batch; ba.Hkv = p->n_kv_heads; ba.B = p->budget;
   ba.max_seq_len = max_seq_len; ba.W32 = L.W32;
   hipLaunchKernelGGL(cd::bitmap_from_indices_kernel, dim3(p->batch * p->n_kv_heads), dim3(256), 0, st, ba);
@@ -357,20 +372,26 @@ const char* calidrop_last_error(void) { return g_err; }
 int calidrop_version(void) { return 100; }
 void calidrop_set_inspection(int enabled) { g_inspection.store(enabled ? 1 : 0, std::memory_order_relaxed); }
 
-size_t calidrop_compress_workspace_bytes(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len) {
+size_t calidrop_compress_workspace_bytes(const calidrop_params* p_in, int64_t total_tokens, int32_t max_seq_len) {
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if (load_params(p_in, &pp) != CALIDROP_OK) return 0;
   if (check_params(p) != CALIDROP_OK || check_sizes(p, total_tokens, max_seq_len) != CALIDROP_OK) return 0;
   return compress_layout(p, total_tokens, max_seq_len).total;
 }
 
-size_t calidrop_decode_workspace_bytes(const calidrop_params* p, int32_t max_cache_len) {
+size_t calidrop_decode_workspace_bytes(const calidrop_params* p_in, int32_t max_cache_len) {
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if (load_params(p_in, &pp) != CALIDROP_OK) return 0;
   if (check_params(p) != CALIDROP_OK) return 0;
   if (max_cache_len < 1) { fail(CALIDROP_ESHAPE, "max_cache_len must be >= 1"); return 0; }
   return decode_layout(p, max_cache_len).total;
 }
 
-int calidrop_compress_workspace_region(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len,
+int calidrop_compress_workspace_region(const calidrop_params* p_in, int64_t total_tokens, int32_t max_seq_len,
                                        int32_t region, size_t* offset, size_t* bytes) {
   int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
   if ((rc = check_params(p))) return rc;
   if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
   if (!offset || !bytes) return fail(CALIDROP_EINVAL, "offset/bytes is NULL");
@@ -387,12 +408,14 @@ int calidrop_compress_workspace_region(const calidrop_params* p, int64_t total_t
   return CALIDROP_OK;
 }
 
-int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k, const void* v,
+int calidrop_compress(const calidrop_params* p_in, const void* q_win, const void* k, const void* v,
                       const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, const void* q_cal,
                       void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
-                      float* c_q, float* c_out, float* c_lse, void* workspace, size_t workspace_bytes,
-                      void* stream) {
+                      int32_t* cal_indices, float* c_q, float* c_out, float* c_lse, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
   if ((rc = check_params(p))) return rc;
   if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
   const struct { const void* ptr; const char* name; } req[] = {
@@ -404,6 +427,12 @@ int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k
   for (const auto& r : req)
     if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
   if (q_cal && !aligned16(q_cal)) return fail(CALIDROP_EALIGN, "q_cal is not 16-byte aligned");
+  if (p->calib_size > 0) {
+    if (!cal_indices) return fail(CALIDROP_EINVAL, "cal_indices is NULL although calib_size is %d", p->calib_size);
+    if (!aligned16(cal_indices)) return fail(CALIDROP_EALIGN, "cal_indices is not 16-byte aligned");
+  } else {
+    cal_indices = nullptr;
+  }
   const CompressLayout L = compress_layout(p, total_tokens, max_seq_len);
   if (!workspace || workspace_bytes < L.total)
     return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
@@ -413,7 +442,7 @@ int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k
   char* ws = static_cast<char*>(workspace);
 #define CD_DISPATCH(T, D)                                                                                       \
   return compress_impl<T, D>(p, q_win, k, v, seq_offsets, total_tokens, max_seq_len, q_cal, k_c, v_c,           \
-                             cache_offsets, cache_lens, indices, c_q, c_out, c_lse, ws, L, st)
+                             cache_offsets, cache_lens, indices, cal_indices, c_q, c_out, c_lse, ws, L, st)
   if (p->dtype == CALIDROP_BF16) {
     if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
     CD_DISPATCH(cd::bf16_t, 64);
@@ -423,11 +452,13 @@ int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k
 #undef CD_DISPATCH
 }
 
-int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, const void* v_c,
+int calidrop_decode(const calidrop_params* p_in, const void* q_t, const void* k_c, const void* v_c,
                     const int32_t* cache_offsets, const int32_t* cache_lens, int32_t max_cache_len,
                     const float* c_q, const float* c_out, const float* c_lse, void* out, float* a_lse,
                     uint8_t* flags, void* workspace, size_t workspace_bytes, void* stream) {
   int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
   if ((rc = check_params(p))) return rc;
   if (max_cache_len < 1) return fail(CALIDROP_ESHAPE, "max_cache_len must be >= 1 (got %d)", max_cache_len);
   const struct { const void* ptr; const char* name; } req[] = {
@@ -456,17 +487,22 @@ int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, 
 #undef CD_DISPATCH
 }
 
-size_t calidrop_recalibrate_workspace_bytes(const calidrop_params* p, int32_t max_seq_len) {
+size_t calidrop_recalibrate_workspace_bytes(const calidrop_params* p_in, int32_t max_seq_len) {
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if (load_params(p_in, &pp) != CALIDROP_OK) return 0;
   if (check_params(p) != CALIDROP_OK) return 0;
   if (max_seq_len < 1) { fail(CALIDROP_ESHAPE, "max_seq_len must be >= 1"); return 0; }
   return recal_layout(p, max_seq_len).total;
 }
 
-int calidrop_recalibrate(const calidrop_params* p, const void* q_t, const void* k, const void* v,
+int calidrop_recalibrate(const calidrop_params* p_in, const void* q_t, const void* k, const void* v,
                          const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
-                         const int32_t* indices, uint8_t* flags, const float* a_lse, void* out, float* c_q,
-                         float* c_out, float* c_lse, void* workspace, size_t workspace_bytes, void* stream) {
+                         const int32_t* indices, const int32_t* cal_indices, uint8_t* flags, const float* a_lse,
+                         void* out, float* c_q, float* c_out, float* c_lse, void* workspace, size_t workspace_bytes,
+                         void* stream) {
   int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
   if ((rc = check_params(p))) return rc;
   if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
   const struct { const void* ptr; const char* name; } req[] = {
@@ -476,6 +512,12 @@ int calidrop_recalibrate(const calidrop_params* p, const void* q_t, const void* 
     if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
   for (const auto& r : req)
     if (r.ptr != flags && !aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  if (p->calib_size > 0) {
+    if (!cal_indices) return fail(CALIDROP_EINVAL, "cal_indices is NULL although calib_size is %d", p->calib_size);
+    if (!aligned16(cal_indices)) return fail(CALIDROP_EALIGN, "cal_indices is not 16-byte aligned");
+  } else {
+    cal_indices = nullptr;
+  }
   const RecalLayout L = recal_layout(p, max_seq_len);
   if (!workspace || workspace_bytes < L.total)
     return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
@@ -484,8 +526,8 @@ int calidrop_recalibrate(const calidrop_params* p, const void* q_t, const void* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
 #define CD_DISPATCH(T, D)                                                                                        \
-  return recal_impl<T, D>(p, q_t, k, v, seq_offsets, total_tokens, max_seq_len, indices, flags, a_lse, out, c_q, \
-                          c_out, c_lse, ws, L, st)
+  return recal_impl<T, D>(p, q_t, k, v, seq_offsets, total_tokens, max_seq_len, indices, cal_indices, flags, a_lse, \
+                          out, c_q, c_out, c_lse, ws, L, st)
   if (p->dtype == CALIDROP_BF16) {
     if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
     CD_DISPATCH(cd::bf16_t, 64);

@@ -387,12 +387,13 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
 }
 
 struct BitmapArgs {
-  const int32_t* seq_off; const int32_t* indices; uint32_t* bitmap;
+  const int32_t* seq_off; const int32_t* indices; const int32_t* cal_indices; uint32_t* bitmap;
   int64_t total_tokens;
-  int batch, Hkv, B, max_seq_len, W32;
+  int batch, Hkv, B, calib, max_seq_len, W32;
 };
 
-// Rebuild the not-evicted bitmap of every (sequence, KV head) from the retained index list.
+// Rebuild the skip bitmap of the calibration pass for every (sequence, KV head): either "not
+// evicted" from the retained index list, or "not in the calibration set" from that set's list.
 __global__ __launch_bounds__(256) void bitmap_from_indices_kernel(BitmapArgs a) {
   const int bg = blockIdx.x;
   const int b = bg / a.Hkv;
@@ -400,13 +401,22 @@ __global__ __launch_bounds__(256) void bitmap_from_indices_kernel(BitmapArgs a) 
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   uint32_t* bm = a.bitmap + static_cast<int64_t>(bg) * a.W32;
   const int words = (n + 31) / 32;
-  for (int wd = threadIdx.x; wd < words; wd += 256) bm[wd] = 0u;
+  const bool from_cal = a.cal_indices != nullptr && a.calib > 0;
+  for (int wd = threadIdx.x; wd < words; wd += 256) bm[wd] = from_cal ? 0xFFFFFFFFu : 0u;
   __threadfence();
   __syncthreads();
-  const int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
-  for (int r = threadIdx.x; r < a.B; r += 256) {
-    const int pos = idx[r];
-    if (pos >= 0 && pos < n) atomicOr(&bm[pos >> 5], 1u << (pos & 31));
+  if (from_cal) {
+    const int32_t* cal = a.cal_indices + static_cast<int64_t>(bg) * a.calib;
+    for (int r = threadIdx.x; r < a.calib; r += 256) {
+      const int pos = cal[r];
+      if (pos >= 0 && pos < n) atomicAnd(&bm[pos >> 5], ~(1u << (pos & 31)));
+    }
+  } else {
+    const int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
+    for (int r = threadIdx.x; r < a.B; r += 256) {
+      const int pos = idx[r];
+      if (pos >= 0 && pos < n) atomicOr(&bm[pos >> 5], 1u << (pos & 31));
+    }
   }
 }
 

@@ -1,12 +1,15 @@
-// Pooling, per-KV-head top-k of the pooled scores (the selection inside Alg. 1 step 3) and
-// the gather of KV_compress, one workgroup per (sequence, KV head).
+// Pooling, per-KV-head top-k of the pooled scores (the selection inside Alg. 1 step 3), the
+// optional "calibration size" cut of the evicted tokens (Sec. 5.3) and the gather of
+// KV_compress, one workgroup per (sequence, KV head).
 //
 // Selection is exact: a most-significant-digit-first radix select on the fp32 bit patterns
-// (scores are >= 0, so unsigned order equals numeric order) finds the k_sel-th largest value
-// and how many entries equal to it are kept; an ordered compaction then keeps everything
-// above it plus the first equal entries in position order - the "ties to the lower index"
-// rule - and emits positions in ascending order.  Integer work only: bit-exact and
-// deterministic.
+// (scores are >= 0, so unsigned order equals numeric order) finds the value of a given rank
+// and how many entries equal to it fall inside the rank; an ordered compaction then keeps
+// everything above it plus the first equal entries in position order - the "ties to the lower
+// index" rule - and emits positions in ascending order.  Integer work only: bit-exact and
+// deterministic.  Two ranks are used: k_sel = B - w (the retained prefix tokens) and, when a
+// calibration size m is set, k_sel + m (retained + the m most important evicted tokens, which
+// form the calibration set; everything below is dropped for good).
 //
 // Two variants: select_gather_lds_kernel (prefix up to 32768 positions: pools the votes itself,
 // keys in registers) and select_gather_kernel (longer prefixes: keys read from the pooled-score
@@ -21,161 +24,95 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelPerThread = 32;              // LDS variant: positions per thread (= one bitmap word)
 constexpr int kSelMaxLdsKeys = kSelThreads * kSelPerThread;   // longest prefix the LDS variant takes
 constexpr int kSelMaxPool = 15;                // widest pooling kernel the LDS variant takes
-constexpr int kSelLdsBytes = (kSelMaxLdsKeys + kSelMaxLdsKeys / 32) * 4;   // votes, 1 pad word per 32
 
 struct SelectArgs {
   const int32_t* seq_off;
   const int32_t* cache_off;
   int64_t total_tokens;
   int batch, Hkv, w, B, max_seq_len, W32, NRB, pool_k, row_bytes;
+  int calib;               // calibration size m (0 = every evicted token)
   int write_scores;        // LDS variant: also store the pooled scores (inspection only)
   const float* vote;       // [NRB][total_tokens*Hkv]   (LDS-key variant pools these itself)
   float* score;            // [total_tokens*Hkv] pooled scores: written (LDS variant) or read
   int32_t* indices;        // [batch][Hkv][B]
+  int32_t* cal_indices;    // [batch][Hkv][calib] positions of the calibration set, or NULL
   int32_t* cache_lens;     // [batch]
-  uint32_t* bitmap;        // [batch*Hkv][W32]: bit set = position is NOT evicted
+  uint32_t* bitmap;        // [batch*Hkv][W32]: bit set = position is NOT in the calibration set
   const void* k; const void* v; void* k_c; void* v_c;
 };
 
-// Variant for prefixes too long for LDS: the pooled scores are read from the buffer that
-// pool_scores_kernel wrote, position j of a sweep handled by thread j mod 1024.
-__global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a) {
-  const int bg = blockIdx.x;
-  const int g = bg % a.Hkv;
-  const int b = bg / a.Hkv;
+struct RadixShared {
+  uint32_t hist[256];
+  uint32_t prefix, remaining;
+};
+
+// Radix select of the `rank`-th largest key (rank >= 1, at most the number of keys).
+// `for_each_key(visit)` must call visit(u) once for every key this thread owns.  On return
+// thr = that key's bit pattern and need_eq = how many keys equal to thr lie within the rank.
+// Must be called by every thread of the workgroup.
+template <int NT, typename ForEach>
+__device__ __forceinline__ void radix_select(RadixShared& sh, uint32_t rank, ForEach&& for_each_key, uint32_t& thr,
+                                             uint32_t& need_eq) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  int off0;
-  const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
-  int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
-  const int len = min(n, a.B);
-  if (g == 0 && tid == 0) a.cache_lens[b] = len;
-  const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
-
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t s_prefix, s_remaining;
-  __shared__ uint32_t wave_gt[kSelThreads / 64], wave_eq[kSelThreads / 64];
-
-  if (n <= a.B) {                       // nothing to evict: keep every position
-    for (int r = tid; r < a.B; r += kSelThreads) idx[r] = (r < n) ? r : -1;
-  } else {
-    const int P = n - a.w;
-    const int k_sel = a.B - a.w;
-    const uint32_t* gkey = reinterpret_cast<const uint32_t*>(a.score) + head_tok;
-    auto key_at = [&](int j) -> uint32_t { return gkey[j]; };
-
-    // ---- radix select: 4 digits of 8 bits, most significant first -----------------------
-    uint32_t prefix = 0;            // bits decided so far (the high bits of the threshold)
-    uint32_t remaining = k_sel;     // rank of the threshold among the keys matching `prefix`
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      const uint32_t himask = (pass == 0) ? 0u : (0xFFFFFFFFu << (shift + 8));
-      if (tid < 256) hist[tid] = 0;
-      __syncthreads();
-      {
-        // run-length compressed updates (scores share their leading digits); 8 independent
-        // loads per thread are in flight at a time
-        uint32_t run_bin = 0, run_len = 0;
-        for (int j0 = tid; j0 < P; j0 += 8 * kSelThreads) {
-          uint32_t u[8];
-#pragma unroll
-          for (int q = 0; q < 8; ++q) u[q] = (j0 + q * kSelThreads < P) ? key_at(j0 + q * kSelThreads) : 0u;
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            if (j0 + q * kSelThreads < P && (u[q] & himask) == prefix) {
-              const uint32_t bin = (u[q] >> shift) & 0xFF;
-              if (bin != run_bin && run_len) { atomicAdd(&hist[run_bin], run_len); run_len = 0; }
-              run_bin = bin;
-              ++run_len;
-            }
-          }
-        }
-        if (run_len) atomicAdd(&hist[run_bin], run_len);
-      }
-      __syncthreads();
-      if (wv == 0) {
-        // lane t owns bins 4t..4t+3; find the bin where the count from the top reaches `remaining`
-        const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-        const uint32_t mine = h0 + h1 + h2 + h3;
-        uint32_t acc = mine;
-#pragma unroll
-        for (int s = 1; s < 64; s <<= 1) {        // suffix-inclusive scan over lanes
-          const uint32_t o = __shfl_down(acc, s);
-          if (lane + s < 64) acc += o;
-        }
-        const uint32_t above = acc - mine;        // keys in bins owned by higher lanes
-        if (above < remaining && remaining <= acc) {      // exactly one lane
-          uint32_t cum = above;
-          int bin;
-          if (cum + h3 >= remaining) bin = 3;
-          else { cum += h3; if (cum + h2 >= remaining) bin = 2;
-            else { cum += h2; if (cum + h1 >= remaining) bin = 1; else { cum += h1; bin = 0; } } }
-          s_prefix = prefix | (static_cast<uint32_t>(4 * lane + bin) << shift);
-          s_remaining = remaining - cum;
-        }
-      }
-      __syncthreads();
-      prefix = s_prefix;
-      remaining = s_remaining;
-      __syncthreads();
-    }
-    const uint32_t thr = prefix;          // bit pattern of the k_sel-th largest score
-    const uint32_t need_eq = remaining;   // how many entries equal to thr are kept (>= 1)
-
-    // ---- ordered compaction + retained bitmap: wave w owns the contiguous positions
-    //      [w*seg, (w+1)*seg); one counting sweep, one barrier, one emitting sweep --------------
-    uint32_t* bm = a.bitmap + static_cast<int64_t>(bg) * a.W32;
-    constexpr int NWV = kSelThreads / 64;
-    const int seg = ((n + NWV - 1) / NWV + 63) / 64 * 64;
-    const int seg_lo = wv * seg, seg_hi = min(n, seg_lo + seg);
-    const int key_hi = min(P, seg_hi);    // candidates of this wave: prefix positions of its segment
-    uint32_t cnt_gt = 0, cnt_eq = 0;
-    for (int base = seg_lo; base < seg_hi; base += 4 * 64) {
-      uint32_t u[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? key_at(j) : 0u; }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int j = base + q * 64 + lane;
-        cnt_gt += __popcll(__ballot(j < key_hi && u[q] > thr));
-        cnt_eq += __popcll(__ballot(j < key_hi && u[q] == thr));
-      }
-    }
-    if (lane == 0) { wave_gt[wv] = cnt_gt; wave_eq[wv] = cnt_eq; }
+  uint32_t prefix = 0;            // bits decided so far (the high bits of the answer)
+  uint32_t remaining = rank;      // rank of the answer among the keys matching `prefix`
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const uint32_t himask = (pass == 0) ? 0u : (0xFFFFFFFFu << (shift + 8));
+    for (int t = tid; t < 256; t += NT) sh.hist[t] = 0;
     __syncthreads();
-    uint32_t pre_gt = 0, pre_eq = 0;      // counts over all earlier positions (wave-uniform)
-    for (int ww = 0; ww < wv; ++ww) { pre_gt += wave_gt[ww]; pre_eq += wave_eq[ww]; }
-    const uint64_t below = (1ull << lane) - 1ull;
-    for (int base = seg_lo; base < seg_hi; base += 4 * 64) {
-      uint32_t u[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? key_at(j) : 0u; }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int j = base + q * 64 + lane;
-        if (base + q * 64 < seg_hi) {
-          const bool gt = j < key_hi && u[q] > thr;
-          const bool eq = j < key_hi && u[q] == thr;
-          const uint64_t mgt = __ballot(gt), meq = __ballot(eq);
-          const uint32_t my_eq = pre_eq + __popcll(meq & below);
-          const bool keep = gt || (eq && my_eq < need_eq);
-          if (keep) idx[pre_gt + __popcll(mgt & below) + min(my_eq, need_eq)] = j;
-          // bit = not evicted: selected prefix positions and everything from the window on
-          const uint64_t mk = __ballot(keep || j >= P);
-          if (lane == 0) {
-            bm[(base + q * 64) >> 5] = static_cast<uint32_t>(mk);
-            bm[((base + q * 64) >> 5) + 1] = static_cast<uint32_t>(mk >> 32);
-          }
-          pre_gt += __popcll(mgt);
-          pre_eq += __popcll(meq);
+    {
+      // run-length compressed updates: scores share their leading digits, so consecutive keys
+      // of a thread mostly fall in the same bin and only bin changes touch the histogram
+      uint32_t run_bin = 0, run_len = 0;
+      for_each_key([&](uint32_t u) {
+        if ((u & himask) == prefix) {
+          const uint32_t bin = (u >> shift) & 0xFF;
+          if (bin != run_bin && run_len) { atomicAdd(&sh.hist[run_bin], run_len); run_len = 0; }
+          run_bin = bin;
+          ++run_len;
         }
+      });
+      if (run_len) atomicAdd(&sh.hist[run_bin], run_len);
+    }
+    __syncthreads();
+    if (wv == 0) {
+      // lane t owns bins 4t..4t+3; find the bin where the count from the top reaches `remaining`
+      const uint32_t h0 = sh.hist[4 * lane], h1 = sh.hist[4 * lane + 1], h2 = sh.hist[4 * lane + 2],
+                     h3 = sh.hist[4 * lane + 3];
+      const uint32_t mine = h0 + h1 + h2 + h3;
+      uint32_t acc = mine;
+#pragma unroll
+      for (int s = 1; s < 64; s <<= 1) {        // suffix-inclusive scan over lanes
+        const uint32_t o = __shfl_down(acc, s);
+        if (lane + s < 64) acc += o;
+      }
+      const uint32_t above = acc - mine;        // keys in bins owned by higher lanes
+      if (above < remaining && remaining <= acc) {      // exactly one lane
+        uint32_t cum = above;
+        int bin;
+        if (cum + h3 >= remaining) bin = 3;
+        else { cum += h3; if (cum + h2 >= remaining) bin = 2;
+          else { cum += h2; if (cum + h1 >= remaining) bin = 1; else { cum += h1; bin = 0; } } }
+        sh.prefix = prefix | (static_cast<uint32_t>(4 * lane + bin) << shift);
+        sh.remaining = remaining - cum;
       }
     }
-    for (int r = tid; r < a.w; r += kSelThreads) idx[k_sel + r] = P + r;   // the window is always kept
+    __syncthreads();
+    prefix = sh.prefix;
+    remaining = sh.remaining;
+    __syncthreads();
   }
+  thr = prefix;
+  need_eq = remaining;
+}
 
-  // ---- gather: K_c[g][r] = K[g][idx[g][r]], V likewise; 16 bytes per thread per step -------
-  __threadfence_block();
-  __syncthreads();                       // idx[] written above is read back by other threads
+// K_c[g][r] = K[g][idx[r]], V likewise, for r < len; 16 bytes per thread per copy, 8 independent
+// copies in flight per thread.  `idx` may live in LDS or in global memory.
+template <int NT>
+__device__ __forceinline__ void gather_rows(const SelectArgs& a, const int32_t* idx, int len, int b, int g,
+                                            int64_t head_tok) {
+  const int tid = threadIdx.x;
   const int c0 = a.cache_off[b];
   const int cap = a.cache_off[b + 1] - c0;
   if (cap < len) return;                 // capacity contract broken: write nothing
@@ -185,37 +122,157 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
   const int64_t dst_head = (static_cast<int64_t>(c0) * a.Hkv + static_cast<int64_t>(g) * cap) * a.row_bytes;
   char* kdst = static_cast<char*>(a.k_c) + dst_head;
   char* vdst = static_cast<char*>(a.v_c) + dst_head;
-  constexpr int kBatch = 8;              // independent row copies in flight per thread
+  constexpr int kBatch = 8;
   const int total = len * vec_per_row;
-  for (int t0 = tid; t0 < total; t0 += kBatch * kSelThreads) {
-    int src[kBatch];
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int t = t0 + u * kSelThreads;
-      src[u] = (t < total) ? idx[t / vec_per_row] : 0;
-    }
+  for (int t0 = tid; t0 < total; t0 += kBatch * NT) {
     u32x4 kk[kBatch], vv[kBatch];
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
-      const int t = t0 + u * kSelThreads;
-      const int vcol = t % vec_per_row;
-      const int64_t so = static_cast<int64_t>(src[u]) * a.row_bytes + vcol * 16;
-      if (t < total) { kk[u] = ld16(ksrc + so); vv[u] = ld16(vsrc + so); }
+      const int t = t0 + u * NT;
+      if (t < total) {
+        const int64_t so = static_cast<int64_t>(idx[t / vec_per_row]) * a.row_bytes + (t % vec_per_row) * 16;
+        kk[u] = ld16(ksrc + so);
+        vv[u] = ld16(vsrc + so);
+      }
     }
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
-      const int t = t0 + u * kSelThreads;
+      const int t = t0 + u * NT;
       const int64_t dof = static_cast<int64_t>(t / vec_per_row) * a.row_bytes + (t % vec_per_row) * 16;
       if (t < total) { st16(kdst + dof, kk[u]); st16(vdst + dof, vv[u]); }
     }
   }
 }
 
+// Membership of one candidate, given how many greater / equal keys precede it in position order.
+struct Cut {
+  uint32_t thr, need_eq;
+  bool all;              // no cut: every candidate is inside
+  __device__ __forceinline__ bool inside(uint32_t u, uint32_t eq_before) const {
+    return all || u > thr || (u == thr && eq_before < need_eq);
+  }
+  // number of inside candidates among the first `pos` positions, from the running counts
+  __device__ __forceinline__ uint32_t rank(uint32_t pos, uint32_t gt_before, uint32_t eq_before) const {
+    return all ? pos : gt_before + min(eq_before, need_eq);
+  }
+};
+
+// Variant for prefixes too long for LDS: the pooled scores are read from the buffer that
+// pool_scores_kernel wrote.  The radix sweeps are strided (thread j mod 1024); the compaction
+// gives wave w the contiguous positions [w*seg, (w+1)*seg): a counting sweep, one barrier, an
+// emitting sweep.
+__global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a) {
+  const int bg = blockIdx.x;
+  const int g = bg % a.Hkv;
+  const int b = bg / a.Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int off0;
+  const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
+  int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
+  int32_t* cal = (a.cal_indices && a.calib > 0) ? a.cal_indices + static_cast<int64_t>(bg) * a.calib : nullptr;
+  const int len = min(n, a.B);
+  if (g == 0 && tid == 0) a.cache_lens[b] = len;
+  const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
+
+  __shared__ RadixShared sh;
+  constexpr int NWV = kSelThreads / 64;
+  __shared__ uint32_t wave_cnt[4][NWV];      // greater/equal counts for the two cuts, per wave
+
+  if (n <= a.B) {                       // nothing to evict: keep every position
+    for (int r = tid; r < a.B; r += kSelThreads) idx[r] = (r < n) ? r : -1;
+    if (cal) for (int r = tid; r < a.calib; r += kSelThreads) cal[r] = -1;
+  } else {
+    const int P = n - a.w;
+    const int k_sel = a.B - a.w;
+    const uint32_t* gkey = reinterpret_cast<const uint32_t*>(a.score) + head_tok;
+    auto each_key = [&](auto&& visit) {          // 8 independent loads per thread in flight
+      for (int j0 = tid; j0 < P; j0 += 8 * kSelThreads) {
+        uint32_t u[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) u[q] = (j0 + q * kSelThreads < P) ? gkey[j0 + q * kSelThreads] : 0u;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          if (j0 + q * kSelThreads < P) visit(u[q]);
+      }
+    };
+    Cut c1, c2;                          // c1: retained prefix tokens; c2: retained + calibration set
+    c1.all = false;
+    radix_select<kSelThreads>(sh, k_sel, each_key, c1.thr, c1.need_eq);
+    c2.all = a.calib <= 0 || k_sel + a.calib >= P;
+    c2.thr = 0; c2.need_eq = 0;
+    if (!c2.all) radix_select<kSelThreads>(sh, k_sel + a.calib, each_key, c2.thr, c2.need_eq);
+
+    uint32_t* bm = a.bitmap + static_cast<int64_t>(bg) * a.W32;
+    const int seg = ((n + NWV - 1) / NWV + 63) / 64 * 64;
+    const int seg_lo = wv * seg, seg_hi = min(n, seg_lo + seg);
+    const int key_hi = min(P, seg_hi);    // candidates of this wave: prefix positions of its segment
+    uint32_t cnt[4] = {0, 0, 0, 0};       // gt1, eq1, gt2, eq2 of this wave's segment
+    for (int base = seg_lo; base < seg_hi; base += 4 * 64) {
+      uint32_t u[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? gkey[j] : 0u; }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const bool in = base + q * 64 + lane < key_hi;
+        cnt[0] += __popcll(__ballot(in && u[q] > c1.thr));
+        cnt[1] += __popcll(__ballot(in && u[q] == c1.thr));
+        cnt[2] += __popcll(__ballot(in && u[q] > c2.thr));
+        cnt[3] += __popcll(__ballot(in && u[q] == c2.thr));
+      }
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) wave_cnt[q][wv] = cnt[q];
+    }
+    __syncthreads();
+    uint32_t pre[4] = {0, 0, 0, 0};       // counts over all earlier positions (wave-uniform)
+    for (int ww = 0; ww < wv; ++ww)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) pre[q] += wave_cnt[q][ww];
+    const uint64_t below = (1ull << lane) - 1ull;
+    for (int base = seg_lo; base < seg_hi; base += 4 * 64) {
+      uint32_t u[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? gkey[j] : 0u; }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int j = base + q * 64 + lane;
+        if (base + q * 64 < seg_hi) {
+          const bool in = j < key_hi;
+          const uint64_t m0 = __ballot(in && u[q] > c1.thr), m1 = __ballot(in && u[q] == c1.thr);
+          const uint64_t m2 = __ballot(in && u[q] > c2.thr), m3 = __ballot(in && u[q] == c2.thr);
+          const uint32_t gt1 = pre[0] + __popcll(m0 & below), eq1 = pre[1] + __popcll(m1 & below);
+          const uint32_t gt2 = pre[2] + __popcll(m2 & below), eq2 = pre[3] + __popcll(m3 & below);
+          const bool keep = in && c1.inside(u[q], eq1);
+          const bool calib = in && !keep && c2.inside(u[q], eq2);
+          if (keep) idx[c1.rank(j, gt1, eq1)] = j;
+          if (calib && cal) cal[c2.rank(j, gt2, eq2) - c1.rank(j, gt1, eq1)] = j;
+          // bit = skip in the calibration pass: everything that is not in the calibration set
+          const uint64_t mk = __ballot(!calib);
+          if (lane == 0) {
+            bm[(base + q * 64) >> 5] = static_cast<uint32_t>(mk);
+            bm[((base + q * 64) >> 5) + 1] = static_cast<uint32_t>(mk >> 32);
+          }
+          pre[0] += __popcll(m0); pre[1] += __popcll(m1); pre[2] += __popcll(m2); pre[3] += __popcll(m3);
+        }
+      }
+    }
+    for (int r = tid; r < a.w; r += kSelThreads) idx[k_sel + r] = P + r;   // the window is always kept
+    if (cal) {                                                              // pad a short calibration set
+      const int n_cal = min(a.calib, P - k_sel);
+      for (int r = n_cal + tid; r < a.calib; r += kSelThreads) cal[r] = -1;
+    }
+  }
+  __threadfence_block();
+  __syncthreads();                       // idx[] written above is read back by other threads
+  gather_rows<kSelThreads>(a, idx, len, b, g, head_tok);
+}
+
 // LDS variant for prefixes of up to 32 * NT positions (NT = 256, 512 or 1024 threads; the
 // smaller workgroups let two or four heads share a compute unit).  Thread t owns positions
 // 32t..32t+31: their pooled scores live in its registers for the radix passes and the
-// compaction, and their retained bits are exactly bitmap word t.  The votes are staged once in
-// LDS (padded by one word per 32 so that the stride-32 accesses do not collide), and the same
+// compaction, and their bits are exactly bitmap word t.  The votes are staged once in LDS
+// (padded by one word per 32 so that the stride-32 accesses do not collide), and the same
 // LDS later holds the retained indices for the gather.
 template <int NT>
 __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
@@ -229,13 +286,13 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
+  int32_t* cal = (a.cal_indices && a.calib > 0) ? a.cal_indices + static_cast<int64_t>(bg) * a.calib : nullptr;
   const int len = min(n, a.B);
   if (g == 0 && tid == 0) a.cache_lens[b] = len;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
 
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t s_prefix, s_remaining;
-  __shared__ uint32_t wave_tot[NT / 64];
+  __shared__ RadixShared sh;
+  __shared__ uint32_t wave_tot[2][NT / 64];
   constexpr int PER = kSelPerThread;
   auto pad = [](int j) { return j + (j >> 5); };
 
@@ -244,6 +301,7 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
       idx[r] = (r < n) ? r : -1;
       if (r < n) s_idx[r] = r;
     }
+    if (cal) for (int r = tid; r < a.calib; r += NT) cal[r] = -1;
   } else {
     const int P = n - a.w;
     const int k_sel = a.B - a.w;
@@ -310,126 +368,66 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
         }
       }
     }
-    // ---- radix select: 4 digits of 8 bits, most significant first ---------------------------
-    uint32_t prefix = 0;            // bits decided so far (the high bits of the threshold)
-    uint32_t remaining = k_sel;     // rank of the threshold among the keys matching `prefix`
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      const uint32_t himask = (pass == 0) ? 0u : (0xFFFFFFFFu << (shift + 8));
-      if (tid < 256) hist[tid] = 0;
-      __syncthreads();
-      {
-        // run-length compressed updates: neighbouring pooled scores share their leading digits
-        uint32_t run_bin = 0, run_len = 0;
+    auto each_key = [&](auto&& visit) {
 #pragma unroll
-        for (int u = 0; u < PER; ++u) {
-          if (j0 + u < P && (key[u] & himask) == prefix) {
-            const uint32_t bin = (key[u] >> shift) & 0xFF;
-            if (bin != run_bin && run_len) { atomicAdd(&hist[run_bin], run_len); run_len = 0; }
-            run_bin = bin;
-            ++run_len;
-          }
-        }
-        if (run_len) atomicAdd(&hist[run_bin], run_len);
-      }
-      __syncthreads();
-      if (wv == 0) {
-        // lane t owns bins 4t..4t+3; find the bin where the count from the top reaches `remaining`
-        const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-        const uint32_t mine = h0 + h1 + h2 + h3;
-        uint32_t acc = mine;
-#pragma unroll
-        for (int s = 1; s < 64; s <<= 1) {        // suffix-inclusive scan over lanes
-          const uint32_t o = __shfl_down(acc, s);
-          if (lane + s < 64) acc += o;
-        }
-        const uint32_t above = acc - mine;        // keys in bins owned by higher lanes
-        if (above < remaining && remaining <= acc) {      // exactly one lane
-          uint32_t cum = above;
-          int bin;
-          if (cum + h3 >= remaining) bin = 3;
-          else { cum += h3; if (cum + h2 >= remaining) bin = 2;
-            else { cum += h2; if (cum + h1 >= remaining) bin = 1; else { cum += h1; bin = 0; } } }
-          s_prefix = prefix | (static_cast<uint32_t>(4 * lane + bin) << shift);
-          s_remaining = remaining - cum;
-        }
-      }
-      __syncthreads();
-      prefix = s_prefix;
-      remaining = s_remaining;
-      __syncthreads();
-    }
-    const uint32_t thr = prefix;          // bit pattern of the k_sel-th largest score
-    const uint32_t need_eq = remaining;   // how many entries equal to thr are kept (>= 1)
+      for (int u = 0; u < PER; ++u)
+        if (j0 + u < P) visit(key[u]);
+    };
+    Cut c1, c2;                          // c1: retained prefix tokens; c2: retained + calibration set
+    c1.all = false;
+    radix_select<NT>(sh, k_sel, each_key, c1.thr, c1.need_eq);
+    c2.all = a.calib <= 0 || k_sel + a.calib >= P;
+    c2.thr = 0; c2.need_eq = 0;
+    if (!c2.all) radix_select<NT>(sh, k_sel + a.calib, each_key, c2.thr, c2.need_eq);
 
-    // ---- ordered compaction: exclusive scan of per-thread (greater, equal) counts -----------
-    uint32_t cnt = 0;                     // greater in the low half, equal in the high half
+    // ---- ordered compaction: exclusive scans of the per-thread (greater, equal) counts of
+    //      both cuts, greater in the low half-word and equal in the high half-word -------------
+    uint32_t cnt1 = 0, cnt2 = 0;
 #pragma unroll
     for (int u = 0; u < PER; ++u)
-      if (j0 + u < P) cnt += (key[u] > thr ? 1u : 0u) + (key[u] == thr ? 0x10000u : 0u);
-    uint32_t incl = cnt;
+      if (j0 + u < P) {
+        cnt1 += (key[u] > c1.thr ? 1u : 0u) + (key[u] == c1.thr ? 0x10000u : 0u);
+        cnt2 += (key[u] > c2.thr ? 1u : 0u) + (key[u] == c2.thr ? 0x10000u : 0u);
+      }
+    uint32_t inc1 = cnt1, inc2 = cnt2;
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) {
-      const uint32_t o = __shfl_up(incl, s);
-      if (lane >= s) incl += o;
+      const uint32_t o1 = __shfl_up(inc1, s), o2 = __shfl_up(inc2, s);
+      if (lane >= s) { inc1 += o1; inc2 += o2; }
     }
-    if (lane == 63) wave_tot[wv] = incl;
+    if (lane == 63) { wave_tot[0][wv] = inc1; wave_tot[1][wv] = inc2; }
     __syncthreads();                      // also: every thread is done reading the staged votes
-    uint32_t before = incl - cnt;
-    for (int ww = 0; ww < wv; ++ww) before += wave_tot[ww];
-    uint32_t pre_gt = before & 0xFFFFu, pre_eq = before >> 16;
+    uint32_t bef1 = inc1 - cnt1, bef2 = inc2 - cnt2;
+    for (int ww = 0; ww < wv; ++ww) { bef1 += wave_tot[0][ww]; bef2 += wave_tot[1][ww]; }
+    uint32_t gt1 = bef1 & 0xFFFFu, eq1 = bef1 >> 16, gt2 = bef2 & 0xFFFFu, eq2 = bef2 >> 16;
     uint32_t word = 0;
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
       const int j = j0 + u;
       const bool in = j < P;
-      const bool gt = in && key[u] > thr;
-      const bool eq = in && key[u] == thr;
-      const bool keep = gt || (eq && pre_eq < need_eq);
+      const bool keep = in && c1.inside(key[u], eq1);
+      const bool calib = in && !keep && c2.inside(key[u], eq2);
       if (keep) {
-        const uint32_t pos = pre_gt + min(pre_eq, need_eq);
+        const uint32_t pos = c1.rank(j, gt1, eq1);
         idx[pos] = j;
         s_idx[pos] = j;
       }
-      pre_gt += gt ? 1u : 0u;
-      pre_eq += eq ? 1u : 0u;
-      word |= ((keep || !in) ? 1u : 0u) << u;       // bit = not evicted (window and beyond count as kept)
+      if (calib && cal) cal[c2.rank(j, gt2, eq2) - c1.rank(j, gt1, eq1)] = j;
+      if (in) {
+        gt1 += key[u] > c1.thr; eq1 += key[u] == c1.thr;
+        gt2 += key[u] > c2.thr; eq2 += key[u] == c2.thr;
+      }
+      word |= (calib ? 0u : 1u) << u;       // bit = skip in the calibration pass
     }
     if (j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + tid] = word;
     for (int r = tid; r < a.w; r += NT) { idx[k_sel + r] = P + r; s_idx[k_sel + r] = P + r; }
+    if (cal) {                                                              // pad a short calibration set
+      const int n_cal = min(a.calib, P - k_sel);
+      for (int r = n_cal + tid; r < a.calib; r += NT) cal[r] = -1;
+    }
   }
-
-  // ---- gather: K_c[g][r] = K[g][idx[g][r]], V likewise; 16 bytes per thread per copy ---------
   __syncthreads();
-  const int c0 = a.cache_off[b];
-  const int cap = a.cache_off[b + 1] - c0;
-  if (cap < len) return;                 // capacity contract broken: write nothing
-  const int vec_per_row = a.row_bytes / 16;
-  const char* ksrc = static_cast<const char*>(a.k) + head_tok * a.row_bytes;
-  const char* vsrc = static_cast<const char*>(a.v) + head_tok * a.row_bytes;
-  const int64_t dst_head = (static_cast<int64_t>(c0) * a.Hkv + static_cast<int64_t>(g) * cap) * a.row_bytes;
-  char* kdst = static_cast<char*>(a.k_c) + dst_head;
-  char* vdst = static_cast<char*>(a.v_c) + dst_head;
-  constexpr int kBatch = 8;              // independent row copies in flight per thread
-  const int total = len * vec_per_row;
-  for (int t0 = tid; t0 < total; t0 += kBatch * NT) {
-    u32x4 kk[kBatch], vv[kBatch];
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int t = t0 + u * NT;
-      if (t < total) {
-        const int64_t so = static_cast<int64_t>(s_idx[t / vec_per_row]) * a.row_bytes + (t % vec_per_row) * 16;
-        kk[u] = ld16(ksrc + so);
-        vv[u] = ld16(vsrc + so);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int t = t0 + u * NT;
-      const int64_t dof = static_cast<int64_t>(t / vec_per_row) * a.row_bytes + (t % vec_per_row) * 16;
-      if (t < total) { st16(kdst + dof, kk[u]); st16(vdst + dof, vv[u]); }
-    }
-  }
+  gather_rows<NT>(a, s_idx, len, b, g, head_tok);
 }
 
 }  // namespace cd

@@ -40,7 +40,8 @@ def gpu_compress(wl, x, q_cal=None, extra_capacity=0, **over):
     return bufs
 
 
-def oracle_compress(wl, x, b, heads=None, q_cal=None, override=None, budget=None, pool_kernel=None):
+def oracle_compress(wl, x, b, heads=None, q_cal=None, override=None, budget=None, pool_kernel=None,
+                    calib_size=0):
     """Oracle compress of sequence b (optionally only the KV heads in `heads`)."""
     G = wl.group
     heads = list(range(wl.n_kv_heads)) if heads is None else list(heads)
@@ -50,7 +51,7 @@ def oracle_compress(wl, x, b, heads=None, q_cal=None, override=None, budget=None
     q_win = to64(x["q_win"][b])[qh]
     qc = None if q_cal is None else to64(q_cal[b])[qh]
     return ref.compress(q_win, K, V, wl.window, budget or wl.budget, pool_kernel or wl.pool_kernel,
-                        q_cal=qc, retained_override=override)
+                        q_cal=qc, retained_override=override, calib_size=calib_size)
 
 
 def check_indices(gpu_idx: np.ndarray, orc: dict, dtype: str, k_sel: int, report: dict):
@@ -83,6 +84,30 @@ def check_indices(gpu_idx: np.ndarray, orc: dict, dtype: str, k_sel: int, report
     return override
 
 
+def check_calibration_set(gpu_cal, orc, dtype, k_sel, m, report):
+    """The calibration set (Sec. 5.3 calibration size) per head: exact, except rounding-order
+    swaps at its own rank boundary (same tie-band rule as the retained set).  Returns the lists
+    to evaluate the calibration state with (the GPU's when a swap happened)."""
+    tau = TIE_BAND[dtype]
+    lists = []
+    for g in range(gpu_cal.shape[0]):
+        want = orc["evicted"][g]
+        got = gpu_cal[g]
+        assert np.all(got[len(want):] == -1), f"head {g}: calibration list not padded with -1"
+        got = got[:len(want)]
+        if not np.array_equal(got, want):
+            assert np.all(np.diff(got) > 0) and len(set(got) & set(orc["idx"][g])) == 0
+            score = orc["score"][g]
+            cand = np.sort(np.delete(score, orc["idx"][g][:k_sel]))[::-1]      # evicted tokens' scores
+            boundary, nxt = cand[m - 1], cand[m]
+            assert (boundary - nxt) / boundary < tau, f"head {g}: calibration set differs outside the tie band"
+            diff = np.setxor1d(got, want)
+            assert np.all(np.abs(score[diff] - boundary) <= tau * boundary)
+            report["tie_band_cal_heads"] = report.get("tie_band_cal_heads", 0) + 1
+        lists.append(got)
+    return lists
+
+
 def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_scores=True):
     """Compare everything calidrop_compress wrote for sequence b against the oracle."""
     report = {} if report is None else report
@@ -90,7 +115,8 @@ def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_sc
     G, B, w = wl.group, wl.budget, wl.window
     n = wl.seq_lens[b]
     heads = list(range(wl.n_kv_heads)) if heads is None else list(heads)
-    orc = oracle_compress(wl, x, b, heads, q_cal)
+    m = int(bufs.p.calib_size)
+    orc = oracle_compress(wl, x, b, heads, q_cal, calib_size=m)
     length = min(B, n)
     assert int(bufs.cache_lens[b].item()) == length
     gpu_idx = bufs.indices[b].cpu().numpy()[heads]
@@ -98,7 +124,17 @@ def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_sc
         assert np.all(gpu_idx[:, n:] == -1)
     override = check_indices(gpu_idx, orc, dt, B - w, report)
     if override is not None:        # evaluate downstream values for the GPU's retained set
-        orc = oracle_compress(wl, x, b, heads, q_cal, override=override)
+        orc = oracle_compress(wl, x, b, heads, q_cal, override=override, calib_size=m)
+    if m > 0:
+        gpu_cal = bufs.cal_indices[b].cpu().numpy()[heads]
+        if n <= B:
+            assert np.all(gpu_cal == -1)
+        else:
+            lists = check_calibration_set(gpu_cal, orc, dt, B - w, m, report)
+            if any(not np.array_equal(lists[j], orc["evicted"][j]) for j in range(len(heads))):
+                Kh = to64(synth.seq_view(x["k"], wl, b))[heads]
+                Vh = to64(synth.seq_view(x["v"], wl, b))[heads]
+                _, orc["c_out"], orc["c_lse"] = ref.calibration_state(orc["c_q"], Kh, Vh, lists, G, wl.head_dim ** -0.5)
     # gathered rows are copies: bit-exact
     Kc = to64(bufs.cache_view("k", b))[heads][:, :length]
     Vc = to64(bufs.cache_view("v", b))[heads][:, :length]
@@ -186,9 +222,10 @@ def check_recalibrate(wl, x, bufs, q_t, b, before, heads=None, report=None):
     K = to64(synth.seq_view(x["k"], wl, b))[heads]
     V = to64(synth.seq_view(x["v"], wl, b))[heads]
     idx = bufs.indices[b].cpu().numpy()[heads]
+    cal_idx = bufs.cal_indices[b].cpu().numpy()[heads] if bufs.p.calib_size > 0 else None
     out, flags, c_q, c_out, c_lse = ref.recalibrate(
         to64(q_t[b])[qh], K, V, idx, before["flags"][b][qh], before["a_lse"][b][qh], before["out"][b][qh],
-        before["c_q"][b][qh], before["c_out"][b][qh], before["c_lse"][b][qh], wl.window)
+        before["c_q"][b][qh], before["c_out"][b][qh], before["c_lse"][b][qh], wl.window, cal_idx=cal_idx)
     g_flags = bufs.flags[b].cpu().numpy()[qh]
     assert np.array_equal(g_flags, flags), (g_flags, flags)
     g_out, g_cq = to64(bufs.out[b])[qh], to64(bufs.c_q[b])[qh]

@@ -30,7 +30,7 @@ def test_header_symbols_are_exported():
     for n in names:
         assert hasattr(L, n), n
     assert L.calidrop_version() >= 100
-    assert ctypes.sizeof(cd.Params) == 48
+    assert ctypes.sizeof(cd.Params) == 52
 
 
 def test_workspace_sizes():
@@ -62,8 +62,7 @@ def test_workspace_sizes():
 def test_bad_params_rejected(kw, status):
     p = good(**kw)
     A = 4096     # fake, aligned, never dereferenced: validation fails first
-    rc = cd.lib().calidrop_compress(ctypes.byref(p), A, A, A, A, 2 * 8192, 8192, None, A, A, A, A,
-                                    A, A, A, A, A, 1 << 40, None)
+    rc = cd.lib().calidrop_compress(ctypes.byref(p), A, A, A, A, 2 * 8192, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None)
     assert rc == status, cd.calidrop_last_error()
     assert cd.calidrop_last_error() != ""
     rc = cd.lib().calidrop_decode(ctypes.byref(p), A, A, A, A, A, 512, A, A, A, A, None, None, A,
@@ -76,31 +75,22 @@ def test_bad_struct_size_null_align_workspace():
     L = cd.lib()
     p = good()
     p.struct_size = 40
-    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
-                               A, A, 1 << 40, None) == cd.EINVAL
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == cd.EINVAL
     p = good()
-    assert L.calidrop_compress(None, A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A, A, A,
-                               1 << 40, None) == cd.EINVAL
+    assert L.calidrop_compress(None, A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == cd.EINVAL
     # null k
-    assert L.calidrop_compress(ctypes.byref(p), A, None, A, A, 16384, 8192, None, A, A, A, A, A, A,
-                               A, A, A, 1 << 40, None) == cd.EINVAL
+    assert L.calidrop_compress(ctypes.byref(p), A, None, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == cd.EINVAL
     assert "k is NULL" in cd.calidrop_last_error()
     # misaligned v
-    assert L.calidrop_compress(ctypes.byref(p), A, A, A + 8, A, 16384, 8192, None, A, A, A, A, A, A,
-                               A, A, A, 1 << 40, None) == cd.EALIGN
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A + 8, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == cd.EALIGN
     # workspace too small / missing / misaligned
     need = cd.calidrop_compress_workspace_bytes(p, 16384, 8192)
-    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
-                               A, A, need - 1, None) == cd.EWORKSPACE
-    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
-                               A, None, 0, None) == cd.EWORKSPACE
-    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
-                               A, A + 16, need, None) == cd.EALIGN
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A, need - 1, None) == cd.EWORKSPACE
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, None, 0, None) == cd.EWORKSPACE
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A + 16, need, None) == cd.EALIGN
     # inconsistent sizes
-    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 100, 8192, None, A, A, A, A, A, A, A, A,
-                               A, 1 << 40, None) == cd.ESHAPE
-    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 3 * 8192, 8192, None, A, A, A, A, A, A,
-                               A, A, A, 1 << 40, None) == cd.ESHAPE      # batch*max < total
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 100, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == cd.ESHAPE
+    assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 3 * 8192, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == cd.ESHAPE      # batch*max < total
     # decode
     needd = cd.calidrop_decode_workspace_bytes(p, 512)
     assert L.calidrop_decode(ctypes.byref(p), A, A, A, A, A, 512, A, A, A, A, None, None, A,
@@ -114,12 +104,35 @@ def test_bad_struct_size_null_align_workspace():
     # recalibrate
     needr = cd.calidrop_recalibrate_workspace_bytes(p, 8192)
     assert needr > 0 and needr % 256 == 0
-    args = [A, A, A, A, 16384, 8192, A, A, A, A, A, A, A]
+    args = [A, A, A, A, 16384, 8192, A, None, A, A, A, A, A, A]
     assert L.calidrop_recalibrate(ctypes.byref(p), *args, A, needr - 1, None) == cd.EWORKSPACE
-    args[7] = None                                          # flags is required here
+    args[8] = None                                          # flags is required here
     assert L.calidrop_recalibrate(ctypes.byref(p), *args, A, needr, None) == cd.EINVAL
     assert "flags is NULL" in cd.calidrop_last_error()
-    args[7] = A; args[1] = A + 4
+    args[8] = A; args[1] = A + 4
     assert L.calidrop_recalibrate(ctypes.byref(p), *args, A, needr, None) == cd.EALIGN
-    assert L.calidrop_recalibrate(ctypes.byref(good(head_dim=96)), A, A, A, A, 16384, 8192, A, A, A, A, A, A, A, A,
-                                  needr, None) == cd.EUNSUPPORTED
+    assert L.calidrop_recalibrate(ctypes.byref(good(head_dim=96)), A, A, A, A, 16384, 8192, A, None, A, A, A, A, A, A,
+                                  A, needr, None) == cd.EUNSUPPORTED
+    # calibration size: the list of the calibration set becomes a required argument
+    pc = good(calib_size=64)
+    args = [A, A, A, A, 16384, 8192, A, None, A, A, A, A, A, A]
+    assert L.calidrop_recalibrate(ctypes.byref(pc), *args, A, needr, None) == cd.EINVAL
+    assert "cal_indices" in cd.calidrop_last_error()
+    assert L.calidrop_compress(ctypes.byref(pc), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A,
+                               1 << 40, None) == cd.EINVAL
+    assert L.calidrop_compress(ctypes.byref(good(calib_size=-1)), A, A, A, A, 16384, 8192, None, A, A, A, A, A, A, A,
+                               A, A, A, 1 << 40, None) == cd.EINVAL
+
+
+def test_older_params_layout_is_accepted():
+    # a caller compiled against the 48-byte struct (no calib_size) keeps working
+    p = good()
+    p.struct_size = 48
+    p.calib_size = 12345            # must be ignored: it lies outside the declared size
+    assert cd.calidrop_decode_workspace_bytes(p, 512) > 0
+    assert cd.calidrop_compress_workspace_bytes(p, 16384, 8192) == cd.calidrop_compress_workspace_bytes(good(), 16384, 8192)
+    A = 4096
+    # no cal_indices needed: calib_size is 0 for this layout
+    need = cd.calidrop_compress_workspace_bytes(p, 16384, 8192)
+    assert cd.lib().calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A,
+                                      A, need - 1, None) == cd.EWORKSPACE

@@ -348,3 +348,32 @@ def test_decode_under_hip_graph_replay():
         for t in range(4):
             assert torch.equal(outs[t], eager[t][0]), (rep_i, t)
         assert torch.equal(bufs.a_lse, eager[3][1]) and torch.equal(bufs.flags, eager[3][2])
+
+
+@pytest.mark.parametrize("dtype,D,k,m", [("bf16", 128, 5, 1), ("bf16", 64, 7, 50), ("fp32", 64, 3, 200),
+                                         ("bf16", 128, 17, 33), ("fp32", 128, 1, 5000)])
+def test_calibration_size(dtype, D, k, m):
+    # Sec. 5.3: only the m evicted tokens of highest score are calibrated / offloaded; m larger
+    # than the evicted set means all of it; k = 17 goes through the long-prefix selection kernel
+    wl = small(dtype, 8, 2, D, [900, 40, 1700], 16, 96, k, T=6, name=f"calib_{dtype}_{D}_{k}_{m}")
+    x = to_dev(synth.make_inputs(wl, 41))
+    bufs = H.gpu_compress(wl, x, calib_size=m)
+    rep = {}
+    for b in range(wl.batch):
+        H.check_compress(wl, x, bufs, b, report=rep)
+    cal = bufs.cal_indices.cpu().numpy()
+    assert cal.shape == (3, 2, m)
+    n_e = 900 - 96
+    assert np.all((cal[0] >= 0).sum(axis=1) == min(m, n_e))
+    for t in range(wl.decode_steps):
+        q_t = x["q_dec"][t]
+        bufs.decode(q_t)
+        torch.cuda.synchronize()
+        before = H.snapshot_state(bufs)
+        bufs.recalibrate(q_t, x["k"], x["v"], x["seq_offsets"])
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
+    rep.pop("flags", None)
+    print(wl.name, rep, flush=True)
+    assert rep["recal_heads"] > 0

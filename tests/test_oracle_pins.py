@@ -416,3 +416,38 @@ def test_recompute_with_nothing_evicted_is_a_noop_on_the_output():
     np.testing.assert_array_equal(out2, out)
     assert np.all(c_lse == -np.inf) and np.all(flags2 == ref.FLAG_RECOMPUTED)
     np.testing.assert_array_equal(c_q, q_t)
+
+
+def test_calibration_size_keeps_the_most_important_evicted_tokens():
+    # Sec. 5.3: only the m evicted tokens of highest importance are offloaded / calibrated
+    q_win, K, V = rand_case(n=60, w=6, D=16)
+    full = ref.compress(q_win, K, V, 6, 18, 3)
+    for m in [1, 5, 17]:
+        r = ref.compress(q_win, K, V, 6, 18, 3, calib_size=m)
+        np.testing.assert_array_equal(r["idx"], full["idx"])                 # selection itself is unchanged
+        for g in range(2):
+            ev_all = full["evicted"][g]
+            # brute force: repeated arg-max with removal over the evicted tokens' scores
+            want = [int(ev_all[i]) for i in brute_force_top(full["score"][g][ev_all], m)]
+            assert r["evicted"][g].tolist() == sorted(want)
+        for h in range(4):
+            g = h // 2
+            ev = r["evicted"][g]
+            np.testing.assert_allclose(r["c_out"][h], sdpa64(q_win[h, -1], K[g][ev], V[g][ev], 0.25), atol=1e-13)
+            np.testing.assert_allclose(r["c_lse"][h], logsumexp(0.25 * K[g][ev] @ q_win[h, -1]), atol=1e-13)
+    # m >= number of evicted tokens, and m = 0, both mean "all of them"
+    for m in [0, 42, 1000]:
+        r = ref.compress(q_win, K, V, 6, 18, 3, calib_size=m)
+        np.testing.assert_array_equal(r["c_out"], full["c_out"])
+        np.testing.assert_array_equal(r["c_lse"], full["c_lse"])
+    # the recomputation branch then only sees the offloaded subset
+    r = ref.compress(q_win, K, V, 6, 18, 3, calib_size=5)
+    q_t = -q_win[:, -1]
+    out, a_lse, flags, _ = ref.decode(q_t, r["K_c"], r["V_c"], 18, r["c_q"], r["c_out"], r["c_lse"], 0.7, 0.85)
+    cal_idx = np.stack(r["evicted"])
+    out2, _, _, c_out, c_lse = ref.recalibrate(q_t, K, V, r["idx"], flags, a_lse, out, r["c_q"], r["c_out"], r["c_lse"],
+                                               6, cal_idx=cal_idx)
+    for h in range(4):
+        g = h // 2
+        keep = np.concatenate([r["idx"][g], r["evicted"][g]])
+        np.testing.assert_allclose(out2[h], sdpa64(q_t[h], K[g][keep], V[g][keep], 0.25), atol=1e-13)
