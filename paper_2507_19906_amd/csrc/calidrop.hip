@@ -223,17 +223,12 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
       const size_t votes = (static_cast<size_t>(max_prefix) + max_prefix / 32 + 1) * sizeof(float);
       if (votes > lds) lds = votes;
     }
-    const int nt = max_prefix <= 256 * cd::kSelPerThread ? 256 : (max_prefix <= 512 * cd::kSelPerThread ? 512 : 1024);
-    const void* fn = nt == 256   ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<256>)
-                     : nt == 512 ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<512>)
-                                 : reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<1024>);
+    const void* fn = reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads>);
     if (lds > 48 * 1024) {
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
     }
-    if (nt == 256) hipLaunchKernelGGL(cd::select_gather_lds_kernel<256>, dim3(bg), dim3(256), lds, st, se);
-    else if (nt == 512) hipLaunchKernelGGL(cd::select_gather_lds_kernel<512>, dim3(bg), dim3(512), lds, st, se);
-    else hipLaunchKernelGGL(cd::select_gather_lds_kernel<1024>, dim3(bg), dim3(1024), lds, st, se);
+    hipLaunchKernelGGL(cd::select_gather_lds_kernel<cd::kSelThreads>, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
   } else {
     hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
     if ((rc = launch_status("pool_scores"))) return rc;

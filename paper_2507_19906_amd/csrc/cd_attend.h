@@ -219,7 +219,10 @@ struct AttendWave {
 // kLogits: calibration mode with the logits precomputed by the scoring pass (K is not read).
 template <typename T, int D, bool kLogits>
 __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
-  const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  // grid: x = split of the rows (rotated per head so that the splits every sequence has do not
+  // all land on the same XCDs of the round-robin deal), y = KV head, z = sequence
+  const int g = blockIdx.y, b = blockIdx.z;
+  const int split = (blockIdx.x + g + a.Hkv * b) % gridDim.x;
   int rows, head_stride, off0;
   attend_geometry(a, b, rows, head_stride, off0);
   const int row_begin = split * a.rows_per_split;

@@ -124,8 +124,12 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
   using KS = KeyStream<T, D>;
   constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys;
-  const int chunk = blockIdx.x;
+  // grid: x = key chunk (fastest: neighbouring workgroups stream neighbouring keys), y = (sequence,
+  // KV head, row block).  Workgroups are dealt to the 8 XCDs round-robin in launch order; the chunk
+  // index is rotated by y so that, with sequences of different lengths, the chunks every sequence
+  // has do not all land on the same XCDs.
   const int y = blockIdx.y;
+  const int chunk = (blockIdx.x + y) % gridDim.x;
   const int rb = y % a.NRB;
   const int bg = y / a.NRB;
   const int g = bg % a.Hkv;
@@ -273,8 +277,12 @@ template <typename T, int D>
 __global__ __launch_bounds__(256, sizeof(T) == 2 ? CD_VOTES_WAVES : 2) void score_votes_kernel(ScoreArgs a) {
   using KS = KeyStream<T, D>;
   constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys;
-  const int chunk = blockIdx.x;
+  // grid: x = key chunk (fastest: neighbouring workgroups stream neighbouring keys), y = (sequence,
+  // KV head, row block).  Workgroups are dealt to the 8 XCDs round-robin in launch order; the chunk
+  // index is rotated by y so that, with sequences of different lengths, the chunks every sequence
+  // has do not all land on the same XCDs.
   const int y = blockIdx.y;
+  const int chunk = (blockIdx.x + y) % gridDim.x;
   const int rb = y % a.NRB;
   const int bg = y / a.NRB;
   const int g = bg % a.Hkv;

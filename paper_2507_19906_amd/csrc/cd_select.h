@@ -268,8 +268,9 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
   gather_rows<kSelThreads>(a, idx, len, b, g, head_tok);
 }
 
-// LDS variant for prefixes of up to 32 * NT positions (NT = 256, 512 or 1024 threads; the
-// smaller workgroups let two or four heads share a compute unit).  Thread t owns positions
+// LDS variant for prefixes of up to 32 * NT positions (NT = 1024 threads in use: smaller
+// workgroups were measured slower, their staging and gather phases have too few threads).
+// Thread t owns positions
 // 32t..32t+31: their pooled scores live in its registers for the radix passes and the
 // compaction, and their bits are exactly bitmap word t.  The votes are staged once in LDS
 // (padded by one word per 32 so that the stride-32 accesses do not collide), and the same
