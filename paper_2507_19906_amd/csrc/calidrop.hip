@@ -233,6 +233,9 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
     hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
     if ((rc = launch_status("pool_scores"))) return rc;
     hipLaunchKernelGGL(cd::select_gather_kernel, dim3(bg), dim3(cd::kSelThreads), 0, st, se);
+    if ((rc = launch_status("select"))) return rc;
+    const int vecs = p->budget * (se.row_bytes / 16);
+    hipLaunchKernelGGL(cd::gather_kv_kernel, dim3(ceil_div(vecs, 256), bg), dim3(256), 0, st, se);
   }
   if ((rc = launch_status("select_gather"))) return rc;
 

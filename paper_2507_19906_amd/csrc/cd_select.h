@@ -185,13 +185,14 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
     const int P = n - a.w;
     const int k_sel = a.B - a.w;
     const uint32_t* gkey = reinterpret_cast<const uint32_t*>(a.score) + head_tok;
-    auto each_key = [&](auto&& visit) {          // 8 independent loads per thread in flight
-      for (int j0 = tid; j0 < P; j0 += 8 * kSelThreads) {
-        uint32_t u[8];
+    constexpr int kDepth = 16;                   // independent loads per thread in flight
+    auto each_key = [&](auto&& visit) {
+      for (int j0 = tid; j0 < P; j0 += kDepth * kSelThreads) {
+        uint32_t u[kDepth];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) u[q] = (j0 + q * kSelThreads < P) ? gkey[j0 + q * kSelThreads] : 0u;
+        for (int q = 0; q < kDepth; ++q) u[q] = (j0 + q * kSelThreads < P) ? gkey[j0 + q * kSelThreads] : 0u;
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
+        for (int q = 0; q < kDepth; ++q)
           if (j0 + q * kSelThreads < P) visit(u[q]);
       }
     };
@@ -207,12 +208,13 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
     const int seg_lo = wv * seg, seg_hi = min(n, seg_lo + seg);
     const int key_hi = min(P, seg_hi);    // candidates of this wave: prefix positions of its segment
     uint32_t cnt[4] = {0, 0, 0, 0};       // gt1, eq1, gt2, eq2 of this wave's segment
-    for (int base = seg_lo; base < seg_hi; base += 4 * 64) {
-      uint32_t u[4];
+    constexpr int kSl = 8;                // 64-position slices per iteration (loads in flight)
+    for (int base = seg_lo; base < seg_hi; base += kSl * 64) {
+      uint32_t u[kSl];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? gkey[j] : 0u; }
+      for (int q = 0; q < kSl; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? gkey[j] : 0u; }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < kSl; ++q) {
         const bool in = base + q * 64 + lane < key_hi;
         cnt[0] += __popcll(__ballot(in && u[q] > c1.thr));
         cnt[1] += __popcll(__ballot(in && u[q] == c1.thr));
@@ -230,12 +232,12 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
 #pragma unroll
       for (int q = 0; q < 4; ++q) pre[q] += wave_cnt[q][ww];
     const uint64_t below = (1ull << lane) - 1ull;
-    for (int base = seg_lo; base < seg_hi; base += 4 * 64) {
-      uint32_t u[4];
+    for (int base = seg_lo; base < seg_hi; base += kSl * 64) {
+      uint32_t u[kSl];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? gkey[j] : 0u; }
+      for (int q = 0; q < kSl; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? gkey[j] : 0u; }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < kSl; ++q) {
         const int j = base + q * 64 + lane;
         if (base + q * 64 < seg_hi) {
           const bool in = j < key_hi;
@@ -263,9 +265,30 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
       for (int r = n_cal + tid; r < a.calib; r += kSelThreads) cal[r] = -1;
     }
   }
-  __threadfence_block();
-  __syncthreads();                       // idx[] written above is read back by other threads
-  gather_rows<kSelThreads>(a, idx, len, b, g, head_tok);
+  // the gather of the retained rows is a separate, fully parallel launch (gather_kv_kernel):
+  // one workgroup per head cannot move a budget of thousands of rows fast enough
+}
+
+// K_c[g][r] = K[g][idx[g][r]], V likewise, for the long-prefix path; 16 bytes per thread.
+__global__ __launch_bounds__(256) void gather_kv_kernel(SelectArgs a) {
+  const int bg = blockIdx.y;
+  const int g = bg % a.Hkv;
+  const int b = bg / a.Hkv;
+  int off0;
+  const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
+  const int len = min(n, a.B);
+  const int c0 = a.cache_off[b];
+  const int cap = a.cache_off[b + 1] - c0;
+  if (cap < len) return;                 // capacity contract broken: write nothing
+  const int vec_per_row = a.row_bytes / 16;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  const int r = t / vec_per_row, vcol = t - r * vec_per_row;
+  if (r >= len) return;
+  const int src = a.indices[static_cast<int64_t>(bg) * a.B + r];
+  const int64_t so = ((static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n + src) * a.row_bytes) + vcol * 16;
+  const int64_t dof = ((static_cast<int64_t>(c0) * a.Hkv + static_cast<int64_t>(g) * cap + r) * a.row_bytes) + vcol * 16;
+  st16(static_cast<char*>(a.k_c) + dof, ld16(static_cast<const char*>(a.k) + so));
+  st16(static_cast<char*>(a.v_c) + dof, ld16(static_cast<const char*>(a.v) + so));
 }
 
 // LDS variant for prefixes of up to 32 * NT positions (NT = 1024 threads in use: smaller
