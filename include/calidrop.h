@@ -194,9 +194,9 @@ int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, 
  * calidrop_recalibrate - the rho < theta1 branch of Alg. 2 (steps 3-8), for the heads that the
  * preceding calidrop_decode call of the same step flagged CALIDROP_FLAG_RECOMPUTE.
  *
- * For every such (sequence b, query head h), with KV head g = h / G and KV_evict = the prefix
- * rows of the prompt (positions < n_b - w) that are not listed in indices[b][g] - or, when
- * calib_size > 0, exactly the rows listed in cal_indices[b][g]:
+ * For every such (sequence b, query head h), with KV head g = h / G and KV_evict = the rows of
+ * the prompt that are not listed in indices[b][g] (the list holds the window, so these are
+ * prefix rows) - or, when calib_size > 0, exactly the rows listed in cal_indices[b][g]:
  *   c_lse[h] = log sum_{t in evict} exp(scale q_t[h].K_t),  c_out[h] = Att(q_t[h], K_evict, V_evict)
  *   (the current query is used, as the text of Sec. 3.2 says), c_q[h] = q_t[h]           (steps 5-7)
  *   out[h] = alpha_i out[h] + alpha_j c_out[h] with alpha_j = 1/(1+exp(a_lse[h] - c_lse[h]))  (step 8)
@@ -219,6 +219,45 @@ int calidrop_recalibrate(const calidrop_params* p, const void* q_t, const void* 
                          const int32_t* indices, const int32_t* cal_indices, uint8_t* flags,
                          const float* a_lse, void* out, float* c_q, float* c_out, float* c_lse,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Other eviction strategies f (Alg. 1 step 3).  The method is independent of how the retained
+ * set is chosen (Sec. 3.2; Sec. 4.1.3 also evaluates StreamingLLM and H2O), so the steps after
+ * the choice - gather of KV_compress, KV_evict = everything else, calibration state - are also
+ * available for a retained set that is already known.
+ *
+ * calidrop_streaming_indices - the StreamingLLM choice (Sec. 4.1.3: a fixed number of attention
+ * sinks, the rest of the budget spent on the most recent tokens): for every sequence b and KV
+ * head, indices[b][g] = 0..n_sink-1 followed by n_b-(B-n_sink)..n_b-1 when n_b > B, else
+ * 0..n_b-1 padded with -1.  Index arithmetic only; the paper's setting is n_sink = 32.
+ *   0 <= n_sink <= budget (CALIDROP_EINVAL otherwise); seq_offsets, total_tokens, max_seq_len
+ *   as in calidrop_compress; indices out [batch][Hkv][B] int32.  No workspace.
+ *
+ * calidrop_compress_given - Alg. 1 steps 4-8 for the retained lists in `indices`:
+ *   n_b <= B : everything is retained (the library overwrites indices[b] with 0..n_b-1, -1 padded),
+ *              c_lse = -inf, c_out = 0.
+ *   n_b >  B : indices[b][g] must hold B distinct positions in [0, n_b), ascending (device memory,
+ *              so the host cannot check it: an entry outside the range is read as the nearest valid
+ *              position by the gather and marks nothing as retained - memory safe, result
+ *              meaningless).  K_c, V_c = those rows; KV_evict = every other row of the prompt;
+ *              c_lse, c_out = log-weight and attention of q_cal over KV_evict; c_q = q_cal.
+ *   `window` and `pool_kernel` of the params play no role here; calib_size must be 0 (the ranking
+ *   of evicted tokens needs scores: CALIDROP_EUNSUPPORTED otherwise).  calidrop_decode and
+ *   calidrop_recalibrate work on the result unchanged.
+ * Arguments: q_cal [batch][Hq][D] dtype (required: the last prompt query Q_{-1}); the others as in
+ * calidrop_compress; workspace >= calidrop_compress_given_workspace_bytes(p, max_seq_len) bytes,
+ * 256-byte aligned.
+ */
+size_t calidrop_compress_given_workspace_bytes(const calidrop_params* p, int32_t max_seq_len);
+int calidrop_streaming_indices(const calidrop_params* p, int32_t n_sink, const int32_t* seq_offsets,
+                               int64_t total_tokens, int32_t max_seq_len, int32_t* indices,
+                               void* stream);
+int calidrop_compress_given(const calidrop_params* p, const void* q_cal, const void* k,
+                            const void* v, const int32_t* seq_offsets, int64_t total_tokens,
+                            int32_t max_seq_len, int32_t* indices, void* k_c, void* v_c,
+                            const int32_t* cache_offsets, int32_t* cache_lens, float* c_q,
+                            float* c_out, float* c_lse, void* workspace, size_t workspace_bytes,
+                            void* stream);
 
 /* Host string describing the last error on the calling thread ("" if none). Never NULL.      */
 const char* calidrop_last_error(void);

@@ -204,6 +204,45 @@ def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=Non
 
 
 # --------------------------------------------------------------------------------------------
+# Other eviction strategies f (Sec. 4.1.3) and Alg. 1 for a retained set that is already known
+# --------------------------------------------------------------------------------------------
+def streaming_llm_retained(n, B, n_sink):
+    """StreamingLLM as configured in Sec. 4.1.3: n_sink attention-sink positions at the start of
+    the prompt, the rest of the budget on the most recent positions.  Ascending positions."""
+    if n <= B:
+        return np.arange(n)
+    keep = [j for j in range(n) if j < n_sink or j >= n - (B - n_sink)]
+    return np.asarray(keep, np.int64)
+
+
+def compress_given(q_cal, K, V, B, retained, scale=None):
+    """Alg. 1 steps 4-8 for one sequence when step 3 (the choice of KV_compress) was made elsewhere.
+
+    retained: list over KV heads of position arrays (ascending); ignored when n <= B (nothing is
+    evicted).  KV_evict = every position of the prompt that is not retained.  q_cal [Hq][D] is
+    Q_{-1}.  Returns dict idx, K_c, V_c, c_q, c_out, c_lse, evicted."""
+    q_cal = np.asarray(q_cal, F)
+    K = np.asarray(K, F)
+    V = np.asarray(V, F)
+    Hq, D = q_cal.shape
+    Hkv, n, _ = K.shape
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    idx, evicted = [], []
+    for g in range(Hkv):
+        keep = np.arange(n) if n <= B else np.asarray(retained[g], np.int64)
+        ev = np.asarray([j for j in range(n) if j not in set(keep.tolist())], np.int64)
+        idx.append(keep)
+        evicted.append(ev)
+    idx = np.stack(idx)
+    K_c = np.stack([K[g][idx[g]] for g in range(Hkv)])
+    V_c = np.stack([V[g][idx[g]] for g in range(Hkv)])
+    c_q, c_out, c_lse = calibration_state(q_cal, K, V, evicted, G, scale)
+    return dict(idx=idx, K_c=K_c, V_c=V_c, c_q=c_q, c_out=c_out, c_lse=c_lse, evicted=evicted)
+
+
+# --------------------------------------------------------------------------------------------
 # Alg. 2 (decode side), one sequence, one step
 # --------------------------------------------------------------------------------------------
 FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE, FLAG_RECOMPUTED = 0, 1, 2, 3
@@ -256,11 +295,11 @@ def decode(q_t, K_c, V_c, length, c_q, c_out, c_lse, theta1, theta2, scale=None)
     return out, a_lse, flags, rhos
 
 
-def recalibrate(q_t, K, V, idx, flags, a_lse, out, c_q, c_out, c_lse, w, scale=None, cal_idx=None):
+def recalibrate(q_t, K, V, idx, flags, a_lse, out, c_q, c_out, c_lse, scale=None, cal_idx=None):
     """Alg. 2 steps 3-8 (the rho < theta1 branch) for the heads that `decode` flagged.
 
-    The evicted K/V are the prefix rows of the prompt tensors K, V [Hkv][n][D] that are not in
-    idx [Hkv][B] (KV_evict = KV_full minus KV_compress, frozen at prefill).  For every head with
+    The evicted K/V are the rows of the prompt tensors K, V [Hkv][n][D] that are not in
+    idx [Hkv][B] (Alg. 1 step 4: KV_evict = KV_full minus KV_compress, frozen at prefill).  For every head with
     flag FLAG_RECOMPUTE: C_weight and C_out are recomputed with the CURRENT query (the prose of
     Sec. 3.2; the listing prints Q_{-1} but then sets C_q = Q_t), C_q = Q_t, and the output is
     calibrated by Eq. 1: out = alpha_i * out + alpha_j * C_out.  `out`, `a_lse` are what decode
@@ -278,14 +317,13 @@ def recalibrate(q_t, K, V, idx, flags, a_lse, out, c_q, c_out, c_lse, w, scale=N
     out = np.array(out, F)
     flags = np.array(flags, np.uint8)
     c_q, c_out, c_lse = np.array(c_q, F), np.array(c_out, F), np.array(c_lse, F)
-    P = n - w
     for h in range(Hq):
         if flags[h] != FLAG_RECOMPUTE:
             continue
         g = h // G
         keep = np.asarray(idx[g])
-        mask = np.ones(max(P, 0), bool)
-        mask[keep[(keep >= 0) & (keep < P)]] = False
+        mask = np.ones(n, bool)
+        mask[keep[(keep >= 0) & (keep < n)]] = False
         ev = np.nonzero(mask)[0]
         if cal_idx is not None:
             ci = np.asarray(cal_idx[g])

@@ -92,6 +92,13 @@ def lib() -> ctypes.CDLL:
         L.calidrop_recalibrate_workspace_bytes.argtypes = [pp, i32]
         L.calidrop_recalibrate.restype = ctypes.c_int
         L.calidrop_recalibrate.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.calidrop_compress_given_workspace_bytes.restype = sz
+        L.calidrop_compress_given_workspace_bytes.argtypes = [pp, i32]
+        L.calidrop_streaming_indices.restype = ctypes.c_int
+        L.calidrop_streaming_indices.argtypes = [pp, i32, vp, i64, i32, vp, vp]
+        L.calidrop_compress_given.restype = ctypes.c_int
+        L.calidrop_compress_given.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp,
+                                              vp, sz, vp]
         _lib = L
     return _lib
 
@@ -181,6 +188,29 @@ def calidrop_recalibrate(p: Params, q_t, k, v, seq_offsets, total_tokens: int, m
         _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
+def calidrop_compress_given_workspace_bytes(p: Params, max_seq_len: int) -> int:
+    n = lib().calidrop_compress_given_workspace_bytes(ctypes.byref(p), max_seq_len)
+    if n == 0:
+        raise CalidropError(EINVAL, calidrop_last_error())
+    return n
+
+
+def calidrop_streaming_indices(p: Params, n_sink: int, seq_offsets, total_tokens: int, max_seq_len: int,
+                               indices, stream=None) -> None:
+    _check(lib().calidrop_streaming_indices(ctypes.byref(p), n_sink, _ptr(seq_offsets), total_tokens,
+                                            max_seq_len, _ptr(indices), _stream(stream)))
+
+
+def calidrop_compress_given(p: Params, q_cal, k, v, seq_offsets, total_tokens: int, max_seq_len: int,
+                            indices, k_c, v_c, cache_offsets, cache_lens, c_q, c_out, c_lse, workspace,
+                            stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().calidrop_compress_given(
+        ctypes.byref(p), _ptr(q_cal), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
+        _ptr(indices), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens), _ptr(c_q), _ptr(c_out),
+        _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
 # ---- device-memory plumbing (allocation only) ----------------------------------------------
 class CompressBuffers:
     """Output and workspace tensors for calidrop_compress / calidrop_decode, allocated with
@@ -220,6 +250,19 @@ class CompressBuffers:
                           q_cal, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
                           self.indices, self.cal_indices, self.c_q, self.c_out, self.c_lse,
                           self.ws_compress, stream)
+
+    def compress_given(self, q_cal, k, v, seq_offsets, stream=None):
+        """Alg. 1 steps 4-8 for the retained lists already in self.indices."""
+        if getattr(self, "ws_given", None) is None:
+            self.ws_given = torch.empty(calidrop_compress_given_workspace_bytes(self.p, self.max_seq_len),
+                                        dtype=torch.uint8, device=self.out.device)
+        calidrop_compress_given(self.p, q_cal, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
+                                self.indices, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
+                                self.c_q, self.c_out, self.c_lse, self.ws_given, stream)
+
+    def streaming_indices(self, n_sink, seq_offsets, stream=None):
+        calidrop_streaming_indices(self.p, n_sink, seq_offsets, self.total_tokens, self.max_seq_len,
+                                   self.indices, stream)
 
     def decode(self, q_t, stream=None, max_cache_len=None):
         calidrop_decode(self.p, q_t, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,

@@ -11,6 +11,7 @@
 
 #include "cd_attend.h"
 #include "cd_common.h"
+#include "cd_given.h"
 #include "cd_score.h"
 #include "cd_select.h"
 
@@ -343,7 +344,8 @@ int recal_impl(const calidrop_params* p, const void* q_t, const void* k, const v
   cd::AttendArgs aa{};
   aa.q = q_t; aa.q_is_window = 0; aa.k = k; aa.v = v; aa.row_off = seq_offsets; aa.row_len = nullptr;
   aa.bitmap = ba.bitmap; aa.total_tokens = total_tokens; aa.batch = p->batch; aa.Hq = p->n_q_heads;
-  aa.Hkv = p->n_kv_heads; aa.G = G; aa.w = p->window; aa.B = p->budget; aa.max_len = max_seq_len; aa.W32 = L.W32;
+  // w = 0: the pass covers every position; the bitmap masks the retained ones, window included
+  aa.Hkv = p->n_kv_heads; aa.G = G; aa.w = 0; aa.B = p->budget; aa.max_len = max_seq_len; aa.W32 = L.W32;
   aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = logit_scale(p) * cd::kLog2e;
   aa.cal_logit = nullptr; aa.zstride = 0; aa.only_flagged = flags;
   aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
@@ -355,11 +357,59 @@ int recal_impl(const calidrop_params* p, const void* q_t, const void* k, const v
   cd::FinalArgs fa{};
   fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = seq_offsets; fa.row_len = nullptr;
   fa.total_tokens = total_tokens; fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G;
-  fa.w = p->window; fa.B = p->budget; fa.max_len = max_seq_len; fa.rows_per_split = L.sp.rows_per_split;
+  fa.w = 0; fa.B = p->budget; fa.max_len = max_seq_len; fa.rows_per_split = L.sp.rows_per_split;
   fa.NS = L.sp.NS; fa.calib_mode = 2; fa.q_is_window = 0; fa.q = q_t;
   fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse; fa.out = out; fa.a_lse = const_cast<float*>(a_lse); fa.flags = flags;
   hipLaunchKernelGGL((cd::attend_finalize_kernel<T, D>), dim3(p->n_q_heads, p->batch), dim3(D), 0, st, fa);
   return launch_status("attend_finalize(recalibrate)");
+}
+
+// Alg. 1 steps 4-8 for a retained set that is already known (caller's strategy, or the
+// StreamingLLM list): bitmap + cache_lens, gather, calibration pass over everything else.
+template <typename T, int D>
+int compress_given_impl(const calidrop_params* p, const void* q_cal, const void* k, const void* v,
+                        const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, int32_t* indices,
+                        void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, float* c_q,
+                        float* c_out, float* c_lse, char* ws, const RecalLayout& L, hipStream_t st) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  const int bg = p->batch * p->n_kv_heads;
+  int rc;
+  cd::GivenArgs ga{};
+  ga.seq_off = seq_offsets; ga.total_tokens = total_tokens; ga.batch = p->batch; ga.Hkv = p->n_kv_heads;
+  ga.B = p->budget; ga.max_seq_len = max_seq_len; ga.W32 = L.W32; ga.indices = indices; ga.cache_lens = cache_lens;
+  ga.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
+  hipLaunchKernelGGL(cd::given_prepare_kernel, dim3(bg), dim3(256), 0, st, ga);
+  if ((rc = launch_status("given_prepare"))) return rc;
+
+  cd::SelectArgs se{};
+  se.seq_off = seq_offsets; se.cache_off = cache_offsets; se.total_tokens = total_tokens; se.batch = p->batch;
+  se.Hkv = p->n_kv_heads; se.w = 0; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
+  se.row_bytes = D * static_cast<int>(sizeof(T)); se.indices = indices; se.cache_lens = cache_lens;
+  se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
+  const int vecs = p->budget * (se.row_bytes / 16);
+  hipLaunchKernelGGL(cd::gather_kv_kernel, dim3(ceil_div(vecs, 256), bg), dim3(256), 0, st, se);
+  if ((rc = launch_status("gather_kv"))) return rc;
+
+  cd::AttendArgs aa{};
+  aa.q = q_cal; aa.q_is_window = 0; aa.k = k; aa.v = v; aa.row_off = seq_offsets; aa.row_len = nullptr;
+  aa.bitmap = ga.bitmap; aa.total_tokens = total_tokens; aa.batch = p->batch; aa.Hq = p->n_q_heads;
+  aa.Hkv = p->n_kv_heads; aa.G = G; aa.w = 0; aa.B = p->budget; aa.max_len = max_seq_len; aa.W32 = L.W32;
+  aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = logit_scale(p) * cd::kLog2e;
+  aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
+  aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+  if (max_seq_len > p->budget) {
+    hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0,
+                       st, aa);
+    if ((rc = launch_status("attend_partial(given)"))) return rc;
+  }
+  cd::FinalArgs fa{};
+  fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = seq_offsets; fa.row_len = nullptr;
+  fa.total_tokens = total_tokens; fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G;
+  fa.w = 0; fa.B = p->budget; fa.max_len = max_seq_len; fa.rows_per_split = L.sp.rows_per_split;
+  fa.NS = L.sp.NS; fa.calib_mode = 1; fa.q_is_window = 0; fa.q = q_cal;
+  fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse;
+  hipLaunchKernelGGL((cd::attend_finalize_kernel<T, D>), dim3(p->n_q_heads, p->batch), dim3(D), 0, st, fa);
+  return launch_status("attend_finalize(given)");
 }
 
 }  // namespace
@@ -367,7 +417,7 @@ int recal_impl(const calidrop_params* p, const void* q_t, const void* k, const v
 extern "C" {
 
 const char* calidrop_last_error(void) { return g_err; }
-int calidrop_version(void) { return 100; }
+int calidrop_version(void) { return 200; }
 void calidrop_set_inspection(int enabled) { g_inspection.store(enabled ? 1 : 0, std::memory_order_relaxed); }
 
 size_t calidrop_compress_workspace_bytes(const calidrop_params* p_in, int64_t total_tokens, int32_t max_seq_len) {
@@ -526,6 +576,70 @@ int calidrop_recalibrate(const calidrop_params* p_in, const void* q_t, const voi
 #define CD_DISPATCH(T, D)                                                                                        \
   return recal_impl<T, D>(p, q_t, k, v, seq_offsets, total_tokens, max_seq_len, indices, cal_indices, flags, a_lse, \
                           out, c_q, c_out, c_lse, ws, L, st)
+  if (p->dtype == CALIDROP_BF16) {
+    if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
+    CD_DISPATCH(cd::bf16_t, 64);
+  }
+  if (p->head_dim == 128) CD_DISPATCH(float, 128);
+  CD_DISPATCH(float, 64);
+#undef CD_DISPATCH
+}
+
+size_t calidrop_compress_given_workspace_bytes(const calidrop_params* p_in, int32_t max_seq_len) {
+  return calidrop_recalibrate_workspace_bytes(p_in, max_seq_len);   // same regions: bitmap + split partials
+}
+
+int calidrop_streaming_indices(const calidrop_params* p_in, int32_t n_sink, const int32_t* seq_offsets,
+                               int64_t total_tokens, int32_t max_seq_len, int32_t* indices, void* stream) {
+  int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
+  if ((rc = check_params(p))) return rc;
+  if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
+  if (n_sink < 0 || n_sink > p->budget)
+    return fail(CALIDROP_EINVAL, "n_sink must lie in [0, budget] (got %d, budget %d)", n_sink, p->budget);
+  if (!seq_offsets) return fail(CALIDROP_EINVAL, "seq_offsets is NULL");
+  if (!indices) return fail(CALIDROP_EINVAL, "indices is NULL");
+  if (!aligned16(seq_offsets) || !aligned16(indices))
+    return fail(CALIDROP_EALIGN, "seq_offsets / indices is not 16-byte aligned");
+  cd::StreamingArgs sa{};
+  sa.seq_off = seq_offsets; sa.total_tokens = total_tokens; sa.batch = p->batch; sa.Hkv = p->n_kv_heads;
+  sa.B = p->budget; sa.n_sink = n_sink; sa.max_seq_len = max_seq_len; sa.indices = indices;
+  hipLaunchKernelGGL(cd::streaming_indices_kernel, dim3(ceil_div(p->budget, 256), p->batch * p->n_kv_heads), dim3(256),
+                     0, static_cast<hipStream_t>(stream), sa);
+  return launch_status("streaming_indices");
+}
+
+int calidrop_compress_given(const calidrop_params* p_in, const void* q_cal, const void* k, const void* v,
+                            const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, int32_t* indices,
+                            void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, float* c_q,
+                            float* c_out, float* c_lse, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
+  if ((rc = check_params(p))) return rc;
+  if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
+  const struct { const void* ptr; const char* name; } req[] = {
+      {q_cal, "q_cal"}, {k, "k"}, {v, "v"}, {seq_offsets, "seq_offsets"}, {indices, "indices"}, {k_c, "k_c"},
+      {v_c, "v_c"}, {cache_offsets, "cache_offsets"}, {cache_lens, "cache_lens"}, {c_q, "c_q"}, {c_out, "c_out"},
+      {c_lse, "c_lse"}};
+  for (const auto& r : req)
+    if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
+  for (const auto& r : req)
+    if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  if (p->calib_size != 0)
+    return fail(CALIDROP_EUNSUPPORTED, "calib_size needs the scored strategy (got %d with a given retained set)",
+                p->calib_size);
+  const RecalLayout L = recal_layout(p, max_seq_len);
+  if (!workspace || workspace_bytes < L.total)
+    return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
+                L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+#define CD_DISPATCH(T, D)                                                                                         \
+  return compress_given_impl<T, D>(p, q_cal, k, v, seq_offsets, total_tokens, max_seq_len, indices, k_c, v_c,     \
+                                   cache_offsets, cache_lens, c_q, c_out, c_lse, ws, L, st)
   if (p->dtype == CALIDROP_BF16) {
     if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
     CD_DISPATCH(cd::bf16_t, 64);

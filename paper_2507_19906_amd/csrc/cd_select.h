@@ -269,7 +269,8 @@ __global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a
   // one workgroup per head cannot move a budget of thousands of rows fast enough
 }
 
-// K_c[g][r] = K[g][idx[g][r]], V likewise, for the long-prefix path; 16 bytes per thread.
+// K_c[g][r] = K[g][idx[g][r]], V likewise (long-prefix path and caller-supplied lists); 16 bytes
+// per thread.
 __global__ __launch_bounds__(256) void gather_kv_kernel(SelectArgs a) {
   const int bg = blockIdx.y;
   const int g = bg % a.Hkv;
@@ -284,7 +285,8 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(SelectArgs a) {
   const int t = blockIdx.x * 256 + threadIdx.x;
   const int r = t / vec_per_row, vcol = t - r * vec_per_row;
   if (r >= len) return;
-  const int src = a.indices[static_cast<int64_t>(bg) * a.B + r];
+  // clamped: the list may be the caller's (a strategy applied outside the library)
+  const int src = min(max(a.indices[static_cast<int64_t>(bg) * a.B + r], 0), n - 1);
   const int64_t so = ((static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n + src) * a.row_bytes) + vcol * 16;
   const int64_t dof = ((static_cast<int64_t>(c0) * a.Hkv + static_cast<int64_t>(g) * cap + r) * a.row_bytes) + vcol * 16;
   st16(static_cast<char*>(a.k_c) + dof, ld16(static_cast<const char*>(a.k) + so));

@@ -225,7 +225,7 @@ def check_recalibrate(wl, x, bufs, q_t, b, before, heads=None, report=None):
     cal_idx = bufs.cal_indices[b].cpu().numpy()[heads] if bufs.p.calib_size > 0 else None
     out, flags, c_q, c_out, c_lse = ref.recalibrate(
         to64(q_t[b])[qh], K, V, idx, before["flags"][b][qh], before["a_lse"][b][qh], before["out"][b][qh],
-        before["c_q"][b][qh], before["c_out"][b][qh], before["c_lse"][b][qh], wl.window, cal_idx=cal_idx)
+        before["c_q"][b][qh], before["c_out"][b][qh], before["c_lse"][b][qh], cal_idx=cal_idx)
     g_flags = bufs.flags[b].cpu().numpy()[qh]
     assert np.array_equal(g_flags, flags), (g_flags, flags)
     g_out, g_cq = to64(bufs.out[b])[qh], to64(bufs.c_q[b])[qh]

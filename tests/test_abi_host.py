@@ -136,3 +136,27 @@ def test_older_params_layout_is_accepted():
     need = cd.calidrop_compress_workspace_bytes(p, 16384, 8192)
     assert cd.lib().calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A,
                                       A, need - 1, None) == cd.EWORKSPACE
+
+
+def test_given_strategy_entry_points_validate_on_the_host():
+    A = 4096
+    L = cd.lib()
+    p = good()
+    need = cd.calidrop_compress_given_workspace_bytes(p, 8192)
+    assert need > 0 and need % 256 == 0
+    # streaming list: sink count must fit the budget
+    assert L.calidrop_streaming_indices(ctypes.byref(p), -1, A, 16384, 8192, A, None) == cd.EINVAL
+    assert L.calidrop_streaming_indices(ctypes.byref(p), 513, A, 16384, 8192, A, None) == cd.EINVAL
+    assert "n_sink" in cd.calidrop_last_error()
+    assert L.calidrop_streaming_indices(ctypes.byref(p), 32, A, 16384, 8192, None, None) == cd.EINVAL
+    assert L.calidrop_streaming_indices(ctypes.byref(p), 32, A, 100, 8192, A, None) == cd.ESHAPE
+    # compress_given: q_cal is required, calib_size unsupported, workspace checked
+    args = [A, A, A, A, 16384, 8192, A, A, A, A, A, A, A, A]
+    assert L.calidrop_compress_given(ctypes.byref(p), *args, A, need - 1, None) == cd.EWORKSPACE
+    bad = list(args); bad[0] = None
+    assert L.calidrop_compress_given(ctypes.byref(p), *bad, A, need, None) == cd.EINVAL
+    assert "q_cal is NULL" in cd.calidrop_last_error()
+    bad = list(args); bad[6] = A + 4
+    assert L.calidrop_compress_given(ctypes.byref(p), *bad, A, need, None) == cd.EALIGN
+    assert L.calidrop_compress_given(ctypes.byref(good(calib_size=8)), *args, A, need, None) == cd.EUNSUPPORTED
+    assert L.calidrop_compress_given(ctypes.byref(good(head_dim=96)), *args, A, need, None) == cd.EUNSUPPORTED

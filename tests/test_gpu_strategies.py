@@ -1,0 +1,159 @@
+"""Retained sets that do not come from the scored selection (Sec. 4.1.3: StreamingLLM; or any
+list a caller computed): index arithmetic, gather and calibration state on the GPU vs the
+oracle, then Alg. 2 (decode and the recomputation branch) on that state.  Needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import calidrop_ref as ref
+from paper_2507_19906_amd import binding as cd
+from paper_2507_19906_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def to_dev(x):
+    return {k: v.to(DEV) for k, v in x.items()}
+
+
+def small(dtype, Hq, Hkv, D, lens, w, B, k, T=4, name="small"):
+    return synth.Workload(name, len(lens), Hq, Hkv, D, list(lens), w, B, k, dtype, T)
+
+
+def check_given(wl, x, bufs, q_cal, lists, rep):
+    """Everything calidrop_compress_given wrote vs the oracle, for the retained `lists`
+    [batch][Hkv] (None for sequences within the budget)."""
+    B, G = wl.budget, wl.group
+    for b in range(wl.batch):
+        n = wl.seq_lens[b]
+        K = H.to64(synth.seq_view(x["k"], wl, b))
+        V = H.to64(synth.seq_view(x["v"], wl, b))
+        orc = ref.compress_given(H.to64(q_cal[b]), K, V, B, lists[b])
+        length = min(n, B)
+        assert int(bufs.cache_lens[b].item()) == length
+        gi = bufs.indices[b].cpu().numpy()
+        assert np.array_equal(gi[:, :length], orc["idx"]) and np.all(gi[:, length:] == -1)
+        assert np.array_equal(H.to64(bufs.cache_view("k", b))[:, :length], orc["K_c"])
+        assert np.array_equal(H.to64(bufs.cache_view("v", b))[:, :length], orc["V_c"])
+        assert np.array_equal(H.to64(bufs.c_q[b]), orc["c_q"])
+        c_out, c_lse = H.to64(bufs.c_out[b]), H.to64(bufs.c_lse[b])
+        if n <= B:
+            assert np.all(c_lse == -np.inf) and np.all(c_out == 0)
+            continue
+        e_o, e_l = np.abs(c_out - orc["c_out"]).max(), np.abs(c_lse - orc["c_lse"]).max()
+        rep["c_out_err"] = max(rep.get("c_out_err", 0), e_o)
+        rep["c_lse_err"] = max(rep.get("c_lse_err", 0), e_l)
+        assert e_o <= H.TOL_OUT[wl.dtype] and e_l <= H.TOL_LSE[wl.dtype], (e_o, e_l)
+
+
+def decode_and_recalibrate(wl, x, bufs, rep, steps):
+    for t in range(steps):
+        q_t = x["q_dec"][t]
+        bufs.decode(q_t)
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_decode_step(wl, bufs, q_t, b, report=rep)
+        before = H.snapshot_state(bufs)
+        bufs.recalibrate(q_t, x["k"], x["v"], x["seq_offsets"])
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
+
+
+@pytest.mark.parametrize("wl,n_sink", [
+    (small("bf16", 8, 2, 128, [900, 40, 2100], 16, 128, 5, T=6, name="slm_varlen_bf16"), 32),
+    (small("fp32", 8, 2, 64, [1031], 16, 96, 3, T=4, name="slm_fp32_d64"), 32),
+    (small("bf16", 32, 8, 128, [4096, 513], 32, 512, 7, T=3, name="slm_llama_shape"), 32),
+    (small("fp32", 4, 2, 64, [300], 8, 64, 1, T=3, name="slm_window_only"), 0),
+    (small("fp32", 4, 2, 64, [300], 8, 64, 1, T=3, name="slm_sinks_only"), 64),
+], ids=lambda v: v.name if hasattr(v, "name") else str(v))
+def test_streaming_llm_strategy(wl, n_sink):
+    x = to_dev(synth.make_inputs(wl, 77))
+    p = H.params_for(wl)
+    bufs = cd.CompressBuffers(p, wl.seq_lens, DEV)
+    bufs.indices.fill_(-7)
+    bufs.streaming_indices(n_sink, x["seq_offsets"])
+    torch.cuda.synchronize()
+    lists = []
+    for b, n in enumerate(wl.seq_lens):
+        want = ref.streaming_llm_retained(n, wl.budget, n_sink)
+        got = bufs.indices[b].cpu().numpy()
+        for g in range(wl.n_kv_heads):
+            assert np.array_equal(got[g, :len(want)], want) and np.all(got[g, len(want):] == -1)
+        lists.append([want] * wl.n_kv_heads if n > wl.budget else None)
+    q_cal = x["q_win"][:, :, -1].contiguous()                    # Q_{-1}
+    bufs.compress_given(q_cal, x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    rep = {}
+    check_given(wl, x, bufs, q_cal, lists, rep)
+    decode_and_recalibrate(wl, x, bufs, rep, wl.decode_steps)
+    flags = np.bincount(rep.pop("flags"), minlength=4)
+    print(wl.name, rep, flags.tolist(), flush=True)
+
+
+def test_caller_supplied_lists_differ_per_head_and_need_not_hold_the_window():
+    # any f: random distinct positions per (sequence, KV head), window not necessarily retained
+    wl = small("bf16", 8, 4, 128, [1500, 700, 90], 16, 100, 5, T=4, name="given_random")
+    x = to_dev(synth.make_inputs(wl, 5))
+    rng = np.random.default_rng(99)
+    p = H.params_for(wl)
+    bufs = cd.CompressBuffers(p, wl.seq_lens, DEV)
+    host = np.full((wl.batch, wl.n_kv_heads, wl.budget), -1, np.int32)
+    lists = []
+    for b, n in enumerate(wl.seq_lens):
+        if n <= wl.budget:
+            lists.append(None)
+            host[b] = 123456                                    # ignored and overwritten by the library
+            continue
+        per = [np.sort(rng.choice(n, wl.budget, replace=False)) for _ in range(wl.n_kv_heads)]
+        lists.append(per)
+        host[b] = np.stack(per)
+    bufs.indices.copy_(torch.from_numpy(host))
+    q_cal = x["q_win"][:, :, -1].contiguous()
+    bufs.compress_given(q_cal, x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    rep = {}
+    check_given(wl, x, bufs, q_cal, lists, rep)
+    decode_and_recalibrate(wl, x, bufs, rep, wl.decode_steps)
+    rep.pop("flags")
+    print(wl.name, rep, flush=True)
+
+
+def test_given_path_with_the_scored_lists_reproduces_compress():
+    # feeding calidrop_compress's own retained lists back gives the same cache and state
+    wl = small("fp32", 8, 2, 64, [1200, 333], 16, 80, 5, T=1, name="given_equals_scored")
+    x = to_dev(synth.make_inputs(wl, 3))
+    a = H.gpu_compress(wl, x)
+    p = H.params_for(wl)
+    b2 = cd.CompressBuffers(p, wl.seq_lens, DEV)
+    b2.indices.copy_(a.indices)
+    b2.compress_given(x["q_win"][:, :, -1].contiguous(), x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    assert torch.equal(a.k_c, b2.k_c) and torch.equal(a.v_c, b2.v_c) and torch.equal(a.cache_lens, b2.cache_lens)
+    assert torch.equal(a.c_q, b2.c_q)
+    assert (a.c_out - b2.c_out).abs().max().item() < 1e-4
+    assert (a.c_lse - b2.c_lse).abs().max().item() < 1e-4
+
+
+def test_out_of_range_entries_are_memory_safe():
+    # a broken list must not make the kernels read or write outside the buffers: entries outside
+    # [0, n) are clamped by the gather and mark nothing as retained
+    wl = small("fp32", 4, 2, 64, [400], 8, 32, 1, T=1, name="given_bad_entries")
+    x = to_dev(synth.make_inputs(wl, 4))
+    p = H.params_for(wl)
+    bufs = cd.CompressBuffers(p, wl.seq_lens, DEV)
+    host = np.tile(np.arange(32, dtype=np.int32) * 3, (1, 2, 1))
+    host[0, 0, 5] = -9
+    host[0, 1, 7] = 1 << 30
+    bufs.indices.copy_(torch.from_numpy(host))
+    guard_k, guard_v = x["k"].clone(), x["v"].clone()
+    bufs.compress_given(x["q_win"][:, :, -1].contiguous(), x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    assert torch.equal(guard_k, x["k"]) and torch.equal(guard_v, x["v"])
+    assert torch.isfinite(bufs.c_out).all()
+    K = H.to64(synth.seq_view(x["k"], wl, 0))
+    Kc = H.to64(bufs.cache_view("k", 0))
+    assert np.array_equal(Kc[0, 5], K[0, 0]) and np.array_equal(Kc[1, 7], K[1, 399])     # clamped rows
+    assert np.array_equal(Kc[0, 6], K[0, 18])

@@ -385,7 +385,7 @@ def test_recompute_branch_gives_exact_attention_and_refreshes_state():
     out, a_lse, flags, rho = ref.decode(q_t, r["K_c"], r["V_c"], 18, r["c_q"], r["c_out"], r["c_lse"], 0.7, 0.85)
     assert np.all(flags == ref.FLAG_RECOMPUTE)
     out2, flags2, c_q, c_out, c_lse = ref.recalibrate(q_t, K, V, r["idx"], flags, a_lse, out, r["c_q"], r["c_out"],
-                                                      r["c_lse"], 6)
+                                                      r["c_lse"])
     assert np.all(flags2 == ref.FLAG_RECOMPUTED)
     np.testing.assert_array_equal(c_q, q_t)
     for h in range(4):
@@ -401,7 +401,7 @@ def test_recompute_branch_gives_exact_attention_and_refreshes_state():
     # heads that were not flagged are left alone
     flags_mixed = flags.copy(); flags_mixed[1] = ref.FLAG_NONE
     o4, f4, cq4, co4, cl4 = ref.recalibrate(q_t, K, V, r["idx"], flags_mixed, a_lse, out, r["c_q"], r["c_out"],
-                                            r["c_lse"], 6)
+                                            r["c_lse"])
     np.testing.assert_array_equal(o4[1], out[1]); np.testing.assert_array_equal(cq4[1], r["c_q"][1])
     assert f4[1] == ref.FLAG_NONE and f4[0] == ref.FLAG_RECOMPUTED
 
@@ -412,7 +412,7 @@ def test_recompute_with_nothing_evicted_is_a_noop_on_the_output():
     q_t = -q_win[:, -1]
     out, a_lse, flags, _ = ref.decode(q_t, r["K_c"], r["V_c"], 20, r["c_q"], r["c_out"], r["c_lse"], 0.7, 0.85)
     out2, flags2, c_q, c_out, c_lse = ref.recalibrate(q_t, K, V, r["idx"], flags, a_lse, out, r["c_q"], r["c_out"],
-                                                      r["c_lse"], 4)
+                                                      r["c_lse"])
     np.testing.assert_array_equal(out2, out)
     assert np.all(c_lse == -np.inf) and np.all(flags2 == ref.FLAG_RECOMPUTED)
     np.testing.assert_array_equal(c_q, q_t)
@@ -446,8 +446,61 @@ def test_calibration_size_keeps_the_most_important_evicted_tokens():
     out, a_lse, flags, _ = ref.decode(q_t, r["K_c"], r["V_c"], 18, r["c_q"], r["c_out"], r["c_lse"], 0.7, 0.85)
     cal_idx = np.stack(r["evicted"])
     out2, _, _, c_out, c_lse = ref.recalibrate(q_t, K, V, r["idx"], flags, a_lse, out, r["c_q"], r["c_out"], r["c_lse"],
-                                               6, cal_idx=cal_idx)
+                                               cal_idx=cal_idx)
     for h in range(4):
         g = h // 2
         keep = np.concatenate([r["idx"][g], r["evicted"][g]])
         np.testing.assert_allclose(out2[h], sdpa64(q_t[h], K[g][keep], V[g][keep], 0.25), atol=1e-13)
+
+
+# ---- other strategies: StreamingLLM list, Alg. 1 for a known retained set ---------------------
+def test_streaming_llm_list_by_hand_and_by_properties():
+    # n = 12, B = 6, 2 sinks: positions 0,1 and the 4 most recent
+    np.testing.assert_array_equal(ref.streaming_llm_retained(12, 6, 2), [0, 1, 8, 9, 10, 11])
+    np.testing.assert_array_equal(ref.streaming_llm_retained(5, 6, 2), [0, 1, 2, 3, 4])      # fits: keep all
+    np.testing.assert_array_equal(ref.streaming_llm_retained(9, 4, 0), [5, 6, 7, 8])         # pure sliding window
+    np.testing.assert_array_equal(ref.streaming_llm_retained(9, 4, 4), [0, 1, 2, 3])         # sinks only
+    for n, B, s in [(100, 40, 32), (41, 40, 32), (4096, 512, 32)]:
+        r = ref.streaming_llm_retained(n, B, s)
+        assert len(r) == B and len(set(r.tolist())) == B and np.all(np.diff(r) > 0)
+        assert set(range(s)) <= set(r.tolist())
+        assert set(range(n - (B - s), n)) <= set(r.tolist())
+    # the same set as a top-B selection of "sinks first, then the newer the better"
+    n, B, s = 57, 20, 6
+    pref = np.where(np.arange(n) < s, 1e9, np.arange(n).astype(float))
+    top, _ = ref.select_top(pref, B)
+    np.testing.assert_array_equal(ref.streaming_llm_retained(n, B, s), top)
+
+
+def test_compress_given_merges_to_full_attention_and_gathers_the_list():
+    q_win, K, V = rand_case(n=50, w=4, D=8)
+    q_cal = RNG.standard_normal((4, 8))
+    kept = [np.array([0, 3, 7, 20, 21, 40, 48, 49]), np.array([1, 2, 30, 31, 32, 33, 46, 49])]
+    r = ref.compress_given(q_cal, K, V, 8, kept)
+    for g in range(2):
+        np.testing.assert_array_equal(r["idx"][g], kept[g])
+        np.testing.assert_array_equal(r["K_c"][g], K[g][kept[g]])
+        np.testing.assert_array_equal(r["V_c"][g], V[g][kept[g]])
+        assert set(r["evicted"][g].tolist()) == set(range(50)) - set(kept[g].tolist())
+    for h in range(4):
+        g = h // 2
+        ev = np.array(sorted(set(range(50)) - set(kept[g].tolist())))
+        np.testing.assert_allclose(r["c_out"][h], sdpa64(q_cal[h], K[g][ev], V[g][ev], 8 ** -0.5), atol=1e-13)
+        np.testing.assert_allclose(r["c_lse"][h], logsumexp(K[g][ev] @ q_cal[h] * 8 ** -0.5), atol=1e-13)
+        # Eq. 1: retained part + calibration state = attention over the whole prompt
+        o_a, l_a = ref.attention(q_cal[h], r["K_c"][g], r["V_c"][g], 8 ** -0.5)
+        full, _ = ref.merge(o_a, l_a, r["c_out"][h], r["c_lse"][h])
+        np.testing.assert_allclose(full, sdpa64(q_cal[h], K[g], V[g], 8 ** -0.5), atol=1e-13)
+    np.testing.assert_array_equal(r["c_q"], q_cal)
+    # prompt within the budget: nothing evicted, list ignored
+    r2 = ref.compress_given(q_cal, K, V, 64, None)
+    assert np.all(r2["c_lse"] == -np.inf) and np.all(r2["c_out"] == 0)
+    np.testing.assert_array_equal(r2["idx"][0], np.arange(50))
+
+
+def test_compress_given_with_the_scored_list_equals_compress():
+    q_win, K, V = rand_case(n=64, w=8, D=16)
+    r = ref.compress(q_win, K, V, 8, 24, 5)
+    r2 = ref.compress_given(q_win[:, -1], K, V, 24, [r["idx"][0], r["idx"][1]])
+    for key in ("K_c", "V_c", "c_q", "c_out", "c_lse"):
+        np.testing.assert_allclose(r2[key], r[key], atol=1e-14)
