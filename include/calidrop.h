@@ -16,8 +16,8 @@
  *
  * Conventions shared by every entry point
  *   - All data pointers are DEVICE pointers owned by the caller (for example a torch
- *     tensor's data_ptr()); they must stay alive until `stream` has executed the enqueued
- *     work.  `p` and the returned strings are HOST memory.  The library keeps no pointer
+ *     tensor's data_ptr(); the one exception is stated at calidrop_recalibrate_packed); they
+ *     must stay alive until `stream` has executed the enqueued work.  `p` and the returned strings are HOST memory.  The library keeps no pointer
  *     after a call returns; its only state is a thread-local error string and the
  *     process-wide inspection switch below.
  *   - Calls validate their arguments on the host first (no HIP call is made before
@@ -258,6 +258,49 @@ int calidrop_compress_given(const calidrop_params* p, const void* q_cal, const v
                             const int32_t* cache_offsets, int32_t* cache_lens, float* c_q,
                             float* c_out, float* c_lse, void* workspace, size_t workspace_bytes,
                             void* stream);
+
+/*
+ * Offloading KV_evict (Alg. 1 step 4 moves the evicted cache out of GPU memory instead of deleting
+ * it; Alg. 2 step 4 reloads it for the recomputation branch; Sec. 3.2).
+ *
+ * calidrop_pack_evicted - after calidrop_compress / calidrop_compress_given: write the rows of
+ * K, V that form KV_evict - or, with calib_size > 0, the calibration set (Sec. 5.3) - of every
+ * (sequence, KV head) as one contiguous block, so that the caller can move them (for example to
+ * host memory) with plain copies and release the prompt tensors.
+ *   rows per KV head of sequence b: E_b = calidrop_packed_rows(p, n_b)
+ *        = 0 if n_b <= B, else n_b - B, or min(calib_size, n_b - B) when calib_size > 0.
+ *   evict_offsets [batch+1] int32 in: sequence b owns tokens evict_offsets[b]..evict_offsets[b+1]
+ *        of the packed buffers, capacity cap_b = their difference >= E_b (a sequence whose
+ *        capacity is too small gets evict_lens[b] = 0 and nothing written).
+ *   k_e, v_e      out, dtype: inside sequence b [Hkv][cap_b][D]; the first E_b rows of each head are
+ *        written, in ascending prompt position.
+ *   evict_lens    out [batch] int32 = E_b.
+ *   evict_indices out int32, packed like k_e with one int per row: the prompt position of each row.
+ *   indices, cal_indices as written by calidrop_compress (cal_indices required when
+ *   calib_size > 0, ignored otherwise); k, v, seq_offsets, total_tokens, max_seq_len as there;
+ *   workspace >= calidrop_pack_evicted_workspace_bytes(p, max_seq_len) bytes, 256-byte aligned.
+ *
+ * calidrop_recalibrate_packed - calidrop_recalibrate reading the packed rows instead of the prompt:
+ * same results, same in/out arguments (q_t, flags, a_lse, out, c_q, c_out, c_lse).  k_e and v_e may
+ * be device memory or page-locked host memory that the device can address (hipHostMalloc): in the
+ * second case the kernel pulls the rows of the flagged KV groups over the host link while it
+ * computes, and nothing is staged in device memory.  evict_offsets / evict_lens are device memory.
+ * max_evict_len >= every evict_lens[b] (host copy; sizes the grid).  workspace >=
+ * calidrop_recalibrate_packed_workspace_bytes(p, max_evict_len) bytes, 256-byte aligned.
+ */
+int32_t calidrop_packed_rows(const calidrop_params* p, int32_t seq_len);   /* -1 on invalid params */
+size_t calidrop_pack_evicted_workspace_bytes(const calidrop_params* p, int32_t max_seq_len);
+int calidrop_pack_evicted(const calidrop_params* p, const void* k, const void* v,
+                          const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
+                          const int32_t* indices, const int32_t* cal_indices, void* k_e, void* v_e,
+                          const int32_t* evict_offsets, int32_t* evict_lens, int32_t* evict_indices,
+                          void* workspace, size_t workspace_bytes, void* stream);
+size_t calidrop_recalibrate_packed_workspace_bytes(const calidrop_params* p, int32_t max_evict_len);
+int calidrop_recalibrate_packed(const calidrop_params* p, const void* q_t, const void* k_e,
+                                const void* v_e, const int32_t* evict_offsets,
+                                const int32_t* evict_lens, int32_t max_evict_len, uint8_t* flags,
+                                const float* a_lse, void* out, float* c_q, float* c_out,
+                                float* c_lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Host string describing the last error on the calling thread ("" if none). Never NULL.      */
 const char* calidrop_last_error(void);

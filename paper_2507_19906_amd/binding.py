@@ -99,6 +99,16 @@ def lib() -> ctypes.CDLL:
         L.calidrop_compress_given.restype = ctypes.c_int
         L.calidrop_compress_given.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp,
                                               vp, sz, vp]
+        L.calidrop_packed_rows.restype = i32
+        L.calidrop_packed_rows.argtypes = [pp, i32]
+        L.calidrop_pack_evicted_workspace_bytes.restype = sz
+        L.calidrop_pack_evicted_workspace_bytes.argtypes = [pp, i32]
+        L.calidrop_pack_evicted.restype = ctypes.c_int
+        L.calidrop_pack_evicted.argtypes = [pp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.calidrop_recalibrate_packed_workspace_bytes.restype = sz
+        L.calidrop_recalibrate_packed_workspace_bytes.argtypes = [pp, i32]
+        L.calidrop_recalibrate_packed.restype = ctypes.c_int
+        L.calidrop_recalibrate_packed.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -209,6 +219,105 @@ def calidrop_compress_given(p: Params, q_cal, k, v, seq_offsets, total_tokens: i
         ctypes.byref(p), _ptr(q_cal), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
         _ptr(indices), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens), _ptr(c_q), _ptr(c_out),
         _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def calidrop_packed_rows(p: Params, seq_len: int) -> int:
+    n = lib().calidrop_packed_rows(ctypes.byref(p), seq_len)
+    if n < 0:
+        raise CalidropError(EINVAL, calidrop_last_error())
+    return n
+
+
+def calidrop_pack_evicted_workspace_bytes(p: Params, max_seq_len: int) -> int:
+    n = lib().calidrop_pack_evicted_workspace_bytes(ctypes.byref(p), max_seq_len)
+    if n == 0:
+        raise CalidropError(EINVAL, calidrop_last_error())
+    return n
+
+
+def calidrop_pack_evicted(p: Params, k, v, seq_offsets, total_tokens: int, max_seq_len: int, indices,
+                          cal_indices, k_e, v_e, evict_offsets, evict_lens, evict_indices, workspace,
+                          stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().calidrop_pack_evicted(
+        ctypes.byref(p), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len, _ptr(indices),
+        _ptr(cal_indices), _ptr(k_e), _ptr(v_e), _ptr(evict_offsets), _ptr(evict_lens), _ptr(evict_indices),
+        _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def calidrop_recalibrate_packed_workspace_bytes(p: Params, max_evict_len: int) -> int:
+    n = lib().calidrop_recalibrate_packed_workspace_bytes(ctypes.byref(p), max_evict_len)
+    if n == 0:
+        raise CalidropError(EINVAL, calidrop_last_error())
+    return n
+
+
+def calidrop_recalibrate_packed(p: Params, q_t, k_e, v_e, evict_offsets, evict_lens, max_evict_len: int,
+                                flags, a_lse, out, c_q, c_out, c_lse, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().calidrop_recalibrate_packed(
+        ctypes.byref(p), _ptr(q_t), _ptr(k_e), _ptr(v_e), _ptr(evict_offsets), _ptr(evict_lens),
+        max_evict_len, _ptr(flags), _ptr(a_lse), _ptr(out), _ptr(c_q), _ptr(c_out), _ptr(c_lse),
+        _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+class EvictedStore:
+    """The packed KV_evict of a CompressBuffers: allocation and the two calls, nothing else.
+    `host=True` moves the packed rows to page-locked host memory after packing (the offloaded
+    form); recalibrate() then reads them from there."""
+
+    def __init__(self, bufs: "CompressBuffers", seq_lens, host: bool = False):
+        p = bufs.p
+        dev = bufs.out.device
+        dt = torch.bfloat16 if p.dtype == BF16 else torch.float32
+        rows = [calidrop_packed_rows(p, int(n)) for n in seq_lens]
+        caps = [max(r, 1) for r in rows]                      # every sequence owns at least one row slot
+        offs = [0]
+        for c in caps:
+            offs.append(offs[-1] + c)
+        self.p, self.bufs, self.rows, self.host = p, bufs, rows, host
+        self.max_evict_len = max(max(rows), 1)
+        self.evict_offsets = torch.tensor(offs, dtype=torch.int32, device=dev)
+        self.evict_lens = torch.zeros(p.batch, dtype=torch.int32, device=dev)
+        tot = offs[-1] * p.n_kv_heads
+        self.evict_indices = torch.zeros(tot, dtype=torch.int32, device=dev)
+        self.k_e = torch.zeros(tot * p.head_dim, dtype=dt, device=dev)
+        self.v_e = torch.zeros(tot * p.head_dim, dtype=dt, device=dev)
+        self.offs = offs
+        self.ws_pack = torch.empty(calidrop_pack_evicted_workspace_bytes(p, bufs.max_seq_len),
+                                   dtype=torch.uint8, device=dev)
+        self.ws_recal = torch.empty(calidrop_recalibrate_packed_workspace_bytes(p, self.max_evict_len),
+                                    dtype=torch.uint8, device=dev)
+
+    def pack(self, k, v, seq_offsets, stream=None):
+        b = self.bufs
+        calidrop_pack_evicted(self.p, k, v, seq_offsets, b.total_tokens, b.max_seq_len, b.indices,
+                              b.cal_indices, self.k_e, self.v_e, self.evict_offsets, self.evict_lens,
+                              self.evict_indices, self.ws_pack, stream)
+        if self.host:                                         # offload: plain copies into pinned memory
+            k_h = torch.empty(self.k_e.shape, dtype=self.k_e.dtype, pin_memory=True)
+            v_h = torch.empty(self.v_e.shape, dtype=self.v_e.dtype, pin_memory=True)
+            k_h.copy_(self.k_e)
+            v_h.copy_(self.v_e)
+            torch.cuda.synchronize()
+            self.k_dev, self.v_dev = self.k_e, self.v_e
+            self.k_e, self.v_e = k_h, v_h
+
+    def recalibrate(self, q_t, stream=None):
+        b = self.bufs
+        calidrop_recalibrate_packed(self.p, q_t, self.k_e, self.v_e, self.evict_offsets, self.evict_lens,
+                                    self.max_evict_len, b.flags, b.a_lse, b.out, b.c_q, b.c_out, b.c_lse,
+                                    self.ws_recal, stream)
+
+    def view(self, which: str, b: int) -> torch.Tensor:
+        """[Hkv][cap_b][D] view of sequence b inside k_e / v_e ('idx': [Hkv][cap_b] positions)."""
+        Hkv, D = self.p.n_kv_heads, self.p.head_dim
+        cap = self.offs[b + 1] - self.offs[b]
+        lo = self.offs[b] * Hkv
+        if which == "idx":
+            return self.evict_indices[lo:lo + cap * Hkv].view(Hkv, cap)
+        t = self.k_e if which == "k" else self.v_e
+        return t[lo * D:(lo + cap * Hkv) * D].view(Hkv, cap, D)
 
 
 # ---- device-memory plumbing (allocation only) ----------------------------------------------

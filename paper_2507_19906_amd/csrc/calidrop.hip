@@ -3,6 +3,7 @@
 // machine without a GPU.
 #include "../../include/calidrop.h"
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdarg>
@@ -412,6 +413,81 @@ int compress_given_impl(const calidrop_params* p, const void* q_cal, const void*
   return launch_status("attend_finalize(given)");
 }
 
+int packed_rows_host(const calidrop_params* p, int n) {
+  if (n <= p->budget) return 0;
+  return p->calib_size > 0 ? std::min(p->calib_size, n - p->budget) : n - p->budget;
+}
+
+struct PackLayout { size_t bitmap, total; int W32; };
+PackLayout pack_layout(const calidrop_params* p, int32_t max_seq_len) {
+  PackLayout L{};
+  L.W32 = ceil_div(max_seq_len, 64) * 2;
+  L.bitmap = 0;
+  L.total = round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.W32 * sizeof(uint32_t));
+  return L;
+}
+
+// KV_evict (or the calibration set) of every head as contiguous rows, ready to be moved elsewhere.
+int pack_impl(const calidrop_params* p, const void* k, const void* v, const int32_t* seq_offsets, int64_t total_tokens,
+              int32_t max_seq_len, const int32_t* indices, const int32_t* cal_indices, void* k_e, void* v_e,
+              const int32_t* evict_offsets, int32_t* evict_lens, int32_t* evict_indices, char* ws,
+              const PackLayout& L, hipStream_t st) {
+  int rc;
+  const int bg = p->batch * p->n_kv_heads;
+  cd::BitmapArgs ba{};
+  ba.seq_off = seq_offsets; ba.indices = indices; ba.cal_indices = cal_indices;
+  ba.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap); ba.calib = p->calib_size;
+  ba.total_tokens = total_tokens; ba.batch = p->batch; ba.Hkv = p->n_kv_heads; ba.B = p->budget;
+  ba.max_seq_len = max_seq_len; ba.W32 = L.W32;
+  hipLaunchKernelGGL(cd::bitmap_from_indices_kernel, dim3(bg), dim3(256), 0, st, ba);
+  if ((rc = launch_status("bitmap_from_indices"))) return rc;
+  cd::PackArgs pa{};
+  pa.seq_off = seq_offsets; pa.evict_off = evict_offsets; pa.total_tokens = total_tokens; pa.batch = p->batch;
+  pa.Hkv = p->n_kv_heads; pa.B = p->budget; pa.calib = p->calib_size; pa.max_seq_len = max_seq_len; pa.W32 = L.W32;
+  pa.row_bytes = p->head_dim * (p->dtype == CALIDROP_BF16 ? 2 : 4);
+  pa.bitmap = ba.bitmap; pa.evict_lens = evict_lens; pa.evict_indices = evict_indices;
+  pa.k = k; pa.v = v; pa.k_e = k_e; pa.v_e = v_e;
+  hipLaunchKernelGGL(cd::evict_list_kernel, dim3(bg), dim3(256), 0, st, pa);
+  if ((rc = launch_status("evict_list"))) return rc;
+  const int max_rows = packed_rows_host(p, max_seq_len);
+  if (max_rows > 0) {
+    const int64_t vecs = static_cast<int64_t>(max_rows) * (pa.row_bytes / 16);
+    hipLaunchKernelGGL(cd::pack_gather_kernel, dim3(static_cast<unsigned>((vecs + 255) / 256), bg), dim3(256), 0, st, pa);
+    if ((rc = launch_status("pack_gather"))) return rc;
+  }
+  return CALIDROP_OK;
+}
+
+// Recomputation branch over the packed rows: the same streaming pass and tail as calidrop_recalibrate,
+// with the geometry of a packed buffer (offsets + live rows) instead of a prompt and its skip bitmap.
+template <typename T, int D>
+int recal_packed_impl(const calidrop_params* p, const void* q_t, const void* k_e, const void* v_e,
+                      const int32_t* evict_offsets, const int32_t* evict_lens, int32_t max_evict_len, uint8_t* flags,
+                      const float* a_lse, void* out, float* c_q, float* c_out, float* c_lse, char* ws,
+                      const DecodeLayout& L, hipStream_t st) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  int rc;
+  cd::AttendArgs aa{};
+  aa.q = q_t; aa.q_is_window = 0; aa.k = k_e; aa.v = v_e; aa.row_off = evict_offsets; aa.row_len = evict_lens;
+  aa.bitmap = nullptr; aa.total_tokens = 0; aa.batch = p->batch; aa.Hq = p->n_q_heads; aa.Hkv = p->n_kv_heads;
+  aa.G = G; aa.w = 0; aa.B = p->budget; aa.max_len = max_evict_len; aa.W32 = 0;
+  aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = logit_scale(p) * cd::kLog2e;
+  aa.only_flagged = flags;
+  aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
+  aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+  hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0,
+                     st, aa);
+  if ((rc = launch_status("attend_partial(recalibrate, packed)"))) return rc;
+  cd::FinalArgs fa{};
+  fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = evict_offsets; fa.row_len = evict_lens;
+  fa.total_tokens = 0; fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G;
+  fa.w = 0; fa.B = p->budget; fa.max_len = max_evict_len; fa.rows_per_split = L.sp.rows_per_split;
+  fa.NS = L.sp.NS; fa.calib_mode = 2; fa.q_is_window = 0; fa.q = q_t;
+  fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse; fa.out = out; fa.a_lse = const_cast<float*>(a_lse); fa.flags = flags;
+  hipLaunchKernelGGL((cd::attend_finalize_kernel<T, D>), dim3(p->n_q_heads, p->batch), dim3(D), 0, st, fa);
+  return launch_status("attend_finalize(recalibrate, packed)");
+}
+
 }  // namespace
 
 extern "C" {
@@ -640,6 +716,93 @@ int calidrop_compress_given(const calidrop_params* p_in, const void* q_cal, cons
 #define CD_DISPATCH(T, D)                                                                                         \
   return compress_given_impl<T, D>(p, q_cal, k, v, seq_offsets, total_tokens, max_seq_len, indices, k_c, v_c,     \
                                    cache_offsets, cache_lens, c_q, c_out, c_lse, ws, L, st)
+  if (p->dtype == CALIDROP_BF16) {
+    if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
+    CD_DISPATCH(cd::bf16_t, 64);
+  }
+  if (p->head_dim == 128) CD_DISPATCH(float, 128);
+  CD_DISPATCH(float, 64);
+#undef CD_DISPATCH
+}
+
+size_t calidrop_pack_evicted_workspace_bytes(const calidrop_params* p_in, int32_t max_seq_len) {
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if (load_params(p_in, &pp) != CALIDROP_OK) return 0;
+  if (check_params(p) != CALIDROP_OK) return 0;
+  if (max_seq_len < 1) { fail(CALIDROP_ESHAPE, "max_seq_len must be >= 1"); return 0; }
+  return pack_layout(p, max_seq_len).total;
+}
+
+int32_t calidrop_packed_rows(const calidrop_params* p_in, int32_t seq_len) {
+  calidrop_params pp;
+  if (load_params(p_in, &pp) != CALIDROP_OK) return -1;
+  if (check_params(&pp) != CALIDROP_OK) return -1;
+  if (seq_len < 0) { fail(CALIDROP_ESHAPE, "seq_len must be >= 0"); return -1; }
+  return packed_rows_host(&pp, seq_len);
+}
+
+int calidrop_pack_evicted(const calidrop_params* p_in, const void* k, const void* v, const int32_t* seq_offsets,
+                          int64_t total_tokens, int32_t max_seq_len, const int32_t* indices,
+                          const int32_t* cal_indices, void* k_e, void* v_e, const int32_t* evict_offsets,
+                          int32_t* evict_lens, int32_t* evict_indices, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+  int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
+  if ((rc = check_params(p))) return rc;
+  if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
+  const struct { const void* ptr; const char* name; } req[] = {
+      {k, "k"}, {v, "v"}, {seq_offsets, "seq_offsets"}, {indices, "indices"}, {k_e, "k_e"}, {v_e, "v_e"},
+      {evict_offsets, "evict_offsets"}, {evict_lens, "evict_lens"}, {evict_indices, "evict_indices"}};
+  for (const auto& r : req)
+    if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
+  for (const auto& r : req)
+    if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  if (p->calib_size > 0) {
+    if (!cal_indices) return fail(CALIDROP_EINVAL, "cal_indices is NULL although calib_size is %d", p->calib_size);
+    if (!aligned16(cal_indices)) return fail(CALIDROP_EALIGN, "cal_indices is not 16-byte aligned");
+  } else {
+    cal_indices = nullptr;
+  }
+  const PackLayout L = pack_layout(p, max_seq_len);
+  if (!workspace || workspace_bytes < L.total)
+    return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
+                L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
+  return pack_impl(p, k, v, seq_offsets, total_tokens, max_seq_len, indices, cal_indices, k_e, v_e, evict_offsets,
+                   evict_lens, evict_indices, static_cast<char*>(workspace), L, static_cast<hipStream_t>(stream));
+}
+
+size_t calidrop_recalibrate_packed_workspace_bytes(const calidrop_params* p_in, int32_t max_evict_len) {
+  return calidrop_decode_workspace_bytes(p_in, max_evict_len);      // the same split partials
+}
+
+int calidrop_recalibrate_packed(const calidrop_params* p_in, const void* q_t, const void* k_e, const void* v_e,
+                                const int32_t* evict_offsets, const int32_t* evict_lens, int32_t max_evict_len,
+                                uint8_t* flags, const float* a_lse, void* out, float* c_q, float* c_out, float* c_lse,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
+  if ((rc = check_params(p))) return rc;
+  if (max_evict_len < 1) return fail(CALIDROP_ESHAPE, "max_evict_len must be >= 1 (got %d)", max_evict_len);
+  const struct { const void* ptr; const char* name; } req[] = {
+      {q_t, "q_t"}, {k_e, "k_e"}, {v_e, "v_e"}, {evict_offsets, "evict_offsets"}, {evict_lens, "evict_lens"},
+      {flags, "flags"}, {a_lse, "a_lse"}, {out, "out"}, {c_q, "c_q"}, {c_out, "c_out"}, {c_lse, "c_lse"}};
+  for (const auto& r : req)
+    if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
+  for (const auto& r : req)
+    if (r.ptr != flags && !aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  const DecodeLayout L = decode_layout(p, max_evict_len);
+  if (!workspace || workspace_bytes < L.total)
+    return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
+                L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+#define CD_DISPATCH(T, D)                                                                                        \
+  return recal_packed_impl<T, D>(p, q_t, k_e, v_e, evict_offsets, evict_lens, max_evict_len, flags, a_lse, out,   \
+                                 c_q, c_out, c_lse, ws, L, st)
   if (p->dtype == CALIDROP_BF16) {
     if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
     CD_DISPATCH(cd::bf16_t, 64);

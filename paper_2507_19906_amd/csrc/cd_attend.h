@@ -317,7 +317,7 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
   __shared__ float red[4];
   if (a.calib_mode == 2 && a.flags[b * a.Hq + h] != 2) return;      // only heads flagged for recomputation
   int rows;
-  if (a.calib_mode) {
+  if (!a.row_len) {                   // rows of a prompt (minus the window); else live rows of a packed buffer
     int off0;
     int n = seq_len_checked(a.row_off, b, a.max_len, a.total_tokens, off0);
     rows = (n > a.B) ? n - a.w : 0;

@@ -160,3 +160,34 @@ def test_given_strategy_entry_points_validate_on_the_host():
     assert L.calidrop_compress_given(ctypes.byref(p), *bad, A, need, None) == cd.EALIGN
     assert L.calidrop_compress_given(ctypes.byref(good(calib_size=8)), *args, A, need, None) == cd.EUNSUPPORTED
     assert L.calidrop_compress_given(ctypes.byref(good(head_dim=96)), *args, A, need, None) == cd.EUNSUPPORTED
+
+
+def test_offload_entry_points_validate_on_the_host():
+    A = 4096
+    L = cd.lib()
+    p = good()
+    assert cd.calidrop_packed_rows(p, 400) == 0 and cd.calidrop_packed_rows(p, 512) == 0
+    assert cd.calidrop_packed_rows(p, 8192) == 8192 - 512
+    assert cd.calidrop_packed_rows(good(calib_size=100), 8192) == 100
+    assert cd.calidrop_packed_rows(good(calib_size=100), 560) == 48
+    with pytest.raises(cd.CalidropError):
+        cd.calidrop_packed_rows(good(head_dim=100), 8192)
+    needp = cd.calidrop_pack_evicted_workspace_bytes(p, 8192)
+    assert needp > 0 and needp % 256 == 0
+    args = [A, A, A, 16384, 8192, A, None, A, A, A, A, A]
+    assert L.calidrop_pack_evicted(ctypes.byref(p), *args, A, needp - 1, None) == cd.EWORKSPACE
+    bad = list(args); bad[9] = None
+    assert L.calidrop_pack_evicted(ctypes.byref(p), *bad, A, needp, None) == cd.EINVAL
+    assert "evict_offsets is NULL" in cd.calidrop_last_error()
+    assert L.calidrop_pack_evicted(ctypes.byref(good(calib_size=8)), *args, A, needp, None) == cd.EINVAL
+    assert "cal_indices" in cd.calidrop_last_error()
+    needr = cd.calidrop_recalibrate_packed_workspace_bytes(p, 7680)
+    assert needr > 0
+    args = [A, A, A, A, A, 7680, A, A, A, A, A, A]
+    assert L.calidrop_recalibrate_packed(ctypes.byref(p), *args, A, needr - 1, None) == cd.EWORKSPACE
+    bad = list(args); bad[6] = None
+    assert L.calidrop_recalibrate_packed(ctypes.byref(p), *bad, A, needr, None) == cd.EINVAL
+    bad = list(args); bad[5] = 0
+    assert L.calidrop_recalibrate_packed(ctypes.byref(p), *bad, A, needr, None) == cd.ESHAPE
+    bad = list(args); bad[1] = A + 2
+    assert L.calidrop_recalibrate_packed(ctypes.byref(p), *bad, A, needr, None) == cd.EALIGN

@@ -157,3 +157,93 @@ def test_out_of_range_entries_are_memory_safe():
     Kc = H.to64(bufs.cache_view("k", 0))
     assert np.array_equal(Kc[0, 5], K[0, 0]) and np.array_equal(Kc[1, 7], K[1, 399])     # clamped rows
     assert np.array_equal(Kc[0, 6], K[0, 18])
+
+
+# ---- offloading KV_evict: packed rows, and the recomputation branch reading them -------------------
+def check_packed(wl, x, bufs, store, orc_evicted):
+    """Packed lists and rows vs the oracle's evicted / calibration sets (bit-exact)."""
+    for b, n in enumerate(wl.seq_lens):
+        rows = store.rows[b]
+        assert int(store.evict_lens[b].item()) == rows
+        if rows == 0:
+            continue
+        K = H.to64(synth.seq_view(x["k"], wl, b))
+        V = H.to64(synth.seq_view(x["v"], wl, b))
+        gi = store.view("idx", b).cpu().numpy()[:, :rows]
+        ke = H.to64(store.view("k", b))[:, :rows]
+        ve = H.to64(store.view("v", b))[:, :rows]
+        for g in range(wl.n_kv_heads):
+            want = orc_evicted[b][g]
+            assert np.array_equal(gi[g], want), (b, g)
+            assert np.array_equal(ke[g], K[g][want]) and np.array_equal(ve[g], V[g][want])
+
+
+@pytest.mark.parametrize("wl,m,host", [
+    (small("bf16", 8, 2, 128, [900, 40, 2100], 16, 128, 5, T=6, name="pack_varlen_bf16"), 0, False),
+    (small("bf16", 8, 2, 128, [900, 40, 2100], 16, 128, 5, T=6, name="pack_varlen_bf16_host"), 0, True),
+    (small("fp32", 8, 2, 64, [1031, 97], 16, 96, 3, T=4, name="pack_fp32_calib"), 50, False),
+    (small("fp32", 8, 2, 64, [1031, 97], 16, 96, 3, T=4, name="pack_fp32_calib_host"), 50, True),
+    (small("bf16", 32, 8, 128, [4099], 32, 512, 7, T=3, name="pack_llama_shape"), 0, True),
+], ids=lambda v: v.name if hasattr(v, "name") else str(v))
+def test_packed_evicted_rows_and_recomputation_from_them(wl, m, host):
+    x = to_dev(synth.make_inputs(wl, 21))
+    bufs = H.gpu_compress(wl, x, calib_size=m)
+    rep = {}
+    orc_evicted = []
+    for b in range(wl.batch):
+        orc, _ = H.check_compress(wl, x, bufs, b, report=rep)
+        orc_evicted.append(orc["evicted"])
+    assert rep.get("tie_band_heads", 0) == 0 and rep.get("tie_band_cal_heads", 0) == 0
+    store = cd.EvictedStore(bufs, wl.seq_lens, host=host)
+    store.pack(x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    check_packed(wl, x, bufs, store, orc_evicted)
+    # a twin that recomputes from the prompt tensors must agree bit for bit at every step
+    twin = H.gpu_compress(wl, x, calib_size=m)
+    for t in range(wl.decode_steps):
+        q_t = x["q_dec"][t]
+        bufs.decode(q_t)
+        twin.decode(q_t)
+        torch.cuda.synchronize()
+        before = H.snapshot_state(bufs)
+        store.recalibrate(q_t)
+        twin.recalibrate(q_t, x["k"], x["v"], x["seq_offsets"])
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
+        for name in ("out", "flags", "c_q", "c_out", "c_lse"):
+            a, c = getattr(bufs, name), getattr(twin, name)
+            if name in ("c_out", "c_lse", "out"):      # different split points: rounding-level differences only
+                fin = torch.isfinite(c.float())
+                assert torch.equal(torch.isfinite(a.float()), fin)
+                assert (a.float() - c.float())[fin].abs().max().item() <= (2e-2 if wl.dtype == "bf16" else 1e-5), name
+            else:
+                assert torch.equal(a, c), name
+    print(wl.name, {k: v for k, v in rep.items() if k != "flags"}, flush=True)
+    assert wl.decode_steps < 4 or rep["recal_heads"] > 0
+
+
+def test_packing_a_streaming_llm_cache():
+    wl = small("bf16", 8, 2, 128, [1500, 60], 16, 128, 5, T=3, name="pack_slm")
+    x = to_dev(synth.make_inputs(wl, 8))
+    p = H.params_for(wl)
+    bufs = cd.CompressBuffers(p, wl.seq_lens, DEV)
+    bufs.streaming_indices(32, x["seq_offsets"])
+    q_cal = x["q_win"][:, :, -1].contiguous()
+    bufs.compress_given(q_cal, x["k"], x["v"], x["seq_offsets"])
+    store = cd.EvictedStore(bufs, wl.seq_lens, host=True)
+    store.pack(x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    ev = [[np.arange(32, 1500 - 96)] * 2, None]
+    check_packed(wl, x, bufs, store, ev)
+    rep = {}
+    for t in range(wl.decode_steps):
+        q_t = x["q_dec"][t]
+        bufs.decode(q_t)
+        torch.cuda.synchronize()
+        before = H.snapshot_state(bufs)
+        store.recalibrate(q_t)
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
+    print(wl.name, rep, flush=True)
