@@ -250,6 +250,40 @@ def main():
             times.append(e0.elapsed_time(e1) * 1e3)
         recal_us = sorted(times)[len(times) // 2]
 
+    # the same branch reading KV_evict from its packed (offloadable) form: device-resident, then
+    # page-locked host memory pulled over the host link by the kernel itself (2 layers' worth)
+    packed = None
+    if not args.no_extra:
+        L2 = min(2, wl.batch)
+        wl3 = synth.config(3, layers=L2, budget=args.budget, decode_steps=1)
+        p3 = cd.make_params(dtype=wl3.dtype, batch=wl3.batch, n_q_heads=wl3.n_q_heads, n_kv_heads=wl3.n_kv_heads,
+                            head_dim=wl3.head_dim, window=wl3.window, budget=wl3.budget, pool_kernel=wl3.pool_kernel,
+                            theta1=wl3.theta1, theta2=wl3.theta2)
+        b3 = cd.CompressBuffers(p3, wl3.seq_lens, dev)
+        nel = L2 * wl.seq_lens[0] * wl.n_kv_heads * wl.head_dim
+        k3, v3, so3 = x["k"][:nel], x["v"][:nel], x["seq_offsets"][:L2 + 1].clone()
+        q3 = x["q_dec"][0][:L2].contiguous()
+        b3.compress(x["q_win"][:L2].contiguous(), k3, v3, so3, stream=stream)
+        packed = {}
+        for where in ("device", "host"):
+            store = cd.EvictedStore(b3, wl3.seq_lens, host=(where == "host"))
+            store.pack(k3, v3, so3, stream=stream)
+            b3.decode(q3, stream=stream)
+            times = []
+            for _ in range(4):
+                b3.flags.fill_(cd.FLAG_RECOMPUTE)
+                e0, e1 = ev(), ev()
+                e0.record(stream)
+                store.recalibrate(q3, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) * 1e3)
+            us = sorted(times)[len(times) // 2]
+            nbytes = 2 * store.k_e.numel() * store.k_e.element_size()
+            packed[where] = {"us_per_layer": us / L2, "GBps": nbytes / us / 1e3, "bytes_per_layer": nbytes // L2}
+            del store
+        del b3
+
     gbps = dbytes / (dec * 1e-3) / 1e9
     # window scoring (the two MFMA passes of compress): 2*Hq*w*n*D flop per layer and pass
     score_flop = 2.0 * wl.n_q_heads * wl.window * wl.seq_lens[0] * wl.head_dim * wl.batch
@@ -275,6 +309,7 @@ def main():
         "scoring_algorithmic_TFLOP": score_flop / 1e12,
         "recalibrate_all_heads_us_per_layer": None if recal_us is None else recal_us / wl.batch,
         "recalibrate_all_heads_GBps": None if recal_us is None else compress_bytes(wl) / recal_us / 1e3,
+        "recalibrate_all_heads_from_packed_evicted": packed,
         "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel<bf16,128,8>",
                      "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
                      # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of this kernel on this workload,
