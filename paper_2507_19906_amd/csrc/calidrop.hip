@@ -104,8 +104,8 @@ SplitPlan plan_splits(int heads_kv_total, int max_rows) {
 }
 
 struct CompressLayout {
-  size_t rowpart, row_lse, vote, score, bitmap, cal_logit, part_o, part_ml, total;
-  int NRB, NCH, W32, chunk_keys, zstride;
+  size_t rowpart, row_lse, vote, score, bitmap, cal_logit, part_o, part_ml, sel_hist, sel_cnt, total;
+  int NRB, NCH, W32, chunk_keys, zstride, NSEG;
   SplitPlan sp;
 };
 
@@ -136,6 +136,10 @@ CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, i
   const size_t slots = static_cast<size_t>(p->batch) * p->n_q_heads * L.sp.NS;
   L.part_o = off;  off += round256(slots * p->head_dim * sizeof(float));
   L.part_ml = off; off += round256(slots * sizeof(float2));
+  // multi-workgroup selection (prefixes beyond the single-workgroup variant): histograms and counts
+  L.NSEG = ceil_div(std::max(max_seq_len - p->window, 1), cd::kWideSeg);
+  L.sel_hist = off; off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * 2 * 4 * 256 * sizeof(uint32_t));
+  L.sel_cnt = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.NSEG * 4 * sizeof(uint32_t));
   L.total = off;
   return L;
 }
@@ -232,10 +236,24 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
     }
     hipLaunchKernelGGL(cd::select_gather_lds_kernel<cd::kSelThreads>, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
   } else {
+    cd::WideArgs wa{};
+    wa.s = se; wa.NSEG = L.NSEG;
+    wa.hist = reinterpret_cast<uint32_t*>(ws + L.sel_hist);
+    wa.seg_cnt = reinterpret_cast<uint32_t*>(ws + L.sel_cnt);
+    sa.zero_words = wa.hist; sa.zero_per_head = 2 * 4 * 256;
     hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
     if ((rc = launch_status("pool_scores"))) return rc;
-    hipLaunchKernelGGL(cd::select_gather_kernel, dim3(bg), dim3(cd::kSelThreads), 0, st, se);
-    if ((rc = launch_status("select"))) return rc;
+    const dim3 grid_w(L.NSEG, bg);
+    if (max_seq_len > p->budget) {
+      for (wa.pass = 0; wa.pass < 4; ++wa.pass) {
+        hipLaunchKernelGGL(cd::wide_hist_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
+        if ((rc = launch_status("wide_hist"))) return rc;
+      }
+      hipLaunchKernelGGL(cd::wide_count_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
+      if ((rc = launch_status("wide_count"))) return rc;
+    }
+    hipLaunchKernelGGL(cd::wide_emit_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
+    if ((rc = launch_status("wide_emit"))) return rc;
     const int vecs = p->budget * (se.row_bytes / 16);
     hipLaunchKernelGGL(cd::gather_kv_kernel, dim3(ceil_div(vecs, 256), bg), dim3(256), 0, st, se);
   }

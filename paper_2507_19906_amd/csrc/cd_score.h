@@ -34,6 +34,8 @@ struct ScoreArgs {
   float* score;         // [total_tokens*Hkv]
   float* cal_logit;     // [batch*Hq][zstride] log2-unit logits of the last window query, or NULL
   int zstride;
+  uint32_t* zero_words; // pool_scores_kernel only: [batch*Hkv][zero_per_head] words to clear, or NULL
+  int zero_per_head;
 };
 
 // Length of sequence b as the kernels use it: 0 when the offsets break the host-side contract
@@ -394,6 +396,8 @@ __global__ __launch_bounds__(256) void pool_scores_kernel(ScoreArgs a) {
   const int b = bg / a.Hkv;
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
+  if (blockIdx.x == 0 && a.zero_words)          // clears the selection histograms of this head
+    for (int t = threadIdx.x; t < a.zero_per_head; t += 256) a.zero_words[static_cast<int64_t>(bg) * a.zero_per_head + t] = 0u;
   if (n <= a.B) return;
   const int P = n - a.w;
   const int j = blockIdx.x * 256 + threadIdx.x;

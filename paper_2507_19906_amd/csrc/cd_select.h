@@ -11,9 +11,10 @@
 // calibration size m is set, k_sel + m (retained + the m most important evicted tokens, which
 // form the calibration set; everything below is dropped for good).
 //
-// Two variants: select_gather_lds_kernel (prefix up to 32768 positions: pools the votes itself,
-// keys in registers) and select_gather_kernel (longer prefixes: keys read from the pooled-score
-// buffer that pool_scores_kernel wrote).
+// Two variants: select_gather_lds_kernel (prefix up to 32768 positions: one workgroup per head
+// pools the votes itself and keeps the keys in registers) and the wide_* kernels (longer
+// prefixes: many workgroups per head, keys read from the pooled-score buffer that
+// pool_scores_kernel wrote, histograms and counts combined in global memory).
 #pragma once
 #include "cd_common.h"
 #include "cd_score.h"
@@ -157,116 +158,263 @@ struct Cut {
   }
 };
 
-// Variant for prefixes too long for LDS: the pooled scores are read from the buffer that
-// pool_scores_kernel wrote.  The radix sweeps are strided (thread j mod 1024); the compaction
-// gives wave w the contiguous positions [w*seg, (w+1)*seg): a counting sweep, one barrier, an
-// emitting sweep.
-__global__ __launch_bounds__(kSelThreads) void select_gather_kernel(SelectArgs a) {
-  const int bg = blockIdx.x;
-  const int g = bg % a.Hkv;
-  const int b = bg / a.Hkv;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+// ---- long prefixes: selection spread over many workgroups ------------------------------------
+// One workgroup per head cannot sweep hundreds of thousands of scores quickly, so the prefix is
+// cut into segments of kWideSeg positions, one workgroup each, and the radix select becomes a
+// chain of launches that meet in global memory: four histogram passes (each adds its segment's
+// digit counts to the head's 256-bin histogram of that pass), a count pass (greater / equal
+// counts per segment once the thresholds are known) and an emit pass (ordered compaction:
+// counts of the earlier segments + a scan inside the segment).  Nothing waits inside a kernel;
+// every workgroup re-derives the decided digits from the finished histograms of earlier passes.
+constexpr int kWideThreads = 256;
+constexpr int kWidePer = 32;                          // positions per thread (= one bitmap word)
+constexpr int kWideSeg = kWideThreads * kWidePer;     // positions per workgroup
+
+struct WideArgs {
+  SelectArgs s;
+  uint32_t* hist;        // [batch*Hkv][2 cuts][4 passes][256], zero before the first pass
+  uint32_t* seg_cnt;     // [batch*Hkv][NSEG][4]: greater1, equal1, greater2, equal2 per segment
+  int NSEG, pass;
+};
+
+// The bin of a finished 256-bin histogram in which the count from the top reaches `remaining`;
+// updates prefix / remaining like one radix pass.  Lane l holds bins 4l..4l+3 in `hb`.  Called
+// by all 64 lanes of a wave.
+__device__ __forceinline__ void wide_pick(const u32x4 hb, int shift, uint32_t& prefix, uint32_t& remaining) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t h0 = hb[0], h1 = hb[1], h2 = hb[2], h3 = hb[3];
+  const uint32_t mine = h0 + h1 + h2 + h3;
+  uint32_t acc = mine;
+#pragma unroll
+  for (int sft = 1; sft < 64; sft <<= 1) {          // suffix-inclusive scan over lanes
+    const uint32_t o = __shfl_down(acc, sft);
+    if (lane + sft < 64) acc += o;
+  }
+  const uint32_t above = acc - mine;
+  const bool hit = above < remaining && remaining <= acc;
+  uint32_t cum = above;
+  int bin = 0;
+  if (cum + h3 >= remaining) bin = 3;
+  else { cum += h3; if (cum + h2 >= remaining) bin = 2;
+    else { cum += h2; if (cum + h1 >= remaining) bin = 1; else { cum += h1; bin = 0; } } }
+  const uint64_t who = __ballot(hit);
+  if (who == 0) return;                              // inconsistent histogram: leave the digit 0
+  const int src = __ffsll(static_cast<long long>(who)) - 1;
+  const uint32_t digit = __shfl(static_cast<uint32_t>(4 * lane + bin), src);
+  const uint32_t rem = __shfl(remaining - cum, src);
+  prefix |= digit << shift;
+  remaining = rem;
+}
+
+struct WideHead {
+  int n, P, k_sel, b, g, bg;
+  int64_t head_tok;
+  bool all2;             // no second cut (no calibration size, or it covers every evicted token)
+};
+
+__device__ __forceinline__ WideHead wide_head(const SelectArgs& a, int bg) {
+  WideHead h;
+  h.bg = bg; h.g = bg % a.Hkv; h.b = bg / a.Hkv;
   int off0;
-  const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
-  int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
-  int32_t* cal = (a.cal_indices && a.calib > 0) ? a.cal_indices + static_cast<int64_t>(bg) * a.calib : nullptr;
-  const int len = min(n, a.B);
-  if (g == 0 && tid == 0) a.cache_lens[b] = len;
-  const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
+  h.n = seq_len_checked(a.seq_off, h.b, a.max_seq_len, a.total_tokens, off0);
+  h.P = h.n - a.w; h.k_sel = a.B - a.w;
+  h.head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(h.g) * h.n;
+  h.all2 = a.calib <= 0 || h.k_sel + a.calib >= h.P;
+  return h;
+}
 
-  __shared__ RadixShared sh;
-  constexpr int NWV = kSelThreads / 64;
-  __shared__ uint32_t wave_cnt[4][NWV];      // greater/equal counts for the two cuts, per wave
+// Digits decided by passes 0..upto-1, for both cuts.  The histograms of all those passes are
+// fetched together (one round trip); only the scans depend on each other.
+__device__ __forceinline__ void wide_derive(const WideArgs& a, const WideHead& h, int upto, uint32_t (&prefix)[2],
+                                            uint32_t (&remaining)[2]) {
+  const int lane = threadIdx.x & 63;
+  const int ncut = h.all2 ? 1 : 2;
+  u32x4 hb[2][4];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps)
+      if (c < ncut && ps < upto)
+        hb[c][ps] = ld16(a.hist + ((static_cast<int64_t>(h.bg) * 2 + c) * 4 + ps) * 256 + 4 * lane);
+  prefix[0] = prefix[1] = 0;
+  remaining[0] = h.k_sel;
+  remaining[1] = h.k_sel + a.s.calib;
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps)
+      if (c < ncut && ps < upto) wide_pick(hb[c][ps], 24 - 8 * ps, prefix[c], remaining[c]);
+}
 
-  if (n <= a.B) {                       // nothing to evict: keep every position
-    for (int r = tid; r < a.B; r += kSelThreads) idx[r] = (r < n) ? r : -1;
-    if (cal) for (int r = tid; r < a.calib; r += kSelThreads) cal[r] = -1;
-  } else {
-    const int P = n - a.w;
-    const int k_sel = a.B - a.w;
-    const uint32_t* gkey = reinterpret_cast<const uint32_t*>(a.score) + head_tok;
-    constexpr int kDepth = 16;                   // independent loads per thread in flight
-    auto each_key = [&](auto&& visit) {
-      for (int j0 = tid; j0 < P; j0 += kDepth * kSelThreads) {
-        uint32_t u[kDepth];
+__global__ __launch_bounds__(kWideThreads) void wide_hist_kernel(WideArgs a) {
+  const WideHead h = wide_head(a.s, blockIdx.y);
+  const int lo = blockIdx.x * kWideSeg;
+  if (h.n <= a.s.B || lo >= h.P) return;
+  const int tid = threadIdx.x;
+  const uint32_t* gkey = reinterpret_cast<const uint32_t*>(a.s.score) + h.head_tok;
+  uint32_t u[kWidePer];                 // issued first: in flight while the digits are derived
 #pragma unroll
-        for (int q = 0; q < kDepth; ++q) u[q] = (j0 + q * kSelThreads < P) ? gkey[j0 + q * kSelThreads] : 0u;
+  for (int q = 0; q < kWidePer; ++q) { const int j = lo + tid + q * kWideThreads; u[q] = j < h.P ? gkey[j] : 0u; }
+  uint32_t prefix[2], remaining[2];
+  wide_derive(a, h, a.pass, prefix, remaining);
+  __shared__ uint32_t s_hist[2][256];
+  s_hist[0][tid] = 0; s_hist[1][tid] = 0;
+  __syncthreads();
+  const int shift = 24 - 8 * a.pass;
+  const uint32_t himask = a.pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+  for (int c = 0; c < (h.all2 ? 1 : 2); ++c) {
+    uint32_t run_bin = 0, run_len = 0;               // run-length compressed updates
 #pragma unroll
-        for (int q = 0; q < kDepth; ++q)
-          if (j0 + q * kSelThreads < P) visit(u[q]);
-      }
-    };
-    Cut c1, c2;                          // c1: retained prefix tokens; c2: retained + calibration set
-    c1.all = false;
-    radix_select<kSelThreads>(sh, k_sel, each_key, c1.thr, c1.need_eq);
-    c2.all = a.calib <= 0 || k_sel + a.calib >= P;
-    c2.thr = 0; c2.need_eq = 0;
-    if (!c2.all) radix_select<kSelThreads>(sh, k_sel + a.calib, each_key, c2.thr, c2.need_eq);
-
-    uint32_t* bm = a.bitmap + static_cast<int64_t>(bg) * a.W32;
-    const int seg = ((n + NWV - 1) / NWV + 63) / 64 * 64;
-    const int seg_lo = wv * seg, seg_hi = min(n, seg_lo + seg);
-    const int key_hi = min(P, seg_hi);    // candidates of this wave: prefix positions of its segment
-    uint32_t cnt[4] = {0, 0, 0, 0};       // gt1, eq1, gt2, eq2 of this wave's segment
-    constexpr int kSl = 8;                // 64-position slices per iteration (loads in flight)
-    for (int base = seg_lo; base < seg_hi; base += kSl * 64) {
-      uint32_t u[kSl];
-#pragma unroll
-      for (int q = 0; q < kSl; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? gkey[j] : 0u; }
-#pragma unroll
-      for (int q = 0; q < kSl; ++q) {
-        const bool in = base + q * 64 + lane < key_hi;
-        cnt[0] += __popcll(__ballot(in && u[q] > c1.thr));
-        cnt[1] += __popcll(__ballot(in && u[q] == c1.thr));
-        cnt[2] += __popcll(__ballot(in && u[q] > c2.thr));
-        cnt[3] += __popcll(__ballot(in && u[q] == c2.thr));
-      }
-    }
-    if (lane == 0) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) wave_cnt[q][wv] = cnt[q];
-    }
-    __syncthreads();
-    uint32_t pre[4] = {0, 0, 0, 0};       // counts over all earlier positions (wave-uniform)
-    for (int ww = 0; ww < wv; ++ww)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) pre[q] += wave_cnt[q][ww];
-    const uint64_t below = (1ull << lane) - 1ull;
-    for (int base = seg_lo; base < seg_hi; base += kSl * 64) {
-      uint32_t u[kSl];
-#pragma unroll
-      for (int q = 0; q < kSl; ++q) { const int j = base + q * 64 + lane; u[q] = (j < key_hi) ? gkey[j] : 0u; }
-#pragma unroll
-      for (int q = 0; q < kSl; ++q) {
-        const int j = base + q * 64 + lane;
-        if (base + q * 64 < seg_hi) {
-          const bool in = j < key_hi;
-          const uint64_t m0 = __ballot(in && u[q] > c1.thr), m1 = __ballot(in && u[q] == c1.thr);
-          const uint64_t m2 = __ballot(in && u[q] > c2.thr), m3 = __ballot(in && u[q] == c2.thr);
-          const uint32_t gt1 = pre[0] + __popcll(m0 & below), eq1 = pre[1] + __popcll(m1 & below);
-          const uint32_t gt2 = pre[2] + __popcll(m2 & below), eq2 = pre[3] + __popcll(m3 & below);
-          const bool keep = in && c1.inside(u[q], eq1);
-          const bool calib = in && !keep && c2.inside(u[q], eq2);
-          if (keep) idx[c1.rank(j, gt1, eq1)] = j;
-          if (calib && cal) cal[c2.rank(j, gt2, eq2) - c1.rank(j, gt1, eq1)] = j;
-          // bit = skip in the calibration pass: everything that is not in the calibration set
-          const uint64_t mk = __ballot(!calib);
-          if (lane == 0) {
-            bm[(base + q * 64) >> 5] = static_cast<uint32_t>(mk);
-            bm[((base + q * 64) >> 5) + 1] = static_cast<uint32_t>(mk >> 32);
-          }
-          pre[0] += __popcll(m0); pre[1] += __popcll(m1); pre[2] += __popcll(m2); pre[3] += __popcll(m3);
-        }
+    for (int q = 0; q < kWidePer; ++q) {
+      if (lo + tid + q * kWideThreads < h.P && (u[q] & himask) == prefix[c]) {
+        const uint32_t bin = (u[q] >> shift) & 0xFF;
+        if (bin != run_bin && run_len) { atomicAdd(&s_hist[c][run_bin], run_len); run_len = 0; }
+        run_bin = bin;
+        ++run_len;
       }
     }
-    for (int r = tid; r < a.w; r += kSelThreads) idx[k_sel + r] = P + r;   // the window is always kept
-    if (cal) {                                                              // pad a short calibration set
-      const int n_cal = min(a.calib, P - k_sel);
-      for (int r = n_cal + tid; r < a.calib; r += kSelThreads) cal[r] = -1;
+    if (run_len) atomicAdd(&s_hist[c][run_bin], run_len);
+  }
+  __syncthreads();
+  for (int c = 0; c < (h.all2 ? 1 : 2); ++c) {
+    const uint32_t v = s_hist[c][tid];
+    if (v) atomicAdd(a.hist + ((static_cast<int64_t>(h.bg) * 2 + c) * 4 + a.pass) * 256 + tid, v);
+  }
+}
+
+__device__ __forceinline__ void wide_cuts(const WideArgs& a, const WideHead& h, Cut& c1, Cut& c2) {
+  uint32_t prefix[2], remaining[2];
+  wide_derive(a, h, 4, prefix, remaining);
+  c1.all = false; c1.thr = prefix[0]; c1.need_eq = remaining[0];
+  c2.all = h.all2; c2.thr = h.all2 ? 0u : prefix[1]; c2.need_eq = h.all2 ? 0u : remaining[1];
+}
+
+// Sum over the workgroup of four counters; result in every thread.  `red` holds 4 x 4 words.
+__device__ __forceinline__ void wide_block_sum4(uint32_t (&v)[4], uint32_t (*red)[4]) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) v[q] += __shfl_xor(v[q], sft);
+  __syncthreads();
+  if (lane == 0)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) red[wv][q] = v[q];
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) v[q] = red[0][q] + red[1][q] + red[2][q] + red[3][q];
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_count_kernel(WideArgs a) {
+  const WideHead h = wide_head(a.s, blockIdx.y);
+  const int lo = blockIdx.x * kWideSeg;
+  if (h.n <= a.s.B || lo >= h.P) return;
+  const int tid = threadIdx.x;
+  const uint32_t* gkey = reinterpret_cast<const uint32_t*>(a.s.score) + h.head_tok;
+  uint32_t u[kWidePer];
+#pragma unroll
+  for (int q = 0; q < kWidePer; ++q) { const int j = lo + tid + q * kWideThreads; u[q] = j < h.P ? gkey[j] : 0u; }
+  Cut c1, c2;
+  wide_cuts(a, h, c1, c2);
+  uint32_t cnt[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int q = 0; q < kWidePer; ++q)
+    if (lo + tid + q * kWideThreads < h.P) {
+      cnt[0] += u[q] > c1.thr; cnt[1] += u[q] == c1.thr;
+      cnt[2] += u[q] > c2.thr; cnt[3] += u[q] == c2.thr;
+    }
+  __shared__ uint32_t red[4][4];
+  wide_block_sum4(cnt, red);
+  if (tid < 4) a.seg_cnt[(static_cast<int64_t>(h.bg) * a.NSEG + blockIdx.x) * 4 + tid] = cnt[tid];
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_emit_kernel(WideArgs a) {
+  const SelectArgs& s = a.s;
+  const WideHead h = wide_head(s, blockIdx.y);
+  const int seg = blockIdx.x;
+  const int lo = seg * kWideSeg;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int32_t* idx = s.indices + static_cast<int64_t>(h.bg) * s.B;
+  int32_t* cal = (s.cal_indices && s.calib > 0) ? s.cal_indices + static_cast<int64_t>(h.bg) * s.calib : nullptr;
+  if (seg == 0 && h.g == 0 && tid == 0) s.cache_lens[h.b] = min(h.n, s.B);
+  if (h.n <= s.B) {                     // nothing to evict: keep every position
+    if (seg == 0) {
+      for (int r = tid; r < s.B; r += kWideThreads) idx[r] = (r < h.n) ? r : -1;
+      if (cal) for (int r = tid; r < s.calib; r += kWideThreads) cal[r] = -1;
+    }
+    return;
+  }
+  if (seg == 0) {
+    for (int r = tid; r < s.w; r += kWideThreads) idx[h.k_sel + r] = h.P + r;    // the window is always kept
+    if (cal) {                                                                   // pad a short calibration set
+      const int n_cal = min(s.calib, h.P - h.k_sel);
+      for (int r = n_cal + tid; r < s.calib; r += kWideThreads) cal[r] = -1;
     }
   }
-  // the gather of the retained rows is a separate, fully parallel launch (gather_kv_kernel):
-  // one workgroup per head cannot move a budget of thousands of rows fast enough
+  if (lo >= h.P) return;
+  // keys of the segment: coalesced loads, then blocked ownership (thread t: positions lo+32t..)
+  // through LDS, padded by one word per 32 so that the stride-32 reads do not collide
+  __shared__ uint32_t s_key[kWideSeg + kWideSeg / 32];
+  __shared__ uint32_t red[4][4];
+  __shared__ uint32_t wave_tot[2][kWideThreads / 64];
+  auto pad = [](int j) { return j + (j >> 5); };
+  const uint32_t* gkey = reinterpret_cast<const uint32_t*>(s.score) + h.head_tok;
+  Cut c1, c2;
+  uint32_t pre[4] = {0, 0, 0, 0};
+  {
+    uint32_t u[kWidePer];
+#pragma unroll
+    for (int q = 0; q < kWidePer; ++q) { const int j = lo + tid + q * kWideThreads; u[q] = j < h.P ? gkey[j] : 0u; }
+    // counts of all earlier segments and the thresholds, while the keys are in flight
+    for (int sg = tid; sg < seg; sg += kWideThreads) {
+      const u32x4 cp = ld16(a.seg_cnt + (static_cast<int64_t>(h.bg) * a.NSEG + sg) * 4);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) pre[q] += cp[q];
+    }
+    wide_cuts(a, h, c1, c2);
+#pragma unroll
+    for (int q = 0; q < kWidePer; ++q) s_key[pad(tid + q * kWideThreads)] = u[q];
+  }
+  wide_block_sum4(pre, red);            // its barriers also publish s_key
+  uint32_t key[kWidePer];
+  const int j0 = lo + tid * kWidePer;
+#pragma unroll
+  for (int u = 0; u < kWidePer; ++u) key[u] = s_key[pad(tid * kWidePer + u)];
+  uint32_t cnt1 = 0, cnt2 = 0;          // (greater | equal << 16) of this thread's positions, per cut
+#pragma unroll
+  for (int u = 0; u < kWidePer; ++u)
+    if (j0 + u < h.P) {
+      cnt1 += (key[u] > c1.thr ? 1u : 0u) + (key[u] == c1.thr ? 0x10000u : 0u);
+      cnt2 += (key[u] > c2.thr ? 1u : 0u) + (key[u] == c2.thr ? 0x10000u : 0u);
+    }
+  uint32_t inc1 = cnt1, inc2 = cnt2;
+#pragma unroll
+  for (int sft = 1; sft < 64; sft <<= 1) {
+    const uint32_t o1 = __shfl_up(inc1, sft), o2 = __shfl_up(inc2, sft);
+    if (lane >= sft) { inc1 += o1; inc2 += o2; }
+  }
+  if (lane == 63) { wave_tot[0][wv] = inc1; wave_tot[1][wv] = inc2; }
+  __syncthreads();
+  uint32_t bef1 = inc1 - cnt1, bef2 = inc2 - cnt2;
+  for (int ww = 0; ww < wv; ++ww) { bef1 += wave_tot[0][ww]; bef2 += wave_tot[1][ww]; }
+  uint32_t gt1 = pre[0] + (bef1 & 0xFFFFu), eq1 = pre[1] + (bef1 >> 16);
+  uint32_t gt2 = pre[2] + (bef2 & 0xFFFFu), eq2 = pre[3] + (bef2 >> 16);
+  uint32_t word = 0;
+#pragma unroll
+  for (int u = 0; u < kWidePer; ++u) {
+    const int j = j0 + u;
+    const bool in = j < h.P;
+    const bool keep = in && c1.inside(key[u], eq1);
+    const bool calib = in && !keep && c2.inside(key[u], eq2);
+    if (keep) idx[c1.rank(j, gt1, eq1)] = j;
+    if (calib && cal) cal[c2.rank(j, gt2, eq2) - c1.rank(j, gt1, eq1)] = j;
+    if (in) {
+      gt1 += key[u] > c1.thr; eq1 += key[u] == c1.thr;
+      gt2 += key[u] > c2.thr; eq2 += key[u] == c2.thr;
+    }
+    word |= (calib ? 0u : 1u) << u;       // bit = skip in the calibration pass
+  }
+  if (j0 < h.P) s.bitmap[static_cast<int64_t>(h.bg) * s.W32 + (j0 >> 5)] = word;
 }
 
 // K_c[g][r] = K[g][idx[g][r]], V likewise (long-prefix path and caller-supplied lists); 16 bytes

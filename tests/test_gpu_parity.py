@@ -57,6 +57,8 @@ def test_config2_bf16_llama8b_8k():
     small("fp32", 6, 2, 64, [300, 1000, 50, 257], 16, 64, 5, name="varlen_with_short_seq"),
     small("bf16", 32, 8, 128, [513, 2049, 100, 640], 32, 512, 7, name="varlen_bf16_budget_edge"),
     small("bf16", 4, 1, 128, [65], 1, 2, 1, name="window1_budget2"),
+    small("bf16", 8, 2, 128, [20000, 300, 8300], 32, 1024, 17, T=2, name="multi_workgroup_select_bf16"),
+    small("fp32", 4, 2, 64, [16500], 16, 200, 21, T=2, name="multi_workgroup_select_fp32"),
 ], ids=lambda w: w.name)
 def test_shapes_and_ragged_tails(wl):
     run_case(wl)
@@ -86,14 +88,16 @@ def test_many_sequences_single_workgroup_decode(dtype, D, budget):
     print(wl.name, {k: v for k, v in rep.items() if k != "flags"}, flush=True)
 
 
-def test_exact_ties_lower_index_wins():
+@pytest.mark.parametrize("n,k,period,k_sel", [(16 * 40 + 16, 1, 40, 50), (20016, 17, 3000, 777), (20016, 1, 3000, 2500)])
+def test_exact_ties_lower_index_wins(n, k, period, k_sel):
     # periodic keys: position j and j + period have identical keys, hence bit-identical votes
-    # on both sides; with k = 1 the scores tie exactly and the lower position must be kept
-    wl = small("bf16", 8, 2, 64, [16 * 40 + 16], 16, 16 + 50, 1, T=0, name="ties")
+    # on both sides; the pooled scores tie exactly (away from the two ends of the prefix when
+    # k > 1) and the lower position must be kept.  The long prompts take the multi-workgroup
+    # selection, where a tie class spans several workgroups.
+    wl = small("bf16", 8, 2, 64, [n], 16, 16 + k_sel, k, T=0, name="ties")
     x = synth.make_inputs(wl, 99)
     K = synth.seq_view(x["k"], wl, 0)
     P = wl.seq_lens[0] - wl.window
-    period = 40
     for j in range(period, P):
         K[:, j] = K[:, j % period]
     x = to_dev(x)
@@ -101,12 +105,17 @@ def test_exact_ties_lower_index_wins():
     orc = H.oracle_compress(wl, x, 0)
     got = bufs.indices[0].cpu().numpy()
     assert np.array_equal(got, orc["idx"])                      # no band: exact
-    sel = got[:, :50]
+    sel = got[:, :k_sel]
     # the retained prefix positions contain whole tie classes from the lowest copy upwards
+    half = k // 2
+    n_checked = 0
     for g in range(2):
         s = set(sel[g].tolist())
         for j in s:
-            assert j < period or (j - period) in s
+            if j - period >= half and j < P - half:
+                assert (j - period) in s
+                n_checked += 1
+    assert n_checked > 0
 
 
 def test_full_budget_keeps_everything_and_decode_is_exact_attention():
@@ -351,7 +360,7 @@ def test_decode_under_hip_graph_replay():
 
 
 @pytest.mark.parametrize("dtype,D,k,m", [("bf16", 128, 5, 1), ("bf16", 64, 7, 50), ("fp32", 64, 3, 200),
-                                         ("bf16", 128, 17, 33), ("fp32", 128, 1, 5000)])
+                                         ("bf16", 128, 17, 33), ("fp32", 128, 1, 5000), ("fp32", 64, 17, 300)])
 def test_calibration_size(dtype, D, k, m):
     # Sec. 5.3: only the m evicted tokens of highest score are calibrated / offloaded; m larger
     # than the evicted set means all of it; k = 17 goes through the long-prefix selection kernel
@@ -377,3 +386,29 @@ def test_calibration_size(dtype, D, k, m):
     rep.pop("flags", None)
     print(wl.name, rep, flush=True)
     assert rep["recal_heads"] > 0
+
+
+@pytest.mark.parametrize("dtype,m", [("fp32", 1000), ("bf16", 9000)])
+def test_calibration_size_with_multi_workgroup_selection(dtype, m):
+    # second rank cut on the path where several workgroups share a head (prefix > 8192, k = 17)
+    wl = small(dtype, 4, 2, 64, [17000, 500], 16, 300, 17, T=2, name=f"calib_wide_{dtype}_{m}")
+    x = to_dev(synth.make_inputs(wl, 43))
+    bufs = H.gpu_compress(wl, x, calib_size=m)
+    rep = {}
+    for b in range(wl.batch):
+        H.check_compress(wl, x, bufs, b, report=rep)
+    cal = bufs.cal_indices.cpu().numpy()
+    assert np.all((cal[0] >= 0).sum(axis=1) == m) and np.all((cal[1] >= 0).sum(axis=1) == min(m, 200))
+    for t in range(wl.decode_steps):
+        q_t = x["q_dec"][t]
+        bufs.decode(q_t)
+        torch.cuda.synchronize()
+        before = H.snapshot_state(bufs)
+        bufs.flags.fill_(cd.FLAG_RECOMPUTE)
+        before["flags"][:] = cd.FLAG_RECOMPUTE
+        bufs.recalibrate(q_t, x["k"], x["v"], x["seq_offsets"])
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
+    rep.pop("flags", None)
+    print(wl.name, rep, flush=True)
