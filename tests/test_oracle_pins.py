@@ -253,8 +253,8 @@ def test_full_budget_means_full_attention():
 
 
 def test_identical_query_calibration_is_exact():
-    # "if the historical query is completely the same as the current query, the L1 loss
-    # should be 0" (Sec. 3.1.3): q_cal == q_t  =>  calibrated output == full attention
+    # the zero-loss case of Sec. 3.1.3 (calibration query identical to the current query):
+    # q_cal == q_t  =>  calibrated output == full attention
     q_win, K, V = rand_case(n=64, w=8, D=16)
     q_t = RNG.standard_normal((4, 16)) * 1.7
     r = ref.compress(q_win, K, V, 8, 20, 5, q_cal=q_t)
