@@ -17,6 +17,10 @@ What the paper fixes and what it leaves open
   1, zero padding, divisor k), top-(B - w) prefix positions, ties to the lower index, window
   always kept.  PARITY UNPINNED for these internal choices: no value in the paper checks them;
   closed forms and brute force pin the arithmetic of the chosen reading.
+* H2O (Sec. 4.1.3: accumulated attention, budget split evenly into important and local tokens)
+  is read as: causal softmax of every prompt query, column sums over all queries and over the
+  query heads of a KV group, no pooling, the most recent half of the budget always kept.  PARITY
+  UNPINNED for the group sum and the prefill-only accumulation, like the SnapKV-style internals.
 * The gate rho is compared with the thresholds in float32 (the precision the kernels decide
   in); everything else is float64.
 """
@@ -240,6 +244,62 @@ def compress_given(q_cal, K, V, B, retained, scale=None):
     V_c = np.stack([V[g][idx[g]] for g in range(Hkv)])
     c_q, c_out, c_lse = calibration_state(q_cal, K, V, evicted, G, scale)
     return dict(idx=idx, K_c=K_c, V_c=V_c, c_q=c_q, c_out=c_out, c_lse=c_lse, evicted=evicted)
+
+
+def h2o_votes(q_group, K_g, scale):
+    """Accumulated attention score of H2O (Sec. 4.1.3) for one KV head.
+
+    q_group [G][n][D]: every prompt query of the G query heads that share this KV head; the query
+    at position i attends positions 0..i (causal).  Returns vote [n]: for each position the
+    attention probability it received, summed over all queries and over the G heads."""
+    q = np.asarray(q_group, F)
+    K = np.asarray(K_g, F)
+    n = K.shape[0]
+    vote = np.zeros(n, F)
+    for h in range(q.shape[0]):
+        for i in range(n):
+            z = logits(q[h, i], K[:i + 1], scale)
+            e = np.exp(z - z.max())
+            vote[:i + 1] += e / e.sum()
+    return vote
+
+
+def h2o_retained(vote, n, B, n_local):
+    """H2O's retained set: the n_local most recent positions plus the B - n_local positions of
+    highest accumulated score among the others (ties to the lower position).  Sec. 4.1.3 splits
+    the budget evenly (n_local = B / 2).  Ascending positions; also the boundary margin."""
+    if n <= B:
+        return np.arange(n), np.inf
+    sel, margin = select_top(np.asarray(vote, F)[:n - n_local], B - n_local)
+    return np.concatenate([sel, np.arange(n - n_local, n)]), margin
+
+
+def compress_h2o(q_full, K, V, B, n_local, scale=None, retained_override=None):
+    """Alg. 1 steps 3-8 with H2O as the eviction strategy f, one sequence.
+
+    q_full [Hq][n][D] all prompt queries; K, V [Hkv][n][D].  The calibration query is Q_{-1}.
+    Returns the dict of compress_given plus vote (list per KV head) and margin [Hkv]."""
+    q_full = np.asarray(q_full, F)
+    K = np.asarray(K, F)
+    Hq, n, D = q_full.shape
+    Hkv = K.shape[0]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    votes, kept, margins = [], [], []
+    for g in range(Hkv):
+        if n <= B:
+            votes.append(None); kept.append(np.arange(n)); margins.append(np.inf)
+            continue
+        vote = h2o_votes(q_full[g * G:(g + 1) * G], K[g], scale)
+        keep, margin = h2o_retained(vote, n, B, n_local)
+        if retained_override is not None:
+            keep, margin = np.asarray(retained_override[g]), np.inf
+        votes.append(vote); kept.append(keep); margins.append(margin)
+    r = compress_given(q_full[:, n - 1], K, V, B, kept, scale)
+    r["vote"], r["margin"] = votes, np.asarray(margins)
+    r["score"] = votes
+    return r
 
 
 # --------------------------------------------------------------------------------------------

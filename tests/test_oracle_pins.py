@@ -504,3 +504,66 @@ def test_compress_given_with_the_scored_list_equals_compress():
     r2 = ref.compress_given(q_win[:, -1], K, V, 24, [r["idx"][0], r["idx"][1]])
     for key in ("K_c", "V_c", "c_q", "c_out", "c_lse"):
         np.testing.assert_allclose(r2[key], r[key], atol=1e-14)
+
+
+# ---- H2O: accumulated attention over all prompt queries -------------------------------------------
+def test_h2o_votes_match_dense_causal_softmax_and_conserve_mass():
+    rng = np.random.default_rng(5)
+    G, n, D = 3, 37, 8
+    q = rng.standard_normal((G, n, D)); K = rng.standard_normal((n, D))
+    vote = ref.h2o_votes(q, K, 0.3)
+    S = torch.from_numpy(q) @ torch.from_numpy(K).T * 0.3                     # [G][n][n]
+    mask = torch.tril(torch.ones(n, n, dtype=torch.bool))
+    Pm = torch.softmax(S.masked_fill(~mask, float("-inf")), dim=-1)
+    np.testing.assert_allclose(vote, Pm.sum(dim=(0, 1)).numpy(), atol=1e-12)
+    np.testing.assert_allclose(vote.sum(), G * n, atol=1e-10)                 # every row distributes mass 1
+    # a transposed or anti-causal mask would give the first position the least mass, not the most
+    assert vote[0] > vote[-1]
+
+
+def test_h2o_votes_uniform_keys_closed_form():
+    # identical keys: row i spreads 1/(i+1) over columns 0..i  =>  vote[j] = G * (H_n - H_j)
+    G, n, D = 2, 25, 4
+    q = RNG.standard_normal((G, n, D)); K = np.tile(RNG.standard_normal(D), (n, 1))
+    vote = ref.h2o_votes(q, K, 0.5)
+    Hn = np.cumsum(1.0 / np.arange(1, n + 1))
+    want = G * (Hn[-1] - np.concatenate([[0.0], Hn[:-1]]))
+    np.testing.assert_allclose(vote, want, atol=1e-12)
+
+
+def test_h2o_votes_reduce_to_the_window_votes_on_the_last_rows():
+    # rows below P only see keys below P, so: votes(all rows) - votes(rows < P) on the prefix
+    # columns = the observation-window votes of the last w rows
+    G, n, D, w = 2, 40, 8, 6
+    P = n - w
+    q = RNG.standard_normal((G, n, D)); K = RNG.standard_normal((n, D))
+    full = ref.h2o_votes(q, K, 0.35)
+    head = ref.h2o_votes(q[:, :P], K[:P], 0.35)
+    np.testing.assert_allclose(full[:P] - head, ref.window_votes(q[:, P:], K, w, 0.35), atol=1e-12)
+
+
+def test_h2o_retained_set_and_compress():
+    vote = np.array([5.0, 0.1, 3.0, 3.0, 0.2, 9.0, 0.3, 0.4, 7.0, 0.5])
+    keep, margin = ref.h2o_retained(vote, 10, 6, 3)
+    # local = positions 7, 8, 9; heavy hitters among 0..6: 5 (9.0), 0 (5.0), then the tie 2/3 -> 2
+    np.testing.assert_array_equal(keep, [0, 2, 5, 7, 8, 9])
+    assert margin == 0.0
+    np.testing.assert_array_equal(ref.h2o_retained(vote, 10, 12, 6)[0], np.arange(10))
+    # brute force on random scores
+    for _ in range(20):
+        n, B, loc = 30, 12, int(RNG.integers(1, 11))
+        v = np.round(RNG.random(n), 1)                                         # many ties
+        keep, _ = ref.h2o_retained(v, n, B, loc)
+        cand = sorted(range(n - loc), key=lambda j: (-v[j], j))[:B - loc]
+        np.testing.assert_array_equal(keep, sorted(cand) + list(range(n - loc, n)))
+    # end to end: retained + calibration state merge to the full attention of Q_{-1} (Eq. 1)
+    Hq, Hkv, n, D = 4, 2, 45, 8
+    qf = RNG.standard_normal((Hq, n, D)); K = RNG.standard_normal((Hkv, n, D)); V = RNG.standard_normal((Hkv, n, D))
+    r = ref.compress_h2o(qf, K, V, 14, 7)
+    assert r["idx"].shape == (2, 14) and np.all(r["idx"][:, 7:] == np.arange(38, 45))
+    for h in range(Hq):
+        g = h // 2
+        o_a, l_a = ref.attention(qf[h, -1], r["K_c"][g], r["V_c"][g], 8 ** -0.5)
+        full, _ = ref.merge(o_a, l_a, r["c_out"][h], r["c_lse"][h])
+        np.testing.assert_allclose(full, sdpa64(qf[h, -1], K[g], V[g], 8 ** -0.5), atol=1e-13)
+    np.testing.assert_array_equal(r["c_q"], qf[:, -1])
