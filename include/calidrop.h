@@ -260,6 +260,46 @@ int calidrop_compress_given(const calidrop_params* p, const void* q_cal, const v
                             void* stream);
 
 /*
+ * calidrop_compress_h2o - Alg. 1 steps 3-8 with H2O as the eviction strategy f (Sec. 4.1.3:
+ * importance = accumulated attention score; the budget is split into important and local tokens).
+ *
+ * For every sequence b with n_b > B and every KV head g:
+ *   1. every prompt query i of the G heads of the group attends causally (columns 0..i), logits
+ *      scale * q.K, row softmax;  vote[j] = sum over those G * n_b rows of the probability on
+ *      column j (a dense n_b x n_b pass per head, on the matrix cores).
+ *   2. retained = the n_local most recent positions plus the B - n_local positions of largest
+ *      vote among the others (ties to the lower position), ascending.
+ *   3. gather, KV_evict, calibration state exactly as in calidrop_compress, with Q_{-1} (the
+ *      last row of q_full) as the calibration query; calib_size > 0 ranks the evicted tokens by
+ *      the same votes.
+ * n_b <= B keeps everything.  n_local = 0 selects B / 2 (the even split the paper uses);
+ * otherwise 1 <= n_local < B.  `window` and `pool_kernel` of the params play no role.
+ *
+ * Arguments: q_full dtype, packed like k but with Hq heads: sequence b starts at token
+ * seq_offsets[b], inside [Hq][n_b][D] (every prompt query, as used by attention); all other
+ * arguments as in calidrop_compress; batch * n_q_heads <= 65535; workspace >=
+ * calidrop_compress_h2o_workspace_bytes(p, n_local, total_tokens, max_seq_len) bytes, 256-byte
+ * aligned.  With calidrop_set_inspection(1) nothing extra is stored here (the votes are always
+ * in the workspace).
+ */
+size_t calidrop_compress_h2o_workspace_bytes(const calidrop_params* p, int32_t n_local,
+                                             int64_t total_tokens, int32_t max_seq_len);
+/* Regions of that workspace for inspection after the stream has finished:
+ *   ROW_LSE float [batch][Hq][stride]: log2 of the softmax denominator of every prompt query
+ *           (logits in log2 units), stride = bytes / (batch * Hq * 4) >= max_seq_len, +inf padded;
+ *   SCORE   float, packed like K with D = 1: vote of position j of KV head g of sequence b at
+ *           [seq_offsets[b]*Hkv + g*n_b + j], j < n_b.                                          */
+int calidrop_compress_h2o_workspace_region(const calidrop_params* p, int32_t n_local,
+                                           int64_t total_tokens, int32_t max_seq_len,
+                                           int32_t region, size_t* offset, size_t* bytes);
+int calidrop_compress_h2o(const calidrop_params* p, int32_t n_local, const void* q_full,
+                          const void* k, const void* v, const int32_t* seq_offsets,
+                          int64_t total_tokens, int32_t max_seq_len, void* k_c, void* v_c,
+                          const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
+                          int32_t* cal_indices, float* c_q, float* c_out, float* c_lse,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Offloading KV_evict (Alg. 1 step 4 moves the evicted cache out of GPU memory instead of deleting
  * it; Alg. 2 step 4 reloads it for the recomputation branch; Sec. 3.2).
  *

@@ -109,6 +109,14 @@ def lib() -> ctypes.CDLL:
         L.calidrop_recalibrate_packed_workspace_bytes.argtypes = [pp, i32]
         L.calidrop_recalibrate_packed.restype = ctypes.c_int
         L.calidrop_recalibrate_packed.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.calidrop_compress_h2o_workspace_bytes.restype = sz
+        L.calidrop_compress_h2o_workspace_bytes.argtypes = [pp, i32, i64, i32]
+        L.calidrop_compress_h2o_workspace_region.restype = ctypes.c_int
+        L.calidrop_compress_h2o_workspace_region.argtypes = [pp, i32, i64, i32, i32, ctypes.POINTER(sz),
+                                                             ctypes.POINTER(sz)]
+        L.calidrop_compress_h2o.restype = ctypes.c_int
+        L.calidrop_compress_h2o.argtypes = [pp, i32, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                            vp, sz, vp]
         _lib = L
     return _lib
 
@@ -219,6 +227,31 @@ def calidrop_compress_given(p: Params, q_cal, k, v, seq_offsets, total_tokens: i
         ctypes.byref(p), _ptr(q_cal), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
         _ptr(indices), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens), _ptr(c_q), _ptr(c_out),
         _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def calidrop_compress_h2o_workspace_bytes(p: Params, n_local: int, total_tokens: int, max_seq_len: int) -> int:
+    n = lib().calidrop_compress_h2o_workspace_bytes(ctypes.byref(p), n_local, total_tokens, max_seq_len)
+    if n == 0:
+        raise CalidropError(EINVAL, calidrop_last_error())
+    return n
+
+
+def calidrop_compress_h2o_workspace_region(p: Params, n_local: int, total_tokens: int, max_seq_len: int,
+                                           region: int):
+    off, nbytes = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().calidrop_compress_h2o_workspace_region(ctypes.byref(p), n_local, total_tokens, max_seq_len,
+                                                        region, ctypes.byref(off), ctypes.byref(nbytes)))
+    return off.value, nbytes.value
+
+
+def calidrop_compress_h2o(p: Params, n_local: int, q_full, k, v, seq_offsets, total_tokens: int, max_seq_len: int,
+                          k_c, v_c, cache_offsets, cache_lens, indices, cal_indices, c_q, c_out, c_lse, workspace,
+                          stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().calidrop_compress_h2o(
+        ctypes.byref(p), n_local, _ptr(q_full), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
+        _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens), _ptr(indices), _ptr(cal_indices), _ptr(c_q),
+        _ptr(c_out), _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 def calidrop_packed_rows(p: Params, seq_len: int) -> int:
@@ -368,6 +401,21 @@ class CompressBuffers:
         calidrop_compress_given(self.p, q_cal, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
                                 self.indices, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
                                 self.c_q, self.c_out, self.c_lse, self.ws_given, stream)
+
+    def compress_h2o(self, q_full, k, v, seq_offsets, n_local=0, stream=None):
+        """Alg. 1 with H2O as the eviction strategy; the workspace (self.ws_h2o) keeps the votes."""
+        if getattr(self, "ws_h2o", None) is None:
+            self.ws_h2o = torch.empty(
+                calidrop_compress_h2o_workspace_bytes(self.p, n_local, self.total_tokens, self.max_seq_len),
+                dtype=torch.uint8, device=self.out.device)
+        calidrop_compress_h2o(self.p, n_local, q_full, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
+                              self.k_c, self.v_c, self.cache_offsets, self.cache_lens, self.indices,
+                              self.cal_indices, self.c_q, self.c_out, self.c_lse, self.ws_h2o, stream)
+
+    def h2o_region(self, region: int, n_local=0) -> torch.Tensor:
+        off, nbytes = calidrop_compress_h2o_workspace_region(self.p, n_local, self.total_tokens,
+                                                             self.max_seq_len, region)
+        return self.ws_h2o[off:off + nbytes].view(torch.float32)
 
     def streaming_indices(self, n_sink, seq_offsets, stream=None):
         calidrop_streaming_indices(self.p, n_sink, seq_offsets, self.total_tokens, self.max_seq_len,

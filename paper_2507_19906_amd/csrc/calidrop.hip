@@ -13,6 +13,7 @@
 #include "cd_attend.h"
 #include "cd_common.h"
 #include "cd_given.h"
+#include "cd_h2o.h"
 #include "cd_score.h"
 #include "cd_select.h"
 
@@ -174,6 +175,53 @@ int launch_status(const char* what) {
   return CALIDROP_OK;
 }
 
+// Pooling + selection + gather for scores already in sa.vote.  Heads whose pooled scores fit in
+// LDS are pooled inside the single-workgroup selection kernel; longer ones go through the
+// pooled-score buffer and the multi-workgroup chain.  `window` = trailing positions always kept.
+int run_selection(const calidrop_params* p, int window, int pool_k, int max_seq_len, cd::SelectArgs& se,
+                  cd::ScoreArgs& sa, uint32_t* sel_hist, uint32_t* sel_cnt, int NSEG, hipStream_t st) {
+  int rc;
+  const int bg = p->batch * p->n_kv_heads;
+  const int max_prefix = max_seq_len - window;
+  se.write_scores = g_inspection.load(std::memory_order_relaxed);
+  if (max_prefix <= cd::kSelMaxLdsKeys && p->budget <= cd::kSelMaxLdsKeys && pool_k <= cd::kSelMaxPool) {
+    // dynamic LDS: staged votes (padded), later reused for the retained indices
+    size_t lds = static_cast<size_t>(p->budget) * sizeof(int32_t);
+    if (max_seq_len > p->budget) {
+      const size_t votes = (static_cast<size_t>(max_prefix) + max_prefix / 32 + 1) * sizeof(float);
+      if (votes > lds) lds = votes;
+    }
+    const void* fn = reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads>);
+    if (lds > 48 * 1024) {
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(cd::select_gather_lds_kernel<cd::kSelThreads>, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
+  } else {
+    cd::WideArgs wa{};
+    wa.s = se; wa.NSEG = NSEG;
+    wa.hist = sel_hist;
+    wa.seg_cnt = sel_cnt;
+    sa.zero_words = wa.hist; sa.zero_per_head = 2 * 4 * 256;
+    hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
+    if ((rc = launch_status("pool_scores"))) return rc;
+    const dim3 grid_w(NSEG, bg);
+    if (max_seq_len > p->budget) {
+      for (wa.pass = 0; wa.pass < 4; ++wa.pass) {
+        hipLaunchKernelGGL(cd::wide_hist_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
+        if ((rc = launch_status("wide_hist"))) return rc;
+      }
+      hipLaunchKernelGGL(cd::wide_count_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
+      if ((rc = launch_status("wide_count"))) return rc;
+    }
+    hipLaunchKernelGGL(cd::wide_emit_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
+    if ((rc = launch_status("wide_emit"))) return rc;
+    const int vecs = p->budget * (se.row_bytes / 16);
+    hipLaunchKernelGGL(cd::gather_kv_kernel, dim3(ceil_div(vecs, 256), bg), dim3(256), 0, st, se);
+  }
+  return launch_status("select_gather");
+}
+
 template <typename T, int D>
 int compress_impl(const calidrop_params* p, const void* q_win, const void* k, const void* v,
                   const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, const void* q_cal,
@@ -220,44 +268,9 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   se.calib = p->calib_size; se.cal_indices = cal_indices;
   se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
   se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
-  const int max_prefix = max_seq_len - p->window;
-  se.write_scores = g_inspection.load(std::memory_order_relaxed);
-  if (max_prefix <= cd::kSelMaxLdsKeys && p->budget <= cd::kSelMaxLdsKeys && p->pool_kernel <= cd::kSelMaxPool) {
-    // dynamic LDS: staged votes (padded), later reused for the retained indices
-    size_t lds = static_cast<size_t>(p->budget) * sizeof(int32_t);
-    if (max_seq_len > p->budget) {
-      const size_t votes = (static_cast<size_t>(max_prefix) + max_prefix / 32 + 1) * sizeof(float);
-      if (votes > lds) lds = votes;
-    }
-    const void* fn = reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads>);
-    if (lds > 48 * 1024) {
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-      if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
-    }
-    hipLaunchKernelGGL(cd::select_gather_lds_kernel<cd::kSelThreads>, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
-  } else {
-    cd::WideArgs wa{};
-    wa.s = se; wa.NSEG = L.NSEG;
-    wa.hist = reinterpret_cast<uint32_t*>(ws + L.sel_hist);
-    wa.seg_cnt = reinterpret_cast<uint32_t*>(ws + L.sel_cnt);
-    sa.zero_words = wa.hist; sa.zero_per_head = 2 * 4 * 256;
-    hipLaunchKernelGGL(cd::pool_scores_kernel, dim3(ceil_div(max_seq_len, 256), bg), dim3(256), 0, st, sa);
-    if ((rc = launch_status("pool_scores"))) return rc;
-    const dim3 grid_w(L.NSEG, bg);
-    if (max_seq_len > p->budget) {
-      for (wa.pass = 0; wa.pass < 4; ++wa.pass) {
-        hipLaunchKernelGGL(cd::wide_hist_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
-        if ((rc = launch_status("wide_hist"))) return rc;
-      }
-      hipLaunchKernelGGL(cd::wide_count_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
-      if ((rc = launch_status("wide_count"))) return rc;
-    }
-    hipLaunchKernelGGL(cd::wide_emit_kernel, grid_w, dim3(cd::kWideThreads), 0, st, wa);
-    if ((rc = launch_status("wide_emit"))) return rc;
-    const int vecs = p->budget * (se.row_bytes / 16);
-    hipLaunchKernelGGL(cd::gather_kv_kernel, dim3(ceil_div(vecs, 256), bg), dim3(256), 0, st, se);
-  }
-  if ((rc = launch_status("select_gather"))) return rc;
+  if ((rc = run_selection(p, p->window, p->pool_kernel, max_seq_len, se, sa, reinterpret_cast<uint32_t*>(ws + L.sel_hist),
+                          reinterpret_cast<uint32_t*>(ws + L.sel_cnt), L.NSEG, st)))
+    return rc;
 
   cd::AttendArgs aa{};
   aa.q = q_cal ? q_cal : q_win; aa.q_is_window = q_cal ? 0 : 1;
@@ -504,6 +517,103 @@ int recal_packed_impl(const calidrop_params* p, const void* q_t, const void* k_e
   fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse; fa.out = out; fa.a_lse = const_cast<float*>(a_lse); fa.flags = flags;
   hipLaunchKernelGGL((cd::attend_finalize_kernel<T, D>), dim3(p->n_q_heads, p->batch), dim3(D), 0, st, fa);
   return launch_status("attend_finalize(recalibrate, packed)");
+}
+
+constexpr int kH2oRowTiles = CD_H2O_ROW_TILES;        // 16-row tiles per wave in the H2O scoring passes
+constexpr int kH2oBlock = 4 * 16 * kH2oRowTiles;      // stationary rows (or keys) per workgroup
+
+struct H2oLayout {
+  size_t row_lse, vote, score, bitmap, q_last, part_o, part_ml, sel_hist, sel_cnt, total;
+  int lse_stride, W32, NSEG;
+  SplitPlan sp;
+};
+
+H2oLayout h2o_layout(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len, int n_local) {
+  H2oLayout L{};
+  L.lse_stride = ceil_div(max_seq_len, 256) * 256;
+  L.W32 = ceil_div(max_seq_len, 64) * 2;
+  L.sp = plan_splits(p->batch * p->n_kv_heads, max_seq_len);
+  L.NSEG = ceil_div(std::max(max_seq_len - n_local, 1), cd::kWideSeg);
+  const size_t toks = static_cast<size_t>(total_tokens) * p->n_kv_heads;
+  const size_t slots = static_cast<size_t>(p->batch) * p->n_q_heads * L.sp.NS;
+  size_t off = 0;
+  L.row_lse = off; off += round256(static_cast<size_t>(p->batch) * p->n_q_heads * L.lse_stride * sizeof(float));
+  L.vote = off;    off += round256(toks * sizeof(float));
+  L.score = off;   off += round256(toks * sizeof(float));
+  L.bitmap = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.W32 * sizeof(uint32_t));
+  L.q_last = off;  off += round256(static_cast<size_t>(p->batch) * p->n_q_heads * p->head_dim * sizeof(float));
+  L.part_o = off;  off += round256(slots * p->head_dim * sizeof(float));
+  L.part_ml = off; off += round256(slots * sizeof(float2));
+  L.sel_hist = off; off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * 2 * 4 * 256 * sizeof(uint32_t));
+  L.sel_cnt = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.NSEG * 4 * sizeof(uint32_t));
+  L.total = off;
+  return L;
+}
+
+// Alg. 1 steps 3-8 with H2O as f: accumulated attention of every prompt query (two dense passes),
+// top-(B - n_local) among the positions outside the local window, gather, calibration state.
+template <typename T, int D>
+int h2o_impl(const calidrop_params* p, int n_local, const void* q_full, const void* k, const void* v,
+             const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, void* k_c, void* v_c,
+             const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices, int32_t* cal_indices, float* c_q,
+             float* c_out, float* c_lse, char* ws, const H2oLayout& L, hipStream_t st) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  const int bg = p->batch * p->n_kv_heads;
+  const float sl2 = logit_scale(p) * cd::kLog2e;
+  int rc;
+  cd::H2oArgs ha{};
+  ha.q_full = q_full; ha.k = k; ha.seq_off = seq_offsets; ha.total_tokens = total_tokens; ha.batch = p->batch;
+  ha.Hq = p->n_q_heads; ha.Hkv = p->n_kv_heads; ha.G = G; ha.B = p->budget; ha.max_seq_len = max_seq_len;
+  ha.lse_stride = L.lse_stride; ha.sl2 = sl2;
+  ha.row_lse = reinterpret_cast<float*>(ws + L.row_lse);
+  ha.vote = reinterpret_cast<float*>(ws + L.vote);
+  ha.q_last = ws + L.q_last;
+  const int nblk = ceil_div(max_seq_len, kH2oBlock);
+  // always launched: it also extracts Q_{-1}, which prompts within the budget need as C_q
+  hipLaunchKernelGGL((cd::h2o_rowlse_kernel<T, D, kH2oRowTiles>), dim3(nblk, p->batch * p->n_q_heads), dim3(256), 0, st, ha);
+  if ((rc = launch_status("h2o_rowlse"))) return rc;
+  if (max_seq_len > p->budget) {
+    hipLaunchKernelGGL((cd::h2o_votes_kernel<T, D, kH2oRowTiles>), dim3(nblk, bg), dim3(256), 0, st, ha);
+    if ((rc = launch_status("h2o_votes"))) return rc;
+  }
+  // selection: the votes are the scores (no pooling); the local window plays the part of the
+  // observation window (always kept, not a candidate)
+  cd::ScoreArgs sa{};
+  sa.seq_off = seq_offsets; sa.total_tokens = total_tokens; sa.batch = p->batch; sa.Hq = p->n_q_heads;
+  sa.Hkv = p->n_kv_heads; sa.G = G; sa.w = n_local; sa.B = p->budget; sa.NRB = 1; sa.max_seq_len = max_seq_len;
+  sa.pool_k = 1; sa.vote = ha.vote; sa.score = reinterpret_cast<float*>(ws + L.score);
+  cd::SelectArgs se{};
+  se.seq_off = seq_offsets; se.cache_off = cache_offsets; se.total_tokens = total_tokens; se.batch = p->batch;
+  se.Hkv = p->n_kv_heads; se.w = n_local; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
+  se.NRB = 1; se.pool_k = 1; se.row_bytes = D * static_cast<int>(sizeof(T));
+  se.vote = sa.vote; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
+  se.calib = p->calib_size; se.cal_indices = cal_indices;
+  se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
+  se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
+  if ((rc = run_selection(p, n_local, 1, max_seq_len, se, sa, reinterpret_cast<uint32_t*>(ws + L.sel_hist),
+                          reinterpret_cast<uint32_t*>(ws + L.sel_cnt), L.NSEG, st)))
+    return rc;
+
+  cd::AttendArgs aa{};
+  aa.q = ha.q_last; aa.q_is_window = 0; aa.k = k; aa.v = v; aa.row_off = seq_offsets; aa.row_len = nullptr;
+  aa.bitmap = se.bitmap; aa.total_tokens = total_tokens; aa.batch = p->batch; aa.Hq = p->n_q_heads;
+  aa.Hkv = p->n_kv_heads; aa.G = G; aa.w = n_local; aa.B = p->budget; aa.max_len = max_seq_len; aa.W32 = L.W32;
+  aa.rows_per_split = L.sp.rows_per_split; aa.NS = L.sp.NS; aa.sl2 = sl2;
+  aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
+  aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+  if (max_seq_len > p->budget) {
+    hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0,
+                       st, aa);
+    if ((rc = launch_status("attend_partial(h2o)"))) return rc;
+  }
+  cd::FinalArgs fa{};
+  fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = seq_offsets; fa.row_len = nullptr;
+  fa.total_tokens = total_tokens; fa.batch = p->batch; fa.Hq = p->n_q_heads; fa.Hkv = p->n_kv_heads; fa.G = G;
+  fa.w = n_local; fa.B = p->budget; fa.max_len = max_seq_len; fa.rows_per_split = L.sp.rows_per_split;
+  fa.NS = L.sp.NS; fa.calib_mode = 1; fa.q_is_window = 0; fa.q = ha.q_last;
+  fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse;
+  hipLaunchKernelGGL((cd::attend_finalize_kernel<T, D>), dim3(p->n_q_heads, p->batch), dim3(D), 0, st, fa);
+  return launch_status("attend_finalize(h2o)");
 }
 
 }  // namespace
@@ -821,6 +931,94 @@ int calidrop_recalibrate_packed(const calidrop_params* p_in, const void* q_t, co
 #define CD_DISPATCH(T, D)                                                                                        \
   return recal_packed_impl<T, D>(p, q_t, k_e, v_e, evict_offsets, evict_lens, max_evict_len, flags, a_lse, out,   \
                                  c_q, c_out, c_lse, ws, L, st)
+  if (p->dtype == CALIDROP_BF16) {
+    if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
+    CD_DISPATCH(cd::bf16_t, 64);
+  }
+  if (p->head_dim == 128) CD_DISPATCH(float, 128);
+  CD_DISPATCH(float, 64);
+#undef CD_DISPATCH
+}
+
+namespace {
+int h2o_local(const calidrop_params* p, int32_t n_local) {
+  if (n_local == 0) n_local = p->budget / 2;              // the even split of Sec. 4.1.3
+  if (n_local < 1 || n_local >= p->budget) {
+    fail(CALIDROP_EINVAL, "n_local must satisfy 1 <= n_local < budget (got %d, budget %d)", n_local, p->budget);
+    return -1;
+  }
+  return n_local;
+}
+}  // namespace
+
+size_t calidrop_compress_h2o_workspace_bytes(const calidrop_params* p_in, int32_t n_local, int64_t total_tokens,
+                                             int32_t max_seq_len) {
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if (load_params(p_in, &pp) != CALIDROP_OK) return 0;
+  if (check_params(p) != CALIDROP_OK || check_sizes(p, total_tokens, max_seq_len) != CALIDROP_OK) return 0;
+  if ((n_local = h2o_local(p, n_local)) < 0) return 0;
+  return h2o_layout(p, total_tokens, max_seq_len, n_local).total;
+}
+
+int calidrop_compress_h2o_workspace_region(const calidrop_params* p_in, int32_t n_local, int64_t total_tokens,
+                                           int32_t max_seq_len, int32_t region, size_t* offset, size_t* bytes) {
+  int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
+  if ((rc = check_params(p))) return rc;
+  if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
+  if ((n_local = h2o_local(p, n_local)) < 0) return CALIDROP_EINVAL;
+  if (!offset || !bytes) return fail(CALIDROP_EINVAL, "offset/bytes is NULL");
+  const H2oLayout L = h2o_layout(p, total_tokens, max_seq_len, n_local);
+  if (region == CALIDROP_REGION_ROW_LSE) {
+    *offset = L.row_lse;
+    *bytes = static_cast<size_t>(p->batch) * p->n_q_heads * L.lse_stride * sizeof(float);
+  } else if (region == CALIDROP_REGION_SCORE) {
+    *offset = L.vote;
+    *bytes = static_cast<size_t>(total_tokens) * p->n_kv_heads * sizeof(float);
+  } else {
+    return fail(CALIDROP_EINVAL, "unknown workspace region %d", region);
+  }
+  return CALIDROP_OK;
+}
+
+int calidrop_compress_h2o(const calidrop_params* p_in, int32_t n_local, const void* q_full, const void* k,
+                          const void* v, const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
+                          void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
+                          int32_t* cal_indices, float* c_q, float* c_out, float* c_lse, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
+  if ((rc = check_params(p))) return rc;
+  if ((rc = check_sizes(p, total_tokens, max_seq_len))) return rc;
+  if ((n_local = h2o_local(p, n_local)) < 0) return CALIDROP_EINVAL;
+  if (static_cast<int64_t>(p->batch) * p->n_q_heads > 65535)
+    return fail(CALIDROP_EUNSUPPORTED, "batch * n_q_heads exceeds 65535");
+  const struct { const void* ptr; const char* name; } req[] = {
+      {q_full, "q_full"}, {k, "k"}, {v, "v"}, {seq_offsets, "seq_offsets"}, {k_c, "k_c"}, {v_c, "v_c"},
+      {cache_offsets, "cache_offsets"}, {cache_lens, "cache_lens"}, {indices, "indices"}, {c_q, "c_q"},
+      {c_out, "c_out"}, {c_lse, "c_lse"}};
+  for (const auto& r : req)
+    if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
+  for (const auto& r : req)
+    if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  if (p->calib_size > 0) {
+    if (!cal_indices) return fail(CALIDROP_EINVAL, "cal_indices is NULL although calib_size is %d", p->calib_size);
+    if (!aligned16(cal_indices)) return fail(CALIDROP_EALIGN, "cal_indices is not 16-byte aligned");
+  } else {
+    cal_indices = nullptr;
+  }
+  const H2oLayout L = h2o_layout(p, total_tokens, max_seq_len, n_local);
+  if (!workspace || workspace_bytes < L.total)
+    return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
+                L.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+#define CD_DISPATCH(T, D)                                                                                      \
+  return h2o_impl<T, D>(p, n_local, q_full, k, v, seq_offsets, total_tokens, max_seq_len, k_c, v_c,             \
+                        cache_offsets, cache_lens, indices, cal_indices, c_q, c_out, c_lse, ws, L, st)
   if (p->dtype == CALIDROP_BF16) {
     if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);
     CD_DISPATCH(cd::bf16_t, 64);

@@ -1,0 +1,267 @@
+// H2O as the eviction strategy f of Alg. 1 step 3 (Sec. 4.1.3: importance = accumulated
+// attention score): every prompt query attends causally to the prompt, and a position's score
+// is the probability mass it received, summed over all queries and over the G query heads of
+// its KV head.  Unlike the observation-window scoring this is a dense n x n contraction per head
+// (matrix-core bound), done in two passes that mirror each other:
+//   pass 1 (h2o_rowlse): query rows stay in registers, keys stream through LDS; a lane owns a
+//           query row, so the running (max, sum exp2) of its softmax stay in the lane -> row
+//           log-sum-exp for every prompt position.
+//   pass 2 (h2o_votes):  keys stay in registers, query rows stream through LDS; a lane owns a
+//           key, so the column sum of p = exp2(s - lse_row) over all rows that see the key stays
+//           in the lane -> vote[j], written once, no atomics, fixed summation order.
+// Both passes skip the tiles above the diagonal and mask only the tiles on it.
+#pragma once
+#include "cd_common.h"
+#include "cd_score.h"
+
+namespace cd {
+
+#ifndef CD_H2O_ROW_TILES
+#define CD_H2O_ROW_TILES 2     // 16-row tiles of stationary rows per wave (build-time tuning knob)
+#endif
+
+struct H2oArgs {
+  const void* q_full;        // packed like K with Hq heads: sequence b at token seq_off[b], inside [Hq][n_b][D]
+  const void* k;
+  const int32_t* seq_off;
+  int64_t total_tokens;
+  int batch, Hq, Hkv, G, B, max_seq_len;
+  int lse_stride;            // floats per (sequence, query head) in row_lse; a multiple of the row block
+  float sl2;                 // scale * log2(e)
+  float* row_lse;            // [batch*Hq][lse_stride], log2 units; rows >= n_b hold +inf
+  float* vote;               // [total_tokens*Hkv], packed like K with one float per row
+  void* q_last;              // [batch][Hq][D]: the last prompt query of every head (Q_{-1})
+};
+
+// RT = 16-row tiles of stationary rows per wave (a workgroup holds 4 * 16 * RT of them).
+template <typename T, int D, int RT>
+__global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
+  using KS = KeyStream<T, D>;
+  constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys, EPL = KS::EPL, KD = KS::KD;
+  constexpr int WR = 16 * RT, BR = 4 * WR;
+  const int hq = blockIdx.y % a.Hq, b = blockIdx.y / a.Hq, g = hq / a.G;
+  int off0;
+  const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
+  const T* qbase = static_cast<const T*>(a.q_full) + (static_cast<int64_t>(off0) * a.Hq + static_cast<int64_t>(hq) * n) * D;
+  // Q_{-1} of this head, the calibration query of Alg. 1 step 5 (also for prompts within the budget)
+  if (blockIdx.x == 0 && n > 0 && threadIdx.x < D)
+    store_elem<T>(static_cast<T*>(a.q_last), static_cast<int64_t>(b * a.Hq + hq) * D + threadIdx.x,
+                  load_elem<T>(qbase, static_cast<int64_t>(n - 1) * D + threadIdx.x));
+  if (n <= a.B) return;
+  const int nrb = (n + BR - 1) / BR;
+  const int rbp = nrb - 1 - static_cast<int>(blockIdx.x);      // late rows (most keys) are launched first
+  if (rbp < 0) return;
+  const int i0 = rbp * BR;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int i = lane & 15, c = lane >> 4;
+  const T* kbase = static_cast<const T*>(a.k) + (static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n) * D;
+  const int wrow0 = i0 + wv * WR;                // first row of this wave
+
+  __shared__ __attribute__((aligned(16))) char s_k[2][KS::kStageBytes];
+  u32x4 qf[RT][NK];
+  int lim[RT];                                   // last key the row sees (= its position), -1 for padding rows
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int row = wrow0 + rt * 16 + i;
+    const bool valid = row < n;
+    const T* qp = qbase + static_cast<int64_t>(valid ? row : 0) * D + c * EPL;
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) qf[rt][kk] = valid ? ld16(qp + kk * KD) : zero16();
+    lim[rt] = valid ? row : -1;
+  }
+  float m[RT], l[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) { m[rt] = -INFINITY; l[rt] = 0.f; }
+
+  const int key_end = min(n, i0 + BR);           // no row of the block sees a key beyond its last row
+  const int nstages = (key_end + SK - 1) / SK;
+  typename KS::Regs r0, r1;
+  KS::load(r0, kbase, 0, n);
+  if (nstages > 1) KS::load(r1, kbase, SK, n);
+  KS::store(r0, s_k[0]);
+  __syncthreads();
+
+  auto compute = [&](const char* lds, int key0) {
+    if (key0 > wrow0 + WR - 1 || wrow0 >= n) return;        // nothing of this stage is visible to the wave
+    const bool full = key0 + SK - 1 <= wrow0 && wrow0 + WR <= n;   // every key visible to every (real) row
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      u32x4 kf[NK];
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) kf[kk] = KS::frag(lds, kt, kk, i, c);
+      f32x4 acc[RT];
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc[rt], kf[kk], qf[rt][kk]);
+      }
+      // acc[rt][r] <-> key key0 + 16 kt + 4 c + r, row (rt, i)
+      if (full) {
+        float tm[RT];
+        bool grow = false;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          tm[rt] = fmaxf(fmaxf(acc[rt][0], acc[rt][1]), fmaxf(acc[rt][2], acc[rt][3])) * a.sl2;
+          grow |= tm[rt] > m[rt];
+        }
+        if (__any(grow)) {               // some row's running maximum rises: rescale its sum
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt) {
+            const float mn = fmaxf(m[rt], tm[rt]);
+            l[rt] *= fast_exp2(m[rt] - mn);
+            m[rt] = mn;
+          }
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          const float nm = -m[rt];
+          l[rt] += (fast_exp2(fmaf(acc[rt][0], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][1], a.sl2, nm))) +
+                   (fast_exp2(fmaf(acc[rt][2], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][3], a.sl2, nm)));
+        }
+      } else {
+        const int kfirst = key0 + 16 * kt + 4 * c;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          float x[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) x[r] = (kfirst + r <= lim[rt]) ? acc[rt][r] * a.sl2 : -INFINITY;
+          const float tm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+          const float mn = fmaxf(m[rt], tm);
+          const float ms = (mn == -INFINITY) ? 0.f : mn;
+          l[rt] = l[rt] * fast_exp2(m[rt] - ms) +
+                  ((fast_exp2(x[0] - ms) + fast_exp2(x[1] - ms)) + (fast_exp2(x[2] - ms) + fast_exp2(x[3] - ms)));
+          m[rt] = mn;
+        }
+      }
+    }
+  };
+
+  for (int s = 0; s < nstages; s += 2) {
+    if (s + 2 < nstages) KS::load(r0, kbase, (s + 2) * SK, n);
+    compute(s_k[0], s * SK);
+    if (s + 1 < nstages) KS::store(r1, s_k[1]);
+    __syncthreads();
+    if (s + 1 >= nstages) break;
+    if (s + 3 < nstages) KS::load(r1, kbase, (s + 3) * SK, n);
+    compute(s_k[1], (s + 1) * SK);
+    if (s + 2 < nstages) KS::store(r0, s_k[0]);
+    __syncthreads();
+  }
+
+  // merge the four lanes that hold the same row (different keys); padding rows get +inf so that
+  // pass 2 turns them into probability 0
+  float* out = a.row_lse + static_cast<int64_t>(b * a.Hq + hq) * a.lse_stride;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    merge_ml(m[rt], l[rt], __shfl_xor(m[rt], 16), __shfl_xor(l[rt], 16));
+    merge_ml(m[rt], l[rt], __shfl_xor(m[rt], 32), __shfl_xor(l[rt], 32));
+    const int row = wrow0 + rt * 16 + i;
+    if (c == 0 && row < a.lse_stride) out[row] = (row < n && l[rt] > 0.f) ? m[rt] + fast_log2(l[rt]) : INFINITY;
+  }
+}
+
+template <typename T, int D, int RT>
+__global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
+  using KS = KeyStream<T, D>;
+  constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys, EPL = KS::EPL, KD = KS::KD;
+  constexpr int WR = 16 * RT, BR = 4 * WR;
+  const int bg = blockIdx.y;
+  const int g = bg % a.Hkv, b = bg / a.Hkv;
+  int off0;
+  const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
+  if (n <= a.B) return;
+  const int j0 = static_cast<int>(blockIdx.x) * BR;            // early keys (most rows) come first
+  if (j0 >= n) return;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int i = lane & 15, c = lane >> 4;
+  const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
+  const T* kbase = static_cast<const T*>(a.k) + head_tok * D;
+  const int wkey0 = j0 + wv * WR;                // first key of this wave
+
+  __shared__ __attribute__((aligned(16))) char s_q[2][KS::kStageBytes];
+  u32x4 kf[RT][NK];
+  int kpos[RT];                                  // position of the lane's key; beyond every row for padding keys
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int key = wkey0 + rt * 16 + i;
+    const bool valid = key < n;
+    const T* kp = kbase + static_cast<int64_t>(valid ? key : 0) * D + c * EPL;
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) kf[rt][kk] = valid ? ld16(kp + kk * KD) : zero16();
+    kpos[rt] = valid ? key : 0x7fffffff;
+  }
+  float v[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) v[rt] = 0.f;
+
+  // the streamed sequence of stages: for each query head of the group, rows j0 .. n-1
+  const int nst = (n - j0 + SK - 1) / SK;
+  const int nstages = nst * a.G;
+  auto issue = [&](typename KS::Regs& r, int s) {
+    const int hh = s / nst, q0 = j0 + (s - hh * nst) * SK;
+    const T* qbase = static_cast<const T*>(a.q_full) +
+                     (static_cast<int64_t>(off0) * a.Hq + static_cast<int64_t>(g * a.G + hh) * n) * D;
+    KS::load(r, qbase, q0, n);
+  };
+  typename KS::Regs r0, r1;
+  issue(r0, 0);
+  if (nstages > 1) issue(r1, 1);
+  KS::store(r0, s_q[0]);
+  __syncthreads();
+
+  auto compute = [&](const char* lds, int s) {
+    const int hh = s / nst, q0 = j0 + (s - hh * nst) * SK;
+    if (q0 + SK - 1 < wkey0 || wkey0 >= n) return;           // no row of the stage sees a key of this wave
+    const bool full = q0 >= wkey0 + WR - 1;                   // every row sees every key of the wave
+    const float* lz = a.row_lse + static_cast<int64_t>(b * a.Hq + g * a.G + hh) * a.lse_stride + q0 + 4 * c;
+    f32x4 z[KT];                                 // row log-sum-exp of rows q0 + 16 kt + 4 c + r; +inf beyond n
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) z[kt] = *reinterpret_cast<const f32x4*>(lz + 16 * kt);
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      u32x4 qf[NK];
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) qf[kk] = KS::frag(lds, kt, kk, i, c);
+      const int qfirst = q0 + 16 * kt + 4 * c;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc, qf[kk], kf[rt][kk]);
+        // acc[r] <-> row qfirst + r, key (rt, i)
+        if (full) {
+          v[rt] += (fast_exp2(fmaf(acc[0], a.sl2, -z[kt][0])) + fast_exp2(fmaf(acc[1], a.sl2, -z[kt][1]))) +
+                   (fast_exp2(fmaf(acc[2], a.sl2, -z[kt][2])) + fast_exp2(fmaf(acc[3], a.sl2, -z[kt][3])));
+        } else {
+          float p[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            p[r] = (qfirst + r >= kpos[rt]) ? fast_exp2(fmaf(acc[r], a.sl2, -z[kt][r])) : 0.f;
+          v[rt] += (p[0] + p[1]) + (p[2] + p[3]);
+        }
+      }
+    }
+  };
+
+  for (int s = 0; s < nstages; s += 2) {
+    if (s + 2 < nstages) issue(r0, s + 2);
+    compute(s_q[0], s);
+    if (s + 1 < nstages) KS::store(r1, s_q[1]);
+    __syncthreads();
+    if (s + 1 >= nstages) break;
+    if (s + 3 < nstages) issue(r1, s + 3);
+    compute(s_q[1], s + 1);
+    if (s + 2 < nstages) KS::store(r0, s_q[0]);
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const float tot = col4_sum(v[rt]);           // the four row groups c, fixed tree
+    const int key = wkey0 + rt * 16 + i;
+    if (c == 0 && key < n) a.vote[head_tok + key] = tot;
+  }
+}
+
+}  // namespace cd

@@ -145,3 +145,40 @@ def seq_view(flat: torch.Tensor, wl: Workload, b: int) -> torch.Tensor:
     lo = sum(wl.seq_lens[:b]) * Hkv * D
     n = wl.seq_lens[b]
     return flat[lo:lo + n * Hkv * D].view(Hkv, n, D)
+
+
+def full_queries(wl: Workload, x: dict, seed: int = BASE_SEED, device="cpu") -> torch.Tensor:
+    """Every prompt query (what a strategy that scores with all queries reads), packed like K
+    but with Hq heads: sequence b starts at token seq_offsets[b], inside [Hq][n_b][D].  Per
+    (sequence, head) a stationary AR(1) chain along the positions (same rho as the window
+    chain); the last w positions are exactly x["q_win"], so Q_{-1} is the same query."""
+    dt = wl.torch_dtype
+    Hq, D, w, rho = wl.n_q_heads, wl.head_dim, wl.window, wl.rho
+    C = 64                                                        # positions generated per step
+    j = torch.arange(C, device=device, dtype=torch.float32)
+    tri = torch.tril(rho ** (j[:, None] - j[None, :]).clamp(min=0.0))        # tri[j][s] = rho^(j-s), s <= j
+    carry = (rho ** (j + 1.0))[:, None, None]
+    parts = []
+    g = torch.Generator(device=device)
+    for b, n in enumerate(wl.seq_lens):
+        g.manual_seed(seed + 15485863 * (b + 1))
+        m = max(n - w, 0)
+        chain = torch.empty((m, Hq, D), dtype=torch.float32, device=device)
+        prev = torch.randn((Hq, D), generator=g, device=device) / (1.0 - rho ** 2) ** 0.5
+        for t0 in range(0, m, C):
+            c = min(C, m - t0)
+            e = torch.randn((c, Hq, D), generator=g, device=device)
+            blk = torch.einsum("js,shd->jhd", tri[:c, :c], e) + carry[:c] * prev
+            chain[t0:t0 + c] = blk
+            prev = blk[c - 1]
+        qb = torch.cat([chain.permute(1, 0, 2).to(dt), x["q_win"][b][:, max(w - n, 0):]], dim=1)   # [Hq][n][D]
+        parts.append(qb.reshape(-1))
+    return torch.cat(parts)
+
+
+def seq_view_q(flat: torch.Tensor, wl: Workload, b: int) -> torch.Tensor:
+    """[Hq][n_b][D] view of sequence ``b`` inside a packed full-query buffer."""
+    Hq, D = wl.n_q_heads, wl.head_dim
+    lo = sum(wl.seq_lens[:b]) * Hq * D
+    n = wl.seq_lens[b]
+    return flat[lo:lo + n * Hq * D].view(Hq, n, D)
