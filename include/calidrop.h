@@ -100,6 +100,12 @@ size_t calidrop_decode_workspace_bytes(const calidrop_params* p, int32_t max_cac
  * written for prompts too long for the in-LDS selection.  Costs one extra pass of stores.      */
 void calidrop_set_inspection(int enabled);
 
+/* Selection variant switch (process-wide, default off).  The per-head top-k normally runs as one
+ * workgroup per head and switches to the multi-workgroup chain of launches only for prompts longer
+ * than 32768 (or pooling widths above 15); when on, the multi-workgroup chain is used for every
+ * call.  Same results either way (integer selection); for tests and tuning.                     */
+void calidrop_set_wide_selection(int enabled);
+
 /* Named regions inside the compress workspace, for inspection by tests and tools after the
  * stream has finished (SCORE needs calidrop_set_inspection(1) before the compress call).
  * Layouts:
@@ -279,8 +285,7 @@ int calidrop_compress_given(const calidrop_params* p, const void* q_cal, const v
  * seq_offsets[b], inside [Hq][n_b][D] (every prompt query, as used by attention); all other
  * arguments as in calidrop_compress; batch * n_q_heads <= 65535; workspace >=
  * calidrop_compress_h2o_workspace_bytes(p, n_local, total_tokens, max_seq_len) bytes, 256-byte
- * aligned.  With calidrop_set_inspection(1) nothing extra is stored here (the votes are always
- * in the workspace).
+ * aligned.
  */
 size_t calidrop_compress_h2o_workspace_bytes(const calidrop_params* p, int32_t n_local,
                                              int64_t total_tokens, int32_t max_seq_len);
@@ -288,7 +293,8 @@ size_t calidrop_compress_h2o_workspace_bytes(const calidrop_params* p, int32_t n
  *   ROW_LSE float [batch][Hq][stride]: log2 of the softmax denominator of every prompt query
  *           (logits in log2 units), stride = bytes / (batch * Hq * 4) >= max_seq_len, +inf padded;
  *   SCORE   float, packed like K with D = 1: vote of position j of KV head g of sequence b at
- *           [seq_offsets[b]*Hkv + g*n_b + j], j < n_b.                                          */
+ *           [seq_offsets[b]*Hkv + g*n_b + j], for the candidates j < n_b - n_local (needs
+ *           calidrop_set_inspection(1) before the call unless the prompt is longer than 32768).  */
 int calidrop_compress_h2o_workspace_region(const calidrop_params* p, int32_t n_local,
                                            int64_t total_tokens, int32_t max_seq_len,
                                            int32_t region, size_t* offset, size_t* bytes);

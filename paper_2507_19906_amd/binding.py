@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.calidrop_version.argtypes = []
         L.calidrop_set_inspection.restype = None
         L.calidrop_set_inspection.argtypes = [ctypes.c_int]
+        L.calidrop_set_wide_selection.restype = None
+        L.calidrop_set_wide_selection.argtypes = [ctypes.c_int]
         L.calidrop_compress_workspace_bytes.restype = sz
         L.calidrop_compress_workspace_bytes.argtypes = [pp, i64, i32]
         L.calidrop_decode_workspace_bytes.restype = sz
@@ -127,6 +129,10 @@ def calidrop_last_error() -> str:
 
 def calidrop_set_inspection(enabled: bool) -> None:
     lib().calidrop_set_inspection(1 if enabled else 0)
+
+
+def calidrop_set_wide_selection(enabled: bool) -> None:
+    lib().calidrop_set_wide_selection(1 if enabled else 0)
 
 
 def _check(status: int) -> None:

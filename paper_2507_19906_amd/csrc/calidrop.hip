@@ -21,6 +21,7 @@ namespace {
 
 thread_local char g_err[512] = "";
 std::atomic<int> g_inspection{0};   // calidrop_set_inspection
+std::atomic<int> g_wide_select{0};  // calidrop_set_wide_selection
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -184,7 +185,8 @@ int run_selection(const calidrop_params* p, int window, int pool_k, int max_seq_
   const int bg = p->batch * p->n_kv_heads;
   const int max_prefix = max_seq_len - window;
   se.write_scores = g_inspection.load(std::memory_order_relaxed);
-  if (max_prefix <= cd::kSelMaxLdsKeys && p->budget <= cd::kSelMaxLdsKeys && pool_k <= cd::kSelMaxPool) {
+  if (max_prefix <= cd::kSelMaxLdsKeys && p->budget <= cd::kSelMaxLdsKeys && pool_k <= cd::kSelMaxPool &&
+      !g_wide_select.load(std::memory_order_relaxed)) {
     // dynamic LDS: staged votes (padded), later reused for the retained indices
     size_t lds = static_cast<size_t>(p->budget) * sizeof(int32_t);
     if (max_seq_len > p->budget) {
@@ -538,7 +540,7 @@ H2oLayout h2o_layout(const calidrop_params* p, int64_t total_tokens, int32_t max
   const size_t slots = static_cast<size_t>(p->batch) * p->n_q_heads * L.sp.NS;
   size_t off = 0;
   L.row_lse = off; off += round256(static_cast<size_t>(p->batch) * p->n_q_heads * L.lse_stride * sizeof(float));
-  L.vote = off;    off += round256(toks * sizeof(float));
+  L.vote = off;    off += round256(toks * (p->n_q_heads / p->n_kv_heads) * sizeof(float));   // one plane per head of a group
   L.score = off;   off += round256(toks * sizeof(float));
   L.bitmap = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.W32 * sizeof(uint32_t));
   L.q_last = off;  off += round256(static_cast<size_t>(p->batch) * p->n_q_heads * p->head_dim * sizeof(float));
@@ -573,19 +575,19 @@ int h2o_impl(const calidrop_params* p, int n_local, const void* q_full, const vo
   hipLaunchKernelGGL((cd::h2o_rowlse_kernel<T, D, kH2oRowTiles>), dim3(nblk, p->batch * p->n_q_heads), dim3(256), 0, st, ha);
   if ((rc = launch_status("h2o_rowlse"))) return rc;
   if (max_seq_len > p->budget) {
-    hipLaunchKernelGGL((cd::h2o_votes_kernel<T, D, kH2oRowTiles>), dim3(nblk, bg), dim3(256), 0, st, ha);
+    hipLaunchKernelGGL((cd::h2o_votes_kernel<T, D, kH2oRowTiles>), dim3((nblk + 1) / 2, bg, G), dim3(256), 0, st, ha);
     if ((rc = launch_status("h2o_votes"))) return rc;
   }
   // selection: the votes are the scores (no pooling); the local window plays the part of the
   // observation window (always kept, not a candidate)
   cd::ScoreArgs sa{};
   sa.seq_off = seq_offsets; sa.total_tokens = total_tokens; sa.batch = p->batch; sa.Hq = p->n_q_heads;
-  sa.Hkv = p->n_kv_heads; sa.G = G; sa.w = n_local; sa.B = p->budget; sa.NRB = 1; sa.max_seq_len = max_seq_len;
+  sa.Hkv = p->n_kv_heads; sa.G = G; sa.w = n_local; sa.B = p->budget; sa.NRB = G; sa.max_seq_len = max_seq_len;
   sa.pool_k = 1; sa.vote = ha.vote; sa.score = reinterpret_cast<float*>(ws + L.score);
   cd::SelectArgs se{};
   se.seq_off = seq_offsets; se.cache_off = cache_offsets; se.total_tokens = total_tokens; se.batch = p->batch;
   se.Hkv = p->n_kv_heads; se.w = n_local; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
-  se.NRB = 1; se.pool_k = 1; se.row_bytes = D * static_cast<int>(sizeof(T));
+  se.NRB = G; se.pool_k = 1; se.row_bytes = D * static_cast<int>(sizeof(T));
   se.vote = sa.vote; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
   se.calib = p->calib_size; se.cal_indices = cal_indices;
   se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
@@ -623,6 +625,7 @@ extern "C" {
 const char* calidrop_last_error(void) { return g_err; }
 int calidrop_version(void) { return 200; }
 void calidrop_set_inspection(int enabled) { g_inspection.store(enabled ? 1 : 0, std::memory_order_relaxed); }
+void calidrop_set_wide_selection(int enabled) { g_wide_select.store(enabled ? 1 : 0, std::memory_order_relaxed); }
 
 size_t calidrop_compress_workspace_bytes(const calidrop_params* p_in, int64_t total_tokens, int32_t max_seq_len) {
   calidrop_params pp; const calidrop_params* p = &pp;
@@ -974,7 +977,7 @@ int calidrop_compress_h2o_workspace_region(const calidrop_params* p_in, int32_t 
     *offset = L.row_lse;
     *bytes = static_cast<size_t>(p->batch) * p->n_q_heads * L.lse_stride * sizeof(float);
   } else if (region == CALIDROP_REGION_SCORE) {
-    *offset = L.vote;
+    *offset = L.score;
     *bytes = static_cast<size_t>(total_tokens) * p->n_kv_heads * sizeof(float);
   } else {
     return fail(CALIDROP_EINVAL, "unknown workspace region %d", region);

@@ -118,6 +118,13 @@ __device__ __forceinline__ float col4_sum(float x) {
   return x;
 }
 
+// Three-input maximum in one instruction (operands are never NaN here, so no canonicalisation).
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
 // Merge two (max, sum-of-exp2) pairs in the log2 domain; (-inf, 0) is the identity.
 __device__ __forceinline__ void merge_ml(float& m, float& l, float m2, float l2) {
   float mn = fmaxf(m, m2);

@@ -29,7 +29,7 @@ struct H2oArgs {
   int lse_stride;            // floats per (sequence, query head) in row_lse; a multiple of the row block
   float sl2;                 // scale * log2(e)
   float* row_lse;            // [batch*Hq][lse_stride], log2 units; rows >= n_b hold +inf
-  float* vote;               // [total_tokens*Hkv], packed like K with one float per row
+  float* vote;               // [G][total_tokens*Hkv]: one plane per query head of the group, each packed like K with one float per row
   void* q_last;              // [batch][Hq][D]: the last prompt query of every head (Q_{-1})
 };
 
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
         bool grow = false;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-          tm[rt] = fmaxf(fmaxf(acc[rt][0], acc[rt][1]), fmaxf(acc[rt][2], acc[rt][3])) * a.sl2;
+          tm[rt] = max3(max3(acc[rt][0], acc[rt][1], acc[rt][2]), acc[rt][3], acc[rt][3]) * a.sl2;
           grow |= tm[rt] > m[rt];
         }
         if (__any(grow)) {               // some row's running maximum rises: rescale its sum
@@ -166,101 +166,117 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
   using KS = KeyStream<T, D>;
   constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys, EPL = KS::EPL, KD = KS::KD;
   constexpr int WR = 16 * RT, BR = 4 * WR;
-  const int bg = blockIdx.y;
+  // grid: x = pair of key blocks (block x and its mirror nblk-1-x: early keys are seen by many
+  // rows, late keys by few, so every workgroup gets the same amount of work), y = (sequence, KV
+  // head), z = query head of the group; each query head writes its own plane of votes, which
+  // the selection adds up in a fixed order.
+  const int bg = blockIdx.y, hh = blockIdx.z;
   const int g = bg % a.Hkv, b = bg / a.Hkv;
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   if (n <= a.B) return;
-  const int j0 = static_cast<int>(blockIdx.x) * BR;            // early keys (most rows) come first
-  if (j0 >= n) return;
+  const int nblk = (n + BR - 1) / BR;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int i = lane & 15, c = lane >> 4;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
   const T* kbase = static_cast<const T*>(a.k) + head_tok * D;
-  const int wkey0 = j0 + wv * WR;                // first key of this wave
+  const int hq = g * a.G + hh;
+  const T* qbase = static_cast<const T*>(a.q_full) + (static_cast<int64_t>(off0) * a.Hq + static_cast<int64_t>(hq) * n) * D;
+  const float* lse_row = a.row_lse + static_cast<int64_t>(b * a.Hq + hq) * a.lse_stride;
+  float* vote = a.vote + static_cast<int64_t>(hh) * a.total_tokens * a.Hkv + head_tok;
 
   __shared__ __attribute__((aligned(16))) char s_q[2][KS::kStageBytes];
-  u32x4 kf[RT][NK];
-  int kpos[RT];                                  // position of the lane's key; beyond every row for padding keys
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int key = wkey0 + rt * 16 + i;
-    const bool valid = key < n;
-    const T* kp = kbase + static_cast<int64_t>(valid ? key : 0) * D + c * EPL;
-#pragma unroll
-    for (int kk = 0; kk < NK; ++kk) kf[rt][kk] = valid ? ld16(kp + kk * KD) : zero16();
-    kpos[rt] = valid ? key : 0x7fffffff;
-  }
-  float v[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) v[rt] = 0.f;
+  __shared__ __attribute__((aligned(16))) float s_z[2][SK];      // row log-sum-exp of the staged rows
 
-  // the streamed sequence of stages: for each query head of the group, rows j0 .. n-1
-  const int nst = (n - j0 + SK - 1) / SK;
-  const int nstages = nst * a.G;
-  auto issue = [&](typename KS::Regs& r, int s) {
-    const int hh = s / nst, q0 = j0 + (s - hh * nst) * SK;
-    const T* qbase = static_cast<const T*>(a.q_full) +
-                     (static_cast<int64_t>(off0) * a.Hq + static_cast<int64_t>(g * a.G + hh) * n) * D;
-    KS::load(r, qbase, q0, n);
-  };
-  typename KS::Regs r0, r1;
-  issue(r0, 0);
-  if (nstages > 1) issue(r1, 1);
-  KS::store(r0, s_q[0]);
-  __syncthreads();
+  for (int job = 0; job < 2; ++job) {
+    const int blk = job == 0 ? static_cast<int>(blockIdx.x) : nblk - 1 - static_cast<int>(blockIdx.x);
+    // uniform over the workgroup: the first half of the blocks as job 0, their mirrors as job 1
+    if (job == 0 ? 2 * blk >= nblk : (blk < 0 || blk <= static_cast<int>(blockIdx.x))) continue;
+    const int j0 = blk * BR;
+    const int wkey0 = j0 + wv * WR;                // first key of this wave
+    u32x4 kf[RT][NK];
+    int kpos[RT];                                  // position of the lane's key; beyond every row for padding keys
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int key = wkey0 + rt * 16 + i;
+      const bool valid = key < n;
+      const T* kp = kbase + static_cast<int64_t>(valid ? key : 0) * D + c * EPL;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) kf[rt][kk] = valid ? ld16(kp + kk * KD) : zero16();
+      kpos[rt] = valid ? key : 0x7fffffff;
+    }
+    float v[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) v[rt] = 0.f;
 
-  auto compute = [&](const char* lds, int s) {
-    const int hh = s / nst, q0 = j0 + (s - hh * nst) * SK;
-    if (q0 + SK - 1 < wkey0 || wkey0 >= n) return;           // no row of the stage sees a key of this wave
-    const bool full = q0 >= wkey0 + WR - 1;                   // every row sees every key of the wave
-    const float* lz = a.row_lse + static_cast<int64_t>(b * a.Hq + g * a.G + hh) * a.lse_stride + q0 + 4 * c;
-    f32x4 z[KT];                                 // row log-sum-exp of rows q0 + 16 kt + 4 c + r; +inf beyond n
+    // streamed rows: j0 .. n-1 of this query head, SK per stage, with their log-sum-exp
+    const int nstages = (n - j0 + SK - 1) / SK;
+    typename KS::Regs r0, r1;
+    f32x4 z0, z1;
+    auto issue = [&](typename KS::Regs& r, f32x4& z, int s) {
+      KS::load(r, qbase, j0 + s * SK, n);
+      if (threadIdx.x < SK / 4) z = *reinterpret_cast<const f32x4*>(lse_row + j0 + s * SK + 4 * threadIdx.x);
+    };
+    auto stash = [&](const typename KS::Regs& r, const f32x4& z, int buf) {
+      KS::store(r, s_q[buf]);
+      if (threadIdx.x < SK / 4) *reinterpret_cast<f32x4*>(&s_z[buf][4 * threadIdx.x]) = z;
+    };
+    __syncthreads();                               // the previous job is done with the buffers
+    issue(r0, z0, 0);
+    if (nstages > 1) issue(r1, z1, 1);
+    stash(r0, z0, 0);
+    __syncthreads();
+
+    auto compute = [&](int buf, int s) {
+      const int q0 = j0 + s * SK;
+      if (q0 + SK - 1 < wkey0 || wkey0 >= n) return;          // no row of the stage sees a key of this wave
+      const bool full = q0 >= wkey0 + WR - 1;                  // every row sees every key of the wave
+      const char* lds = s_q[buf];
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) z[kt] = *reinterpret_cast<const f32x4*>(lz + 16 * kt);
+      for (int kt = 0; kt < KT; ++kt) {
+        u32x4 qf[NK];
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-      u32x4 qf[NK];
+        for (int kk = 0; kk < NK; ++kk) qf[kk] = KS::frag(lds, kt, kk, i, c);
+        const f32x4 z = *reinterpret_cast<const f32x4*>(&s_z[buf][16 * kt + 4 * c]);   // rows q0+16kt+4c+r; +inf beyond n
+        const int qfirst = q0 + 16 * kt + 4 * c;
 #pragma unroll
-      for (int kk = 0; kk < NK; ++kk) qf[kk] = KS::frag(lds, kt, kk, i, c);
-      const int qfirst = q0 + 16 * kt + 4 * c;
+        for (int rt = 0; rt < RT; ++rt) {
+          f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc, qf[kk], kf[rt][kk]);
+          // acc[r] <-> row qfirst + r, key (rt, i)
+          if (full) {
+            v[rt] += (fast_exp2(fmaf(acc[0], a.sl2, -z[0])) + fast_exp2(fmaf(acc[1], a.sl2, -z[1]))) +
+                     (fast_exp2(fmaf(acc[2], a.sl2, -z[2])) + fast_exp2(fmaf(acc[3], a.sl2, -z[3])));
+          } else {
+            float p[4];
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc, qf[kk], kf[rt][kk]);
-        // acc[r] <-> row qfirst + r, key (rt, i)
-        if (full) {
-          v[rt] += (fast_exp2(fmaf(acc[0], a.sl2, -z[kt][0])) + fast_exp2(fmaf(acc[1], a.sl2, -z[kt][1]))) +
-                   (fast_exp2(fmaf(acc[2], a.sl2, -z[kt][2])) + fast_exp2(fmaf(acc[3], a.sl2, -z[kt][3])));
-        } else {
-          float p[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            p[r] = (qfirst + r >= kpos[rt]) ? fast_exp2(fmaf(acc[r], a.sl2, -z[kt][r])) : 0.f;
-          v[rt] += (p[0] + p[1]) + (p[2] + p[3]);
+            for (int r = 0; r < 4; ++r)
+              p[r] = (qfirst + r >= kpos[rt]) ? fast_exp2(fmaf(acc[r], a.sl2, -z[r])) : 0.f;
+            v[rt] += (p[0] + p[1]) + (p[2] + p[3]);
+          }
         }
       }
-    }
-  };
+    };
 
-  for (int s = 0; s < nstages; s += 2) {
-    if (s + 2 < nstages) issue(r0, s + 2);
-    compute(s_q[0], s);
-    if (s + 1 < nstages) KS::store(r1, s_q[1]);
-    __syncthreads();
-    if (s + 1 >= nstages) break;
-    if (s + 3 < nstages) issue(r1, s + 3);
-    compute(s_q[1], s + 1);
-    if (s + 2 < nstages) KS::store(r0, s_q[0]);
-    __syncthreads();
-  }
+    for (int s = 0; s < nstages; s += 2) {
+      if (s + 2 < nstages) issue(r0, z0, s + 2);
+      compute(0, s);
+      if (s + 1 < nstages) stash(r1, z1, 1);
+      __syncthreads();
+      if (s + 1 >= nstages) break;
+      if (s + 3 < nstages) issue(r1, z1, s + 3);
+      compute(1, s + 1);
+      if (s + 2 < nstages) stash(r0, z0, 0);
+      __syncthreads();
+    }
 
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const float tot = col4_sum(v[rt]);           // the four row groups c, fixed tree
-    const int key = wkey0 + rt * 16 + i;
-    if (c == 0 && key < n) a.vote[head_tok + key] = tot;
+    for (int rt = 0; rt < RT; ++rt) {
+      const float tot = col4_sum(v[rt]);           // the four row groups c, fixed tree
+      const int key = wkey0 + rt * 16 + i;
+      if (c == 0 && key < n) vote[key] = tot;
+    }
   }
 }
 

@@ -40,8 +40,8 @@ def check_h2o(wl, x, q_full, bufs, n_local, rep, calib=0):
             # scores first: they explain any index difference
             off = int(sum(wl.seq_lens[:b])) * wl.n_kv_heads
             for g in range(wl.n_kv_heads):
-                s_gpu = vote_gpu[off + g * n: off + (g + 1) * n]
-                s_ref = orc["vote"][g]
+                s_gpu = vote_gpu[off + g * n: off + g * n + (n - loc)]      # scores of the candidates
+                s_ref = orc["vote"][g][:n - loc]
                 rel = np.abs(s_gpu - s_ref) / (np.abs(s_ref) + 1e-30)
                 big = s_ref > 1e-9 * s_ref.max()
                 rep["vote_rel_err"] = max(rep.get("vote_rel_err", 0), rel[big].max())
@@ -88,6 +88,7 @@ def test_h2o_strategy(wl, n_local):
     q_full = synth.full_queries(wl, x, 61, DEV)
     p = H.params_for(wl)
     bufs = cd.CompressBuffers(p, wl.seq_lens, DEV)
+    cd.calidrop_set_inspection(True)          # the parity checks read the candidates' scores
     bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"], n_local=n_local)
     torch.cuda.synchronize()
     rep = {}
@@ -112,11 +113,52 @@ def test_h2o_is_deterministic():
     x = to_dev(synth.make_inputs(wl, 62))
     q_full = synth.full_queries(wl, x, 62, DEV)
     outs = []
+    cd.calidrop_set_inspection(True)
     for _ in range(2):
         bufs = cd.CompressBuffers(H.params_for(wl), wl.seq_lens, DEV)
         bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
         torch.cuda.synchronize()
-        outs.append((bufs.indices.clone(), bufs.c_out.clone(), bufs.c_lse.clone(),
-                     bufs.h2o_region(cd.REGION_SCORE).clone()))
+        score = bufs.h2o_region(cd.REGION_SCORE).view(wl.n_kv_heads, 1500)[:, :1500 - 64]   # candidates only
+        outs.append((bufs.indices.clone(), bufs.c_out.clone(), bufs.c_lse.clone(), score.clone()))
     for a, c in zip(*outs):
         assert torch.equal(a, c)
+
+
+@pytest.fixture
+def wide_selection():
+    cd.calidrop_set_wide_selection(True)
+    yield
+    cd.calidrop_set_wide_selection(False)
+
+
+def test_h2o_with_multi_workgroup_selection(wide_selection):
+    # the same strategy through the selection variant long prompts take (several workgroups per
+    # head, per-head vote planes added by the pooling kernel), at a size the oracle can follow
+    wl = small("bf16", 8, 2, 128, [9000, 300], 16, 256, 1, T=2, name="h2o_wide")
+    x = to_dev(synth.make_inputs(wl, 63))
+    q_full = synth.full_queries(wl, x, 63, DEV)
+    bufs = cd.CompressBuffers(H.params_for(wl, calib_size=700), wl.seq_lens, DEV)
+    cd.calidrop_set_inspection(True)
+    bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    # same lists as the single-workgroup variant
+    cd.calidrop_set_wide_selection(False)
+    twin = cd.CompressBuffers(H.params_for(wl, calib_size=700), wl.seq_lens, DEV)
+    twin.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    assert torch.equal(bufs.indices, twin.indices) and torch.equal(bufs.cal_indices, twin.cal_indices)
+    assert torch.equal(bufs.k_c, twin.k_c) and torch.equal(bufs.c_out, twin.c_out)
+    # and the oracle on the retained set (calibration state is over the 700 best evicted tokens)
+    n, B = 9000, 256
+    K = H.to64(synth.seq_view(x["k"], wl, 0)); V = H.to64(synth.seq_view(x["v"], wl, 0))
+    Q = H.to64(synth.seq_view_q(q_full, wl, 0))
+    orc = ref.compress_h2o(Q, K, V, B, B // 2)
+    rep = {}
+    fake = dict(idx=orc["idx"], score=[v[:n - B // 2] for v in orc["vote"]], margin=orc["margin"])
+    assert H.check_indices(bufs.indices[0].cpu().numpy(), fake, wl.dtype, B - B // 2, rep) is None
+    cal = bufs.cal_indices[0].cpu().numpy()
+    for g in range(2):
+        ev = orc["evicted"][g]
+        ev = ev[ev < n - B // 2]
+        order = np.argsort(-orc["vote"][g][ev], kind="stable")[:700]
+        assert np.array_equal(cal[g], np.sort(ev[order]))

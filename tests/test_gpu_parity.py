@@ -412,3 +412,26 @@ def test_calibration_size_with_multi_workgroup_selection(dtype, m):
             H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
     rep.pop("flags", None)
     print(wl.name, rep, flush=True)
+
+
+@pytest.fixture
+def wide_selection():
+    cd.calidrop_set_wide_selection(True)
+    yield
+    cd.calidrop_set_wide_selection(False)
+
+
+@pytest.mark.parametrize("wl", [
+    small("bf16", 8, 2, 64, [777], 16, 100, 5, name="wide_ragged_bf16_d64"),
+    small("fp32", 6, 2, 64, [300, 1000, 50, 257], 16, 64, 5, name="wide_varlen_with_short_seq"),
+    small("bf16", 32, 8, 128, [513, 2049, 100, 640], 32, 512, 7, name="wide_varlen_bf16_budget_edge"),
+    small("bf16", 4, 1, 128, [65], 1, 2, 1, name="wide_window1_budget2"),
+], ids=lambda w: w.name)
+def test_multi_workgroup_selection_on_short_prompts(wl, wide_selection):
+    # the chain of launches long prompts use, forced on shapes with one (partial) segment per head
+    run_case(wl)
+
+
+def test_exact_ties_with_multi_workgroup_selection(wide_selection):
+    test_exact_ties_lower_index_wins(16 * 40 + 16, 1, 40, 50)
+    test_exact_ties_lower_index_wins(20016, 1, 3000, 2500)
