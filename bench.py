@@ -284,6 +284,34 @@ def main():
             del store
         del b3
 
+    # H2O as the eviction strategy (accumulated attention of every prompt query: two dense causal
+    # passes on the matrix cores) for one layer of the same shape
+    h2o = None
+    if not args.no_extra:
+        wl4 = synth.config(3, layers=1, budget=args.budget, decode_steps=1)
+        p4 = cd.make_params(dtype=wl4.dtype, batch=1, n_q_heads=wl4.n_q_heads, n_kv_heads=wl4.n_kv_heads,
+                            head_dim=wl4.head_dim, window=wl4.window, budget=wl4.budget, pool_kernel=1,
+                            theta1=wl4.theta1, theta2=wl4.theta2)
+        n4 = wl4.seq_lens[0]
+        x4 = {"q_win": x["q_win"][:1].contiguous()}
+        qf = synth.full_queries(wl4, x4, synth.BASE_SEED, dev)
+        nel = n4 * wl.n_kv_heads * wl.head_dim
+        b4 = cd.CompressBuffers(p4, wl4.seq_lens, dev)
+        so4 = x["seq_offsets"][:2].clone()
+        times = []
+        for _ in range(3):
+            e0, e1 = ev(), ev()
+            e0.record(stream)
+            b4.compress_h2o(qf, x["k"][:nel], x["v"][:nel], so4, stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        ms = min(times)
+        flop = 2 * 2.0 * wl4.n_q_heads * (n4 * (n4 + 1) / 2) * wl4.head_dim       # two causal QK^T passes
+        h2o = {"ms_per_layer": ms, "causal_TFLOP": flop / 1e12, "TFLOPps": flop / ms / 1e9,
+               "pct_bf16_mfma_peak": 100.0 * flop / ms / 1e9 / 2500.0}
+        del b4, qf
+
     gbps = dbytes / (dec * 1e-3) / 1e9
     # window scoring (the two MFMA passes of compress): 2*Hq*w*n*D flop per layer and pass
     score_flop = 2.0 * wl.n_q_heads * wl.window * wl.seq_lens[0] * wl.head_dim * wl.batch
@@ -310,6 +338,7 @@ def main():
         "recalibrate_all_heads_us_per_layer": None if recal_us is None else recal_us / wl.batch,
         "recalibrate_all_heads_GBps": None if recal_us is None else compress_bytes(wl) / recal_us / 1e3,
         "recalibrate_all_heads_from_packed_evicted": packed,
+        "compress_h2o_strategy": h2o,
         "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel<bf16,128,8>",
                      "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
                      # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of this kernel on this workload,
