@@ -81,59 +81,68 @@ __global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
   KS::store(r0, s_k[0]);
   __syncthreads();
 
-  auto compute = [&](const char* lds, int key0) {
-    if (key0 > wrow0 + WR - 1 || wrow0 >= n) return;        // nothing of this stage is visible to the wave
-    const bool full = key0 + SK - 1 <= wrow0 && wrow0 + WR <= n;   // every key visible to every (real) row
+  // S^T tile kt of a stage: keys 16 kt .. 16 kt + 15 against this wave's rows
+  auto mma_tile = [&](const char* lds, int kt, f32x4 (&acc)[RT]) {
+    u32x4 kf[NK];
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-      u32x4 kf[NK];
+    for (int kk = 0; kk < NK; ++kk) kf[kk] = KS::frag(lds, kt, kk, i, c);
 #pragma unroll
-      for (int kk = 0; kk < NK; ++kk) kf[kk] = KS::frag(lds, kt, kk, i, c);
-      f32x4 acc[RT];
+    for (int rt = 0; rt < RT; ++rt) {
+      acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc[rt], kf[kk], qf[rt][kk]);
+    }
+  };
+  // acc[rt][r] <-> key kfirst + r, row (rt, i)
+  auto softmax_tile = [&](const f32x4 (&acc)[RT], int kfirst, bool full) {
+    if (full) {
+      float tm[RT];
+      bool grow = false;
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc[rt], kf[kk], qf[rt][kk]);
+        tm[rt] = max3(max3(acc[rt][0], acc[rt][1], acc[rt][2]), acc[rt][3], acc[rt][3]) * a.sl2;
+        grow |= tm[rt] > m[rt];
       }
-      // acc[rt][r] <-> key key0 + 16 kt + 4 c + r, row (rt, i)
-      if (full) {
-        float tm[RT];
-        bool grow = false;
+      if (__any(grow)) {               // some row's running maximum rises: rescale its sum
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-          tm[rt] = max3(max3(acc[rt][0], acc[rt][1], acc[rt][2]), acc[rt][3], acc[rt][3]) * a.sl2;
-          grow |= tm[rt] > m[rt];
-        }
-        if (__any(grow)) {               // some row's running maximum rises: rescale its sum
-#pragma unroll
-          for (int rt = 0; rt < RT; ++rt) {
-            const float mn = fmaxf(m[rt], tm[rt]);
-            l[rt] *= fast_exp2(m[rt] - mn);
-            m[rt] = mn;
-          }
-        }
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          const float nm = -m[rt];
-          l[rt] += (fast_exp2(fmaf(acc[rt][0], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][1], a.sl2, nm))) +
-                   (fast_exp2(fmaf(acc[rt][2], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][3], a.sl2, nm)));
-        }
-      } else {
-        const int kfirst = key0 + 16 * kt + 4 * c;
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          float x[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) x[r] = (kfirst + r <= lim[rt]) ? acc[rt][r] * a.sl2 : -INFINITY;
-          const float tm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-          const float mn = fmaxf(m[rt], tm);
-          const float ms = (mn == -INFINITY) ? 0.f : mn;
-          l[rt] = l[rt] * fast_exp2(m[rt] - ms) +
-                  ((fast_exp2(x[0] - ms) + fast_exp2(x[1] - ms)) + (fast_exp2(x[2] - ms) + fast_exp2(x[3] - ms)));
+          const float mn = fmaxf(m[rt], tm[rt]);
+          l[rt] *= fast_exp2(m[rt] - mn);
           m[rt] = mn;
         }
       }
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const float nm = -m[rt];
+        l[rt] += (fast_exp2(fmaf(acc[rt][0], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][1], a.sl2, nm))) +
+                 (fast_exp2(fmaf(acc[rt][2], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][3], a.sl2, nm)));
+      }
+    } else {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        float x[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = (kfirst + r <= lim[rt]) ? acc[rt][r] * a.sl2 : -INFINITY;
+        const float tm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+        const float mn = fmaxf(m[rt], tm);
+        const float ms = (mn == -INFINITY) ? 0.f : mn;
+        l[rt] = l[rt] * fast_exp2(m[rt] - ms) +
+                ((fast_exp2(x[0] - ms) + fast_exp2(x[1] - ms)) + (fast_exp2(x[2] - ms) + fast_exp2(x[3] - ms)));
+        m[rt] = mn;
+      }
+    }
+  };
+  // One stage.  The matrix products of tile kt+1 are issued before the softmax arithmetic of
+  // tile kt, so that the matrix cores and the vector ALU of this wave work at the same time.
+  auto compute = [&](const char* lds, int key0) {
+    if (key0 > wrow0 + WR - 1 || wrow0 >= n) return;        // nothing of this stage is visible to the wave
+    const bool full = key0 + SK - 1 <= wrow0 && wrow0 + WR <= n;   // every key visible to every (real) row
+    f32x4 acc[2][RT];
+    mma_tile(lds, 0, acc[0]);
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      if (kt + 1 < KT) mma_tile(lds, kt + 1, acc[(kt + 1) & 1]);
+      softmax_tile(acc[kt & 1], key0 + 16 * kt + 4 * c, full);
     }
   };
 
@@ -227,32 +236,42 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
     stash(r0, z0, 0);
     __syncthreads();
 
+    // S^T tile kt of a stage: rows 16 kt .. 16 kt + 15 of the stage against this wave's keys
+    auto mma_tile = [&](const char* lds, int kt, f32x4 (&acc)[RT]) {
+      u32x4 qf[NK];
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) qf[kk] = KS::frag(lds, kt, kk, i, c);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc[rt], qf[kk], kf[rt][kk]);
+      }
+    };
+    // the matrix products of tile kt+1 are issued before the exponentials of tile kt
     auto compute = [&](int buf, int s) {
       const int q0 = j0 + s * SK;
       if (q0 + SK - 1 < wkey0 || wkey0 >= n) return;          // no row of the stage sees a key of this wave
       const bool full = q0 >= wkey0 + WR - 1;                  // every row sees every key of the wave
       const char* lds = s_q[buf];
+      f32x4 acc[2][RT];
+      mma_tile(lds, 0, acc[0]);
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
-        u32x4 qf[NK];
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) qf[kk] = KS::frag(lds, kt, kk, i, c);
+        if (kt + 1 < KT) mma_tile(lds, kt + 1, acc[(kt + 1) & 1]);
         const f32x4 z = *reinterpret_cast<const f32x4*>(&s_z[buf][16 * kt + 4 * c]);   // rows q0+16kt+4c+r; +inf beyond n
         const int qfirst = q0 + 16 * kt + 4 * c;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-          f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc, qf[kk], kf[rt][kk]);
-          // acc[r] <-> row qfirst + r, key (rt, i)
+          const f32x4& t = acc[kt & 1][rt];                    // t[r] <-> row qfirst + r, key (rt, i)
           if (full) {
-            v[rt] += (fast_exp2(fmaf(acc[0], a.sl2, -z[0])) + fast_exp2(fmaf(acc[1], a.sl2, -z[1]))) +
-                     (fast_exp2(fmaf(acc[2], a.sl2, -z[2])) + fast_exp2(fmaf(acc[3], a.sl2, -z[3])));
+            v[rt] += (fast_exp2(fmaf(t[0], a.sl2, -z[0])) + fast_exp2(fmaf(t[1], a.sl2, -z[1]))) +
+                     (fast_exp2(fmaf(t[2], a.sl2, -z[2])) + fast_exp2(fmaf(t[3], a.sl2, -z[3])));
           } else {
             float p[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-              p[r] = (qfirst + r >= kpos[rt]) ? fast_exp2(fmaf(acc[r], a.sl2, -z[r])) : 0.f;
+              p[r] = (qfirst + r >= kpos[rt]) ? fast_exp2(fmaf(t[r], a.sl2, -z[r])) : 0.f;
             v[rt] += (p[0] + p[1]) + (p[2] + p[3]);
           }
         }
