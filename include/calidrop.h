@@ -115,7 +115,7 @@ void calidrop_set_wide_selection(int enabled);
  *   SCORE     float, packed like K with D = 1: pooled score of prefix position j of KV head g
  *             of sequence b at [seq_offsets[b]*Hkv + g*n_b + j], j < n_b - w.
  * Returns CALIDROP_OK and fills offset/bytes, or CALIDROP_EINVAL.                            */
-typedef enum { CALIDROP_REGION_ROW_LSE = 0, CALIDROP_REGION_SCORE = 1 } calidrop_region;
+typedef enum { CALIDROP_REGION_ROW_LSE = 0, CALIDROP_REGION_SCORE = 1, CALIDROP_REGION_VOTE_PLANES = 2 } calidrop_region;
 int calidrop_compress_workspace_region(const calidrop_params* p, int64_t total_tokens,
                                        int32_t max_seq_len, int32_t region, size_t* offset,
                                        size_t* bytes);
@@ -294,7 +294,10 @@ size_t calidrop_compress_h2o_workspace_bytes(const calidrop_params* p, int32_t n
  *           (logits in log2 units), stride = bytes / (batch * Hq * 4) >= max_seq_len, +inf padded;
  *   SCORE   float, packed like K with D = 1: vote of position j of KV head g of sequence b at
  *           [seq_offsets[b]*Hkv + g*n_b + j], for the candidates j < n_b - n_local (needs
- *           calidrop_set_inspection(1) before the call unless the prompt is longer than 32768).  */
+ *           calidrop_set_inspection(1) before the call unless the prompt is longer than 32768);
+ *   VOTE_PLANES float [G][total_tokens*Hkv] (H2O only): plane hh holds, packed like SCORE and for
+ *           every position j < n_b, the probability mass position j received from the queries
+ *           of query head hh of its group; the score is the sum of the G planes.                  */
 int calidrop_compress_h2o_workspace_region(const calidrop_params* p, int32_t n_local,
                                            int64_t total_tokens, int32_t max_seq_len,
                                            int32_t region, size_t* offset, size_t* bytes);

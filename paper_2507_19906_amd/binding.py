@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("CALIDROP_LIB") or os.path.join(_PKG_DIR, "libcalidrop
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6
 BF16, FP32 = 0, 1
 FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE, FLAG_RECOMPUTED = 0, 1, 2, 3
-REGION_ROW_LSE, REGION_SCORE = 0, 1
+REGION_ROW_LSE, REGION_SCORE, REGION_VOTE_PLANES = 0, 1, 2
 
 
 class CalidropError(RuntimeError):

@@ -979,6 +979,9 @@ int calidrop_compress_h2o_workspace_region(const calidrop_params* p_in, int32_t 
   } else if (region == CALIDROP_REGION_SCORE) {
     *offset = L.score;
     *bytes = static_cast<size_t>(total_tokens) * p->n_kv_heads * sizeof(float);
+  } else if (region == CALIDROP_REGION_VOTE_PLANES) {
+    *offset = L.vote;
+    *bytes = static_cast<size_t>(total_tokens) * p->n_kv_heads * (p->n_q_heads / p->n_kv_heads) * sizeof(float);
   } else {
     return fail(CALIDROP_EINVAL, "unknown workspace region %d", region);
   }

@@ -59,3 +59,63 @@ def test_config4_batch64_varlen():
 def test_config5_long_context_131k():
     wl = synth.config(5, decode_steps=2)
     sampled(wl, [(0, 2)])
+
+
+def test_h2o_one_layer_32k_properties_and_samples():
+    # H2O strategy at the benchmark's shape (one 32k-context layer).  The oracle cannot follow a
+    # dense 32k x 32k pass, so: sampled rows of pass 1 and the last columns of pass 2 against the
+    # oracle, conservation of probability mass over all columns, and the selection checked
+    # against a brute-force ranking of the scores the GPU itself reports.
+    from oracle import calidrop_ref as ref
+    from paper_2507_19906_amd import binding as cd
+    wl = synth.config(3, layers=1, budget=512, decode_steps=1)
+    n, G, D, B = wl.seq_lens[0], wl.group, wl.head_dim, wl.budget
+    loc = B // 2
+    x = synth.make_inputs(wl, synth.BASE_SEED, device=DEV)
+    q_full = synth.full_queries(wl, x, synth.BASE_SEED, DEV)
+    bufs = cd.CompressBuffers(H.params_for(wl), wl.seq_lens, DEV)
+    cd.calidrop_set_inspection(True)
+    bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    lse = bufs.h2o_region(cd.REGION_ROW_LSE).view(wl.n_q_heads, -1).cpu().numpy().astype(np.float64)
+    planes = bufs.h2o_region(cd.REGION_VOTE_PLANES).view(G, wl.n_kv_heads, n).cpu().numpy().astype(np.float64)
+    score = bufs.h2o_region(cd.REGION_SCORE).view(wl.n_kv_heads, n).cpu().numpy()
+    scale = D ** -0.5
+    Q = synth.seq_view_q(q_full, wl, 0)
+    K = synth.seq_view(x["k"], wl, 0)
+    rng = np.random.default_rng(7)
+    # pass 1: row log-sum-exp (log2 units) of sampled rows
+    for h in (0, 13, 31):
+        Kg = H.to64(K[h // G])
+        for i in [0, 1, 127, 128, 4095, 20000, n - 1] + rng.integers(0, n, 5).tolist():
+            z = ref.logits(H.to64(Q[h, i]), Kg[:i + 1], scale)
+            want = (z.max() + np.log(np.exp(z - z.max()).sum())) * np.log2(np.e)
+            assert abs(lse[h, i] - want) < 2e-3, (h, i, lse[h, i], want)
+    # pass 2: the last 48 columns of one KV head (only the rows at or after them contribute)
+    g = 5
+    Kg = H.to64(K[g])
+    want = np.zeros(48)
+    for hh in range(G):
+        Qh = H.to64(Q[g * G + hh, n - 48:])
+        for r in range(48):
+            i = n - 48 + r
+            z = ref.logits(Qh[r], Kg[:i + 1], scale)
+            p = np.exp(z - z.max()); p /= p.sum()
+            want[:r + 1] += p[n - 48:i + 1]
+    got = planes[:, g, n - 48:].sum(axis=0)
+    assert np.abs(got - want).max() / want.max() < 5e-4
+    # conservation: every query row hands out probability 1
+    tot = planes.sum(axis=2)                                       # [G][Hkv]
+    assert np.abs(tot / n - 1.0).max() < 1e-4, tot / n
+    # the reported scores are the plane sums, and the retained set is their exact top-k
+    idx = bufs.indices[0].cpu().numpy()
+    for g in range(wl.n_kv_heads):
+        s = score[g, :n - loc]
+        ps = planes[0, g].astype(np.float32)
+        for hh in range(1, G):
+            ps = ps + planes[hh, g].astype(np.float32)
+        assert np.array_equal(s, ps[:n - loc])
+        order = np.lexsort((np.arange(n - loc), -s.astype(np.float64)))[:B - loc]
+        assert np.array_equal(idx[g, :B - loc], np.sort(order))
+        assert np.array_equal(idx[g, B - loc:], np.arange(n - loc, n))
+    assert torch.isfinite(bufs.c_out).all() and torch.isfinite(bufs.c_lse).all()
