@@ -247,3 +247,79 @@ def test_packing_a_streaming_llm_cache():
         for b in range(wl.batch):
             H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
     print(wl.name, rep, flush=True)
+
+
+def test_random_sweep_over_strategies_shapes_and_offload():
+    # seeded sweep: strategy (StreamingLLM / caller's lists / H2O), dtype, head shape, lengths,
+    # budget, then packing (device or page-locked host) and two decode + recomputation steps,
+    # every value against the oracle
+    from tests.test_gpu_h2o import check_h2o
+    rng = np.random.default_rng(20250719)
+    counts = {"slm": 0, "given": 0, "h2o": 0}
+    for case in range(14):
+        dtype = ["bf16", "fp32"][int(rng.integers(2))]
+        D = [64, 128][int(rng.integers(2))]
+        Hkv = int(rng.integers(1, 4))
+        G = [1, 2, 4, 8][int(rng.integers(4))]
+        w = [4, 8, 16][int(rng.integers(3))]
+        B = int(rng.integers(w + 6, 260))
+        lens = [int(rng.integers(40, 1300)) for _ in range(int(rng.integers(1, 4)))]
+        strat = ["slm", "given", "h2o"][case % 3]
+        wl = small(dtype, Hkv * G, Hkv, D, lens, w, B, 1, T=2, name=f"sweep{case}_{strat}_{dtype}_D{D}_G{G}")
+        print(wl.name, lens, "B", B, flush=True)
+        x = to_dev(synth.make_inputs(wl, 1000 + case))
+        p = H.params_for(wl)
+        bufs = cd.CompressBuffers(p, wl.seq_lens, DEV)
+        q_cal = x["q_win"][:, :, -1].contiguous()
+        rep = {}
+        if strat == "slm":
+            n_sink = int(rng.integers(0, B + 1))
+            bufs.streaming_indices(n_sink, x["seq_offsets"])
+            bufs.compress_given(q_cal, x["k"], x["v"], x["seq_offsets"])
+            torch.cuda.synchronize()
+            lists = [[ref.streaming_llm_retained(n, B, n_sink)] * Hkv if n > B else None for n in lens]
+            check_given(wl, x, bufs, q_cal, lists, rep)
+        elif strat == "given":
+            host = np.full((len(lens), Hkv, B), -1, np.int32)
+            lists = []
+            for b, n in enumerate(lens):
+                if n <= B:
+                    lists.append(None)
+                    continue
+                per = [np.sort(rng.choice(n, B, replace=False)) for _ in range(Hkv)]
+                lists.append(per)
+                host[b] = np.stack(per)
+            bufs.indices.copy_(torch.from_numpy(host))
+            bufs.compress_given(q_cal, x["k"], x["v"], x["seq_offsets"])
+            torch.cuda.synchronize()
+            check_given(wl, x, bufs, q_cal, lists, rep)
+        else:
+            n_local = int(rng.integers(1, B))
+            q_full = synth.full_queries(wl, x, 1000 + case, DEV)
+            cd.calidrop_set_inspection(True)
+            bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"], n_local=n_local)
+            torch.cuda.synchronize()
+            check_h2o(wl, x, q_full, bufs, n_local, rep)
+        counts[strat] += 1
+        store = cd.EvictedStore(bufs, wl.seq_lens, host=bool(rng.integers(2)))
+        store.pack(x["k"], x["v"], x["seq_offsets"])
+        torch.cuda.synchronize()
+        idx = bufs.indices.cpu().numpy()
+        ev = []
+        for b, n in enumerate(lens):
+            ev.append([np.setdiff1d(np.arange(n), idx[b, g][idx[b, g] >= 0]) for g in range(Hkv)] if n > B else None)
+        check_packed(wl, x, bufs, store, ev)
+        for t in range(wl.decode_steps):
+            q_t = x["q_dec"][t]
+            bufs.decode(q_t)
+            torch.cuda.synchronize()
+            for b in range(wl.batch):
+                H.check_decode_step(wl, bufs, q_t, b, report=rep)
+            before = H.snapshot_state(bufs)
+            bufs.flags.fill_(cd.FLAG_RECOMPUTE)                  # exercise the branch on every head
+            before["flags"][:] = cd.FLAG_RECOMPUTE
+            store.recalibrate(q_t)
+            torch.cuda.synchronize()
+            for b in range(wl.batch):
+                H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
+    assert min(counts.values()) >= 4
