@@ -38,6 +38,18 @@ __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<
 __device__ __forceinline__ void st16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
 __device__ __forceinline__ u32x4 zero16() { return u32x4{0u, 0u, 0u, 0u}; }
 
+// LDS-direct loads: each lane reads `bytes` from its own global address and the load unit stores
+// the wave's 64 pieces contiguously (lane order) at the wave-uniform LDS address `lds`.  Tracked
+// by vmcnt like any global load.
+__device__ __forceinline__ void load_to_lds16(const void* g, void* lds) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
+}
+__device__ __forceinline__ void load_to_lds4(const void* g, void* lds) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)lds, 4, 0, 0);
+}
+
 // Reinterpret a 32-bit lane value (always pass vector elements through this by-value helper:
 // bit-casting a vector element expression directly reads element 0 with this compiler).
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }

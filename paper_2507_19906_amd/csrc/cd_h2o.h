@@ -75,11 +75,9 @@ __global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
 
   const int key_end = min(n, i0 + BR);           // no row of the block sees a key beyond its last row
   const int nstages = (key_end + SK - 1) / SK;
-  typename KS::Regs r0, r1;
-  KS::load(r0, kbase, 0, n);
-  if (nstages > 1) KS::load(r1, kbase, SK, n);
-  KS::store(r0, s_k[0]);
-  __syncthreads();
+  KeyStreamDirect<T, D> ks;
+  ks.init();
+  ks.issue(kbase, 0, n, s_k[0]);
 
   // S^T tile kt of a stage: keys 16 kt .. 16 kt + 15 against this wave's rows
   auto mma_tile = [&](const char* lds, int kt, f32x4 (&acc)[RT]) {
@@ -146,16 +144,14 @@ __global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
     }
   };
 
-  for (int s = 0; s < nstages; s += 2) {
-    if (s + 2 < nstages) KS::load(r0, kbase, (s + 2) * SK, n);
-    compute(s_k[0], s * SK);
-    if (s + 1 < nstages) KS::store(r1, s_k[1]);
+  // stage s is computed from buffer s & 1 while the loads of stage s + 1 fill the other one; the
+  // barrier both publishes stage s and says that everyone is done reading the buffer about to be
+  // refilled
+  for (int s = 0; s < nstages; ++s) {
+    ks.wait_all();
     __syncthreads();
-    if (s + 1 >= nstages) break;
-    if (s + 3 < nstages) KS::load(r1, kbase, (s + 3) * SK, n);
-    compute(s_k[1], (s + 1) * SK);
-    if (s + 2 < nstages) KS::store(r0, s_k[0]);
-    __syncthreads();
+    if (s + 1 < nstages) ks.issue(kbase, (s + 1) * SK, n, s_k[(s + 1) & 1]);
+    compute(s_k[s & 1], s * SK);
   }
 
   // merge the four lanes that hold the same row (different keys); padding rows get +inf so that
@@ -195,7 +191,9 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
   float* vote = a.vote + static_cast<int64_t>(hh) * a.total_tokens * a.Hkv + head_tok;
 
   __shared__ __attribute__((aligned(16))) char s_q[2][KS::kStageBytes];
-  __shared__ __attribute__((aligned(16))) float s_z[2][SK];      // row log-sum-exp of the staged rows
+  __shared__ __attribute__((aligned(16))) float s_z[2][64];      // row log-sum-exp of the staged rows
+  KeyStreamDirect<T, D> ks;
+  ks.init();
 
   for (int job = 0; job < 2; ++job) {
     const int blk = job == 0 ? static_cast<int>(blockIdx.x) : nblk - 1 - static_cast<int>(blockIdx.x);
@@ -220,21 +218,13 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
 
     // streamed rows: j0 .. n-1 of this query head, SK per stage, with their log-sum-exp
     const int nstages = (n - j0 + SK - 1) / SK;
-    typename KS::Regs r0, r1;
-    f32x4 z0, z1;
-    auto issue = [&](typename KS::Regs& r, f32x4& z, int s) {
-      KS::load(r, qbase, j0 + s * SK, n);
-      if (threadIdx.x < SK / 4) z = *reinterpret_cast<const f32x4*>(lse_row + j0 + s * SK + 4 * threadIdx.x);
-    };
-    auto stash = [&](const typename KS::Regs& r, const f32x4& z, int buf) {
-      KS::store(r, s_q[buf]);
-      if (threadIdx.x < SK / 4) *reinterpret_cast<f32x4*>(&s_z[buf][4 * threadIdx.x]) = z;
+    auto issue = [&](int s) {                      // rows and their log-sum-exp, straight into LDS
+      const int q0 = j0 + s * SK;
+      ks.issue(qbase, q0, n, s_q[s & 1]);
+      if (threadIdx.x < SK) load_to_lds4(lse_row + q0 + threadIdx.x, &s_z[s & 1][0]);
     };
     __syncthreads();                               // the previous job is done with the buffers
-    issue(r0, z0, 0);
-    if (nstages > 1) issue(r1, z1, 1);
-    stash(r0, z0, 0);
-    __syncthreads();
+    issue(0);
 
     // S^T tile kt of a stage: rows 16 kt .. 16 kt + 15 of the stage against this wave's keys
     auto mma_tile = [&](const char* lds, int kt, f32x4 (&acc)[RT]) {
@@ -278,16 +268,11 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
       }
     };
 
-    for (int s = 0; s < nstages; s += 2) {
-      if (s + 2 < nstages) issue(r0, z0, s + 2);
-      compute(0, s);
-      if (s + 1 < nstages) stash(r1, z1, 1);
+    for (int s = 0; s < nstages; ++s) {
+      ks.wait_all();
       __syncthreads();
-      if (s + 1 >= nstages) break;
-      if (s + 3 < nstages) issue(r1, z1, s + 3);
-      compute(1, s + 1);
-      if (s + 2 < nstages) stash(r0, z0, 0);
-      __syncthreads();
+      if (s + 1 < nstages) issue(s + 1);
+      compute(s & 1, s);
     }
 
 #pragma unroll

@@ -103,6 +103,47 @@ struct KeyStream {
   }
 };
 
+// The same stage layout filled by LDS-direct loads: every lane fetches the 16-byte chunk that
+// belongs in "its" LDS slot (slot = threadIdx.x + 256 u, in the swizzled order above) and the
+// load unit writes it there, so the stage needs no staging registers and no LDS store
+// instructions.  A wave instruction fills 1 KiB of contiguous LDS; the caller waits for its
+// own loads (vmcnt) before the workgroup barrier that publishes the stage.
+template <typename T, int D>
+struct KeyStreamDirect {
+  using KS = KeyStream<T, D>;
+  static constexpr int CH = KS::CH, NLD = KS::NLD, kStageKeys = KS::kStageKeys;
+  int goff[NLD];         // byte offset, inside an in-range stage, of the chunk for slot threadIdx.x + 256 u
+  int lkey[NLD], lch[NLD];   // the slot's stage-local key and its global chunk index (for the clamped tail)
+
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) {
+      const int slot = threadIdx.x + u * 256;
+      const int key = slot / CH, chp = slot % CH;
+      lkey[u] = key;
+      lch[u] = chp ^ KS::swz(key);
+      goff[u] = key * (CH * 16) + lch[u] * 16;
+    }
+  }
+  __device__ __forceinline__ void issue(const T* kbase, int key0, int n, char* lds) const {
+    const char* base = reinterpret_cast<const char*>(kbase);
+    char* dst = lds + (threadIdx.x >> 6) * 1024;           // wave-uniform
+    if (key0 + kStageKeys <= n) {
+      const char* sbase = base + static_cast<int64_t>(key0) * (CH * 16);
+#pragma unroll
+      for (int u = 0; u < NLD; ++u) load_to_lds16(sbase + goff[u], dst + u * 4096);
+    } else {
+#pragma unroll
+      for (int u = 0; u < NLD; ++u) {
+        const int key = min(key0 + lkey[u], n - 1);          // the tail repeats the last row
+        load_to_lds16(base + static_cast<int64_t>(key) * (CH * 16) + lch[u] * 16, dst + u * 4096);
+      }
+    }
+  }
+  // all LDS-direct loads this wave has issued have landed
+  __device__ __forceinline__ static void wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+};
+
 // Query fragments of the 32 rows a wave owns: lane (i, c) holds row 16 rt + i of the wave.
 template <typename T, int D>
 struct WaveQueries {
