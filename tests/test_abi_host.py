@@ -191,3 +191,32 @@ def test_offload_entry_points_validate_on_the_host():
     assert L.calidrop_recalibrate_packed(ctypes.byref(p), *bad, A, needr, None) == cd.ESHAPE
     bad = list(args); bad[1] = A + 2
     assert L.calidrop_recalibrate_packed(ctypes.byref(p), *bad, A, needr, None) == cd.EALIGN
+
+
+def test_h2o_entry_point_validates_on_the_host():
+    A = 4096
+    L = cd.lib()
+    p = good()
+    need = cd.calidrop_compress_h2o_workspace_bytes(p, 0, 16384, 8192)
+    assert need > 0 and need % 256 == 0
+    assert cd.calidrop_compress_h2o_workspace_bytes(p, 100, 16384, 8192) > 0
+    for bad_local in (-1, 512, 4000):
+        with pytest.raises(cd.CalidropError):
+            cd.calidrop_compress_h2o_workspace_bytes(p, bad_local, 16384, 8192)
+    assert "n_local" in cd.calidrop_last_error()
+    args = [A, A, A, A, 16384, 8192, A, A, A, A, A, None, A, A, A]
+    assert L.calidrop_compress_h2o(ctypes.byref(p), 0, *args, A, need - 1, None) == cd.EWORKSPACE
+    assert L.calidrop_compress_h2o(ctypes.byref(p), 512, *args, A, need, None) == cd.EINVAL
+    bad = list(args); bad[0] = None
+    assert L.calidrop_compress_h2o(ctypes.byref(p), 0, *bad, A, need, None) == cd.EINVAL
+    assert "q_full is NULL" in cd.calidrop_last_error()
+    bad = list(args); bad[2] = A + 8
+    assert L.calidrop_compress_h2o(ctypes.byref(p), 0, *bad, A, need, None) == cd.EALIGN
+    assert L.calidrop_compress_h2o(ctypes.byref(good(calib_size=16)), 0, *args, A, need, None) == cd.EINVAL   # cal_indices missing
+    assert L.calidrop_compress_h2o(ctypes.byref(good(batch=4096)), 0, A, A, A, A, 4096 * 8192, 8192, A, A, A, A, A, None,
+                                   A, A, A, A, 1 << 44, None) == cd.EUNSUPPORTED              # batch * Hq > 65535
+    off, nbytes = cd.calidrop_compress_h2o_workspace_region(p, 0, 16384, 8192, cd.REGION_VOTE_PLANES)
+    assert nbytes == 16384 * 8 * 4 * 4 and off % 256 == 0 and off + nbytes <= need
+    off, nbytes = cd.calidrop_compress_h2o_workspace_region(p, 0, 16384, 8192, cd.REGION_ROW_LSE)
+    assert nbytes == 2 * 32 * 8192 * 4
+    cd.calidrop_set_wide_selection(True); cd.calidrop_set_wide_selection(False)
