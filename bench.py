@@ -84,6 +84,51 @@ def cpu_baseline(wl, x, kv_heads: int, decode_steps: int):
     }
 
 
+def machine_probes(dev, stream):
+    """What a plain streaming read and a dense bf16 matrix-core loop reach on this GPU (the probes of
+    libcalidrop_probes.so), for reading the roofline fractions against measured ceilings."""
+    import ctypes
+    import torch
+    import paper_2507_19906_amd
+    path = os.path.join(os.path.dirname(os.path.abspath(paper_2507_19906_amd.__file__)), "libcalidrop_probes.so")
+    L = ctypes.CDLL(path)
+    L.calidrop_probe_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    L.calidrop_probe_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    st = stream.cuda_stream or None
+    buf = torch.ones(2 << 30, dtype=torch.uint8, device=dev)
+    out = torch.zeros(1 << 21, dtype=torch.float32, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    res = {}
+    for label, nbytes, blocks, reps in (("64MiB", 64 << 20, 2048, 32), ("256MiB", 256 << 20, 8192, 16), ("2GiB", 2 << 30, 32768, 6)):
+        nrot = (2 << 30) // nbytes                 # rotate through the buffer: never re-read cached data
+        def launch(r):
+            rc = L.calidrop_probe_stream_read(buf.data_ptr() + (r % nrot) * nbytes, nbytes, blocks, out.data_ptr(), st)
+            assert rc == 0
+        for r in range(3):
+            launch(r)
+        e0, e1 = ev(), ev()
+        e0.record(stream)
+        for r in range(reps):
+            launch(r + 3)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        res["stream_read_" + label] = {"us_per_launch": us, "GBps": nbytes / us / 1e3}
+    blocks, iters = 2048, 20000
+    for _ in range(2):
+        assert L.calidrop_probe_mfma_loop(out.data_ptr(), blocks, 2000, st) == 0
+    e0, e1 = ev(), ev()
+    e0.record(stream)
+    assert L.calidrop_probe_mfma_loop(out.data_ptr(), blocks, iters, st) == 0
+    e1.record(stream)
+    torch.cuda.synchronize()
+    flop = blocks * 4 * iters * 8 * 16384.0
+    ms = e0.elapsed_time(e1)
+    res["mfma_bf16_loop"] = {"ms": ms, "TFLOPps": flop / ms / 1e9, "pct_published_peak": 100.0 * flop / ms / 1e9 / 2500.0}
+    del buf, out
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -312,6 +357,8 @@ def main():
                "pct_bf16_mfma_peak": 100.0 * flop / ms / 1e9 / 2500.0}
         del b4, qf
 
+    probes = machine_probes(dev, stream) if not args.no_extra else None
+
     gbps = dbytes / (dec * 1e-3) / 1e9
     # window scoring (the two MFMA passes of compress): 2*Hq*w*n*D flop per layer and pass
     score_flop = 2.0 * wl.n_q_heads * wl.window * wl.seq_lens[0] * wl.head_dim * wl.batch
@@ -339,6 +386,7 @@ def main():
         "recalibrate_all_heads_GBps": None if recal_us is None else compress_bytes(wl) / recal_us / 1e3,
         "recalibrate_all_heads_from_packed_evicted": packed,
         "compress_h2o_strategy": h2o,
+        "machine_probes": probes,
         "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel<bf16,128,8>",
                      "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
                      # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of this kernel on this workload,

@@ -1,0 +1,31 @@
+/*
+ * calidrop_probes.h - machine probes used by the benchmark (libcalidrop_probes.so).
+ *
+ * Not part of the CaliDrop path: two plain kernels that show what the GPU at hand reaches on a
+ * streaming read and on a dense bf16 matrix-core loop, so that roofline fractions can be quoted
+ * against measured ceilings next to the published peaks.  Device pointers, caller-owned; the
+ * calls enqueue one kernel on `stream` (a hipStream_t, NULL = default) and return 0, or -1 on
+ * bad arguments or a failed launch.  The caller times them (events on the same stream).
+ */
+#ifndef CALIDROP_PROBES_H
+#define CALIDROP_PROBES_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Reads `bytes` bytes at `buf` once (16 bytes per lane, `blocks` workgroups of 256 threads, each
+ * on its own contiguous slice).  bytes must be a multiple of 16 * blocks; `out`: blocks uint32. */
+int calidrop_probe_stream_read(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream);
+
+/* `blocks` workgroups of 4 waves; every wave executes iters * 8 independent-chain
+ * v_mfma_f32_16x16x32_bf16 instructions (16384 flop each) and nothing else.  `out`: blocks * 256
+ * floats.  Total flop = blocks * 4 * iters * 8 * 16384. */
+int calidrop_probe_mfma_loop(void* out, int32_t blocks, int32_t iters, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CALIDROP_PROBES_H */

@@ -28,10 +28,11 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found: the CaliDrop kernels need the ROCm toolchain")
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compile csrc/calidrop.hip into libcalidrop.so next to this file; returns its path."""
-    src = os.path.join(CSRC, "calidrop.hip")
-    tmp = LIB_PATH + ".tmp"
+PROBES_PATH = os.path.join(PKG_DIR, "libcalidrop_probes.so")
+
+
+def _compile(src: str, out: str, verbose: bool, extra_flags=()) -> str:
+    tmp = out + ".tmp"
     cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, src, "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -42,8 +43,15 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    os.replace(tmp, LIB_PATH)
-    return LIB_PATH
+    os.replace(tmp, out)
+    return out
+
+
+def build(verbose: bool = False, extra_flags=()) -> str:
+    """Compile csrc/calidrop.hip into libcalidrop.so next to this file (and the machine probes the
+    benchmark uses into libcalidrop_probes.so); returns the library's path."""
+    _compile(os.path.join(CSRC, "probes.hip"), PROBES_PATH, verbose)
+    return _compile(os.path.join(CSRC, "calidrop.hip"), LIB_PATH, verbose, extra_flags)
 
 
 if __name__ == "__main__":

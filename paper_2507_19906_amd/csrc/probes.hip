@@ -1,0 +1,68 @@
+// Machine probes behind the roofline fractions the benchmark reports: what a plain streaming
+// read and a dense matrix-core loop reach on the GPU at hand.  Measurement support only - no part
+// of the CaliDrop path uses this file.  C ABI, device pointers, caller times the launches with
+// events on `stream`.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+// Every workgroup reads its own contiguous slice, 16 bytes per lane, 8 loads in flight per lane.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ p, uint64_t vec_per_block, uint32_t* out) {
+  const u32x4* q = p + static_cast<uint64_t>(blockIdx.x) * vec_per_block;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (uint64_t i = threadIdx.x; i < vec_per_block; i += 256 * 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (i + u * 256 < vec_per_block) ? q[i + u * 256] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) out[blockIdx.x] = 1u;   // keeps the loads alive
+}
+
+// Each wave runs `iters` rounds of 8 independent accumulate chains of the bf16 16x16x32 matrix
+// instruction: 8 * 16384 flop per round and wave, nothing else in the loop.
+__global__ __launch_bounds__(256) void mfma_loop_kernel(float* out, int iters) {
+  const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});   // 1.0
+  const bf16x8 b = __builtin_bit_cast(bf16x8, u32x4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u});   // 2^-7
+  f32x4 acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  f32x4 s = acc[0];
+#pragma unroll
+  for (int j = 1; j < 8; ++j) s += acc[j];
+  out[static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x] = s[0] + s[1] + s[2] + s[3];
+}
+
+}  // namespace
+
+extern "C" {
+
+// Reads `bytes` (a multiple of 16 * blocks) starting at `buf` with `blocks` workgroups.  `out`
+// needs `blocks` uint32.  Returns 0, or -1 on bad arguments / launch failure.
+int calidrop_probe_stream_read(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream) {
+  if (!buf || !out || blocks < 1 || bytes == 0 || bytes % (16ull * blocks) != 0) return -1;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4*>(buf), bytes / 16 / blocks, static_cast<uint32_t*>(out));
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Launches `blocks` workgroups of 4 waves, each wave doing iters * 8 matrix instructions
+// (16384 flop each).  `out` needs blocks * 256 floats.
+int calidrop_probe_mfma_loop(void* out, int32_t blocks, int32_t iters, void* stream) {
+  if (!out || blocks < 1 || iters < 1) return -1;
+  hipLaunchKernelGGL(mfma_loop_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<float*>(out), iters);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+}  // extern "C"

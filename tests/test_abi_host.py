@@ -220,3 +220,18 @@ def test_h2o_entry_point_validates_on_the_host():
     off, nbytes = cd.calidrop_compress_h2o_workspace_region(p, 0, 16384, 8192, cd.REGION_ROW_LSE)
     assert nbytes == 2 * 32 * 8192 * 4
     cd.calidrop_set_wide_selection(True); cd.calidrop_set_wide_selection(False)
+
+
+def test_probe_library_exports_its_header():
+    hdr = open(os.path.join(ROOT, "include", "calidrop_probes.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(calidrop_probe_[a-z_]+)\s*\(", hdr))
+    assert names == {"calidrop_probe_stream_read", "calidrop_probe_mfma_loop"}
+    L = ctypes.CDLL(os.path.join(ROOT, "paper_2507_19906_amd", "libcalidrop_probes.so"))
+    for n in names:
+        assert hasattr(L, n), n
+    L.calidrop_probe_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    assert L.calidrop_probe_stream_read(None, 1 << 20, 64, 4096, None) == -1          # validation before any launch
+    assert L.calidrop_probe_stream_read(4096, (1 << 20) + 16, 64, 4096, None) == -1
+    L.calidrop_probe_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    assert L.calidrop_probe_mfma_loop(None, 8, 8, None) == -1
