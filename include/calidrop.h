@@ -28,8 +28,8 @@
  *     may already be queued).  calidrop_last_error() describes the last failure on this
  *     thread.
  *   - Base pointers must be 16-byte aligned (CALIDROP_EALIGN otherwise).
- *   - head_dim must be 64 or 128, n_q_heads / n_kv_heads an integer G with 1 <= G <= 16
- *     (CALIDROP_EUNSUPPORTED otherwise).
+ *   - head_dim must be 64 or 128, n_q_heads / n_kv_heads an integer G with 1 <= G <= 16,
+ *     budget <= 2^24 (CALIDROP_EUNSUPPORTED otherwise).
  *   - Accumulation is always fp32; `dtype` is the storage type of Q/K/V, the compressed cache
  *     and the decode output.  The calibration state is always fp32.
  *   - Logits are scaled by 1/sqrt(head_dim) (Eq. 2) unless `scale` is non-zero.

@@ -65,6 +65,8 @@ int check_params(const calidrop_params* p) {
   if (p->budget <= p->window)
     return fail(CALIDROP_EINVAL, "budget %d must exceed window %d (the window counts toward the budget)", p->budget,
                 p->window);
+  if (p->budget > (1 << 24))
+    return fail(CALIDROP_EUNSUPPORTED, "budget %d exceeds %d", p->budget, 1 << 24);
   if (p->pool_kernel < 1 || p->pool_kernel % 2 == 0)
     return fail(CALIDROP_EINVAL, "pool_kernel must be odd and >= 1 (got %d)", p->pool_kernel);
   if (!(p->scale >= 0.f) || std::isinf(p->scale))

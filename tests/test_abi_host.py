@@ -58,6 +58,7 @@ def test_workspace_sizes():
     (dict(scale=-1.0), cd.EINVAL),
     (dict(batch=0), cd.EINVAL),
     (dict(dtype=7), cd.EUNSUPPORTED),
+    (dict(budget=(1 << 24) + 1), cd.EUNSUPPORTED),
 ])
 def test_bad_params_rejected(kw, status):
     p = good(**kw)
