@@ -26,6 +26,30 @@ def test_oracle_reproduces_golden_fixture():
     assert flags.tolist() == g["flags"]
 
 
+def test_oracle_reproduces_strategy_fixture():
+    g = json.load(open(os.path.join(HERE, "golden", "tiny_strategies.json")))
+    s = g["shapes"]
+    qf, K, V, q_t = (np.array(g[k]) for k in ("q_full", "K", "V", "q_t"))
+    slm = ref.streaming_llm_retained(s["n"], s["B"], s["n_sink"])
+    assert slm.tolist() == g["slm_idx"]
+    rs = ref.compress_given(qf[:, -1], K, V, s["B"], [slm, slm])
+    np.testing.assert_allclose(rs["c_out"], np.array(g["slm_c_out"]), atol=1e-13)
+    np.testing.assert_allclose(rs["c_lse"], np.array(g["slm_c_lse"]), atol=1e-13)
+    rh = ref.compress_h2o(qf, K, V, s["B"], s["n_local"])
+    np.testing.assert_allclose(np.array(rh["vote"]), np.array(g["h2o_vote"]), rtol=1e-13)
+    assert rh["idx"].tolist() == g["h2o_idx"]
+    np.testing.assert_allclose(rh["c_out"], np.array(g["h2o_c_out"]), atol=1e-13)
+    np.testing.assert_allclose(rh["c_lse"], np.array(g["h2o_c_lse"]), atol=1e-13)
+    out, a_lse, flags, _ = ref.decode(q_t, rh["K_c"], rh["V_c"], s["B"], rh["c_q"], rh["c_out"], rh["c_lse"], 0.7, 0.85)
+    assert flags.tolist() == g["flags"] and set(g["flags"]) == {ref.FLAG_RECOMPUTE}
+    out2, flags2, _, c_out2, c_lse2 = ref.recalibrate(q_t, K, V, rh["idx"], flags, a_lse, out, rh["c_q"], rh["c_out"],
+                                                      rh["c_lse"])
+    np.testing.assert_allclose(out2, np.array(g["recal_out"]), atol=1e-13)
+    np.testing.assert_allclose(c_out2, np.array(g["recal_c_out"]), atol=1e-13)
+    np.testing.assert_allclose(c_lse2, np.array(g["recal_c_lse"]), atol=1e-13)
+    assert flags2.tolist() == g["recal_flags"]
+
+
 def fake_oracle(score, k_sel, w):
     P = len(score)
     sel, margin = ref.select_top(score, k_sel)
