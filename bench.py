@@ -159,8 +159,8 @@ def main():
     from paper_2507_19906_amd import binding as cd
     from paper_2507_19906_amd import synth
 
-    if not os.path.exists(cd.LIB_PATH):
-        from paper_2507_19906_amd import build as _build
+    from paper_2507_19906_amd import build as _build
+    if not (os.path.exists(cd.LIB_PATH) and os.path.exists(_build.PROBES_PATH)):
         _build.build()
     assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU path)"
     dev = torch.device("cuda:0")

@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the in-tree libraries; compile them only when nothing has been built yet
+    from paper_2507_19906_amd import build as _build
+    if not (os.path.exists(_build.LIB_PATH) and os.path.exists(_build.PROBES_PATH)):
+        _build.build()
 
 
 @pytest.fixture(scope="session")
