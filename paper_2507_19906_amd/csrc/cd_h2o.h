@@ -92,28 +92,37 @@ __global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
     }
   };
   // acc[rt][r] <-> key kfirst + r, row (rt, i)
-  auto softmax_tile = [&](const f32x4 (&acc)[RT], int kfirst, bool full) {
+  auto softmax_tile = [&](const f32x4 (&acc)[RT], int kfirst, bool full, bool first) {
     if (full) {
-      float tm[RT];
-      bool grow = false;
+      // The sum is taken against a reference m that need not be the row maximum: m + log2(sum of
+      // exp2(s - m)) is the same number for any m that keeps the terms in range.  The reference is
+      // the logit of key 0 (every row sees it); only when a sum outgrows 2^64 is the tile redone
+      // against its true maximum.  This saves the running-maximum arithmetic on every tile.
+      if (first) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) m[rt] = __shfl(acc[rt][0] * a.sl2, i);     // lane (i, c = 0), r = 0: key 0
+      }
+      float l_old[RT];
+      bool big = false;
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        tm[rt] = max3(max3(acc[rt][0], acc[rt][1], acc[rt][2]), acc[rt][3], acc[rt][3]) * a.sl2;
-        grow |= tm[rt] > m[rt];
-      }
-      if (__any(grow)) {               // some row's running maximum rises: rescale its sum
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          const float mn = fmaxf(m[rt], tm[rt]);
-          l[rt] *= fast_exp2(m[rt] - mn);
-          m[rt] = mn;
-        }
-      }
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
+        l_old[rt] = l[rt];
         const float nm = -m[rt];
         l[rt] += (fast_exp2(fmaf(acc[rt][0], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][1], a.sl2, nm))) +
                  (fast_exp2(fmaf(acc[rt][2], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][3], a.sl2, nm)));
+        big |= !(l[rt] <= 0x1p+64f);
+      }
+      if (__any(big)) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          const float tm = fmaxf(fmaxf(acc[rt][0], acc[rt][1]), fmaxf(acc[rt][2], acc[rt][3])) * a.sl2;
+          const float mn = fmaxf(m[rt], tm);
+          const float nm = -mn;
+          l[rt] = l_old[rt] * fast_exp2(m[rt] - mn) +
+                  ((fast_exp2(fmaf(acc[rt][0], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][1], a.sl2, nm))) +
+                   (fast_exp2(fmaf(acc[rt][2], a.sl2, nm)) + fast_exp2(fmaf(acc[rt][3], a.sl2, nm))));
+          m[rt] = mn;
+        }
       }
     } else {
 #pragma unroll
@@ -140,7 +149,7 @@ __global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
       if (kt + 1 < KT) mma_tile(lds, kt + 1, acc[(kt + 1) & 1]);
-      softmax_tile(acc[kt & 1], key0 + 16 * kt + 4 * c, full);
+      softmax_tile(acc[kt & 1], key0 + 16 * kt + 4 * c, full, key0 == 0 && kt == 0);
     }
   };
 

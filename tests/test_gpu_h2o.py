@@ -162,3 +162,27 @@ def test_h2o_with_multi_workgroup_selection(wide_selection):
         ev = ev[ev < n - B // 2]
         order = np.argsort(-orc["vote"][g][ev], kind="stable")[:700]
         assert np.array_equal(cal[g], np.sort(ev[order]))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_h2o_rows_whose_logits_outgrow_the_reference(dtype):
+    # pass 1 sums exp2(s - m) against the logit of key 0 and only falls back to the true row maximum
+    # when a sum outgrows 2^64: a tiny key 0 and a few huge later keys force that fallback (and
+    # fp32 overflow of the first attempt) on many rows
+    wl = small(dtype, 4, 2, 128, [900], 16, 64, 1, T=1, name=f"h2o_huge_logits_{dtype}")
+    x = synth.make_inputs(wl, 64)
+    K = synth.seq_view(x["k"], wl, 0)
+    K[:, 0] *= 0.01
+    K[:, 300] *= 10.0
+    K[:, 640] *= 25.0
+    x = to_dev(x)
+    q_full = synth.full_queries(wl, x, 64, DEV)
+    bufs = cd.CompressBuffers(H.params_for(wl), wl.seq_lens, DEV)
+    cd.calidrop_set_inspection(True)
+    bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    rep = {}
+    check_h2o(wl, x, q_full, bufs, 0, rep)
+    lse = bufs.h2o_region(cd.REGION_ROW_LSE).view(wl.n_q_heads, -1)[:, :900]
+    assert torch.isfinite(lse).all() and float(lse.max()) > 150.0       # log2 units: far beyond 64 above key 0
+    print(wl.name, rep, float(lse.max()), flush=True)
