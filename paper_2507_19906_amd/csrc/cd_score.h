@@ -226,28 +226,19 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
     }
     // acc[kt][rt][r] <-> key key0 + 16 kt + 4 c + r, row (rt, i)
     if (key0 + SK <= P) {
-      // every key of the stage is a prefix key: visible to all rows, no masking
-      float tm[2];
-      bool grow = false;
+      // every key of the stage is a prefix key: visible to all rows, no masking.  The sum is taken
+      // against a reference m that need not be the maximum (m + log2 sum exp2(s - m) is the same
+      // number for any m that keeps the terms in range): the logit of the chunk's first key.
+      // Only when a sum outgrows 2^64 is the stage redone against its true maximum.
+      if (key0 == key_base) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) m[rt] = __shfl(acc[0][rt][0] * a.sl2, i);     // lane (i, c = 0), r = 0: first key
+      }
+      float l_old[2];
+      bool big = false;
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt) {
-        float t = -INFINITY;
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt)
-          t = fmaxf(t, fmaxf(fmaxf(acc[kt][rt][0], acc[kt][rt][1]), fmaxf(acc[kt][rt][2], acc[kt][rt][3])));
-        tm[rt] = t * a.sl2;
-        grow |= tm[rt] > m[rt];
-      }
-      if (__any(grow)) {                 // some row's running maximum rises: rescale its sum
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
-          const float mn = fmaxf(m[rt], tm[rt]);
-          l[rt] *= fast_exp2(m[rt] - mn);            // m = -inf only while l = 0: exp2(-inf) = 0
-          m[rt] = mn;
-        }
-      }
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) {
+        l_old[rt] = l[rt];
         const float nm = -m[rt];
         float s = 0.f;
 #pragma unroll
@@ -255,6 +246,25 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
           s += (fast_exp2(fmaf(acc[kt][rt][0], a.sl2, nm)) + fast_exp2(fmaf(acc[kt][rt][1], a.sl2, nm))) +
                (fast_exp2(fmaf(acc[kt][rt][2], a.sl2, nm)) + fast_exp2(fmaf(acc[kt][rt][3], a.sl2, nm)));
         l[rt] += s;
+        big |= !(l[rt] <= 0x1p+64f);
+      }
+      if (__any(big)) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+          float t = -INFINITY;
+#pragma unroll
+          for (int kt = 0; kt < KT; ++kt)
+            t = fmaxf(t, fmaxf(fmaxf(acc[kt][rt][0], acc[kt][rt][1]), fmaxf(acc[kt][rt][2], acc[kt][rt][3])));
+          const float mn = fmaxf(m[rt], t * a.sl2);
+          const float nm = -mn;
+          float s = 0.f;
+#pragma unroll
+          for (int kt = 0; kt < KT; ++kt)
+            s += (fast_exp2(fmaf(acc[kt][rt][0], a.sl2, nm)) + fast_exp2(fmaf(acc[kt][rt][1], a.sl2, nm))) +
+                 (fast_exp2(fmaf(acc[kt][rt][2], a.sl2, nm)) + fast_exp2(fmaf(acc[kt][rt][3], a.sl2, nm)));
+          l[rt] = l_old[rt] * fast_exp2(m[rt] - mn) + s;
+          m[rt] = mn;
+        }
       }
     } else {
       // stage reaches into the window: causal mask per row, and the end of the sequence
