@@ -435,3 +435,29 @@ def test_multi_workgroup_selection_on_short_prompts(wl, wide_selection):
 def test_exact_ties_with_multi_workgroup_selection(wide_selection):
     test_exact_ties_lower_index_wins(16 * 40 + 16, 1, 40, 50)
     test_exact_ties_lower_index_wins(20016, 1, 3000, 2500)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_window_scoring_with_logits_far_above_the_reference(dtype):
+    # pass 1 sums against the first logit of each key chunk and redoes a stage against its true
+    # maximum only when a sum outgrows 2^64: tiny first keys and a few huge later keys force that
+    # path (including fp32 overflow of the first attempt)
+    wl = small(dtype, 8, 2, 128, [3000], 16, 128, 5, T=2, name=f"huge_logits_{dtype}")
+    x = synth.make_inputs(wl, 77)
+    K = synth.seq_view(x["k"], wl, 0)
+    K[:, 0] *= 0.01
+    K[:, 256] *= 0.01
+    K[:, 300] *= 12.0
+    K[:, 1500] *= 30.0
+    x = to_dev(x)
+    bufs = H.gpu_compress(wl, x)
+    rep = {}
+    H.check_compress(wl, x, bufs, 0, report=rep)
+    lse = bufs.region(cd.REGION_ROW_LSE)[:2 * 128].cpu().numpy()
+    assert np.isfinite(lse[lse < 1e30]).all() and lse[lse < 1e30].max() > 150.0        # log2 units
+    for t in range(wl.decode_steps):
+        bufs.decode(x["q_dec"][t])
+        torch.cuda.synchronize()
+        H.check_decode_step(wl, bufs, x["q_dec"][t], 0, report=rep)
+    rep.pop("flags")
+    print(wl.name, rep, flush=True)
