@@ -461,3 +461,43 @@ def test_window_scoring_with_logits_far_above_the_reference(dtype):
         H.check_decode_step(wl, bufs, x["q_dec"][t], 0, report=rep)
     rep.pop("flags")
     print(wl.name, rep, flush=True)
+
+
+@pytest.mark.parametrize("n", [1200, 20000])
+def test_whole_step_under_hip_graph_replay(n):
+    # compress, decode and the recomputation branch allocate nothing, synchronise nothing and
+    # record no memset, so the whole per-layer step can live in one captured graph; every
+    # replay on fresh inputs must reproduce the eager results (n = 20000 needs more than 48 KiB
+    # of dynamic LDS in the selection kernel)
+    wl = small("bf16", 8, 2, 128, [n, 700], 16, 128, 5, T=2, name=f"graph_step_{n}")
+    xs = [to_dev(synth.make_inputs(wl, 500 + j)) for j in range(3)]
+    live = {k: v.clone() for k, v in xs[0].items()}              # the tensors the graph reads
+    eager = []
+    for x in xs:
+        b = H.gpu_compress(wl, x)
+        b.decode(x["q_dec"][0])
+        b.recalibrate(x["q_dec"][0], x["k"], x["v"], x["seq_offsets"])
+        torch.cuda.synchronize()
+        eager.append({k: getattr(b, k).clone() for k in ("indices", "k_c", "c_out", "c_lse", "out", "flags", "a_lse")})
+    bufs = H.gpu_compress(wl, live)                              # warm-up (also sets the LDS attribute)
+    bufs.recalibrate(live["q_dec"][0], live["k"], live["v"], live["seq_offsets"])
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        bufs.compress(live["q_win"], live["k"], live["v"], live["seq_offsets"], stream=side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            st = torch.cuda.current_stream()
+            bufs.compress(live["q_win"], live["k"], live["v"], live["seq_offsets"], stream=st)
+            bufs.decode(live["q_dec"][0], stream=st)
+            bufs.recalibrate(live["q_dec"][0], live["k"], live["v"], live["seq_offsets"], stream=st)
+    for rep_i in range(2):
+        for j, x in enumerate(xs):
+            for k in live:
+                live[k].copy_(x[k])
+            bufs.out.zero_(); bufs.indices.zero_(); bufs.c_out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for k, want in eager[j].items():
+                assert torch.equal(getattr(bufs, k), want), (rep_i, j, k)
