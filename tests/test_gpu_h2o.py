@@ -82,6 +82,8 @@ def check_h2o(wl, x, q_full, bufs, n_local, rep, calib=0):
     (small("bf16", 4, 4, 64, [513], 16, 100, 1, T=2, name="h2o_bf16_d64_g1"), 30),
     (small("fp32", 16, 2, 128, [400], 16, 60, 1, T=2, name="h2o_fp32_g8"), 59),
     (small("bf16", 32, 8, 128, [2050], 32, 512, 1, T=2, name="h2o_llama_shape"), 0),
+    (small("bf16", 14, 2, 128, [900, 130], 16, 128, 1, T=2, name="h2o_g7"), 0),
+    (small("fp32", 6, 2, 64, [611], 16, 90, 1, T=2, name="h2o_g3_fp32"), 17),
 ], ids=lambda v: v.name if hasattr(v, "name") else str(v))
 def test_h2o_strategy(wl, n_local):
     x = to_dev(synth.make_inputs(wl, 61))
