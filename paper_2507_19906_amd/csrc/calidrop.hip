@@ -195,12 +195,15 @@ int run_selection(const calidrop_params* p, int window, int pool_k, int max_seq_
       const size_t votes = (static_cast<size_t>(max_prefix) + max_prefix / 32 + 1) * sizeof(float);
       if (votes > lds) lds = votes;
     }
-    const void* fn = reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads>);
+    const bool fine = max_prefix <= cd::kSelThreads * 8;       // short prefixes: 8 positions per thread
+    const void* fn = fine ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 8>)
+                          : reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 32>);
     if (lds > 48 * 1024) {
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(cd::select_gather_lds_kernel<cd::kSelThreads>, dim3(bg), dim3(cd::kSelThreads), lds, st, se);
+    if (fine) hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 8>), dim3(bg), dim3(cd::kSelThreads), lds, st, se);
+    else hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 32>), dim3(bg), dim3(cd::kSelThreads), lds, st, se);
   } else {
     cd::WideArgs wa{};
     wa.s = se; wa.NSEG = NSEG;

@@ -441,14 +441,14 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(SelectArgs a) {
   st16(static_cast<char*>(a.v_c) + dof, ld16(static_cast<const char*>(a.v) + so));
 }
 
-// LDS variant for prefixes of up to 32 * NT positions (NT = 1024 threads in use: smaller
+// LDS variant for prefixes of up to PER * NT positions (NT = 1024 threads in use: smaller
 // workgroups were measured slower, their staging and gather phases have too few threads).
-// Thread t owns positions
-// 32t..32t+31: their pooled scores live in its registers for the radix passes and the
-// compaction, and their bits are exactly bitmap word t.  The votes are staged once in LDS
+// Thread t owns positions PER*t..PER*t+PER-1: their pooled scores live in its registers for the
+// radix passes and the compaction.  PER = 32: their bits are exactly bitmap word t (prefixes up
+// to 32768); PER = 8: a byte of a word, so that prefixes up to 8192 still keep every thread busy.  The votes are staged once in LDS
 // (padded by one word per 32 so that the stride-32 accesses do not collide), and the same
 // LDS later holds the retained indices for the gather.
-template <int NT>
+template <int NT, int PER>
 __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
   extern __shared__ uint32_t s_sel[];
   float* s_vote = reinterpret_cast<float*>(s_sel);
@@ -467,7 +467,7 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
 
   __shared__ RadixShared sh;
   __shared__ uint32_t wave_tot[2][NT / 64];
-  constexpr int PER = kSelPerThread;
+  static_assert(PER == 32 || PER == 8, "a thread owns a whole bitmap word or a byte of one");
   auto pad = [](int j) { return j + (j >> 5); };
 
   if (n <= a.B) {                       // nothing to evict: keep every position
@@ -593,7 +593,15 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
       }
       word |= (calib ? 0u : 1u) << u;       // bit = skip in the calibration pass
     }
-    if (j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + tid] = word;
+    if constexpr (PER == 32) {
+      if (j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + tid] = word;
+    } else {
+      // four neighbouring lanes hold the four bytes of a word (bits beyond the byte are zero;
+      // positions beyond the prefix were marked "skip" above)
+      const uint32_t w32 = (word & 0xFFu) | ((__shfl_down(word, 1) & 0xFFu) << 8) |
+                           ((__shfl_down(word, 2) & 0xFFu) << 16) | ((__shfl_down(word, 3) & 0xFFu) << 24);
+      if ((tid & 3) == 0 && j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + (j0 >> 5)] = w32;
+    }
     for (int r = tid; r < a.w; r += NT) { idx[k_sel + r] = P + r; s_idx[k_sel + r] = P + r; }
     if (cal) {                                                              // pad a short calibration set
       const int n_cal = min(a.calib, P - k_sel);
