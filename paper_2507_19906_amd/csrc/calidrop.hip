@@ -195,15 +195,19 @@ int run_selection(const calidrop_params* p, int window, int pool_k, int max_seq_
       const size_t votes = (static_cast<size_t>(max_prefix) + max_prefix / 32 + 1) * sizeof(float);
       if (votes > lds) lds = votes;
     }
-    const bool fine = max_prefix <= cd::kSelThreads * 8;       // short prefixes: 8 positions per thread
-    const void* fn = fine ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 8>)
-                          : reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 32>);
+    // positions per thread: the smallest of 8 / 16 / 32 that covers the longest prefix
+    const int per = max_prefix <= cd::kSelThreads * 8 ? 8 : max_prefix <= cd::kSelThreads * 16 ? 16 : 32;
+    const void* fn = per == 8    ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 8>)
+                     : per == 16 ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 16>)
+                                 : reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 32>);
     if (lds > 48 * 1024) {
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
     }
-    if (fine) hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 8>), dim3(bg), dim3(cd::kSelThreads), lds, st, se);
-    else hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 32>), dim3(bg), dim3(cd::kSelThreads), lds, st, se);
+    const dim3 grid(bg), block(cd::kSelThreads);
+    if (per == 8) hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 8>), grid, block, lds, st, se);
+    else if (per == 16) hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 16>), grid, block, lds, st, se);
+    else hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 32>), grid, block, lds, st, se);
   } else {
     cd::WideArgs wa{};
     wa.s = se; wa.NSEG = NSEG;

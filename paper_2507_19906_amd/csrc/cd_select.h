@@ -445,7 +445,8 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(SelectArgs a) {
 // workgroups were measured slower, their staging and gather phases have too few threads).
 // Thread t owns positions PER*t..PER*t+PER-1: their pooled scores live in its registers for the
 // radix passes and the compaction.  PER = 32: their bits are exactly bitmap word t (prefixes up
-// to 32768); PER = 8: a byte of a word, so that prefixes up to 8192 still keep every thread busy.  The votes are staged once in LDS
+// to 32768); PER = 16 / 8: half a word / a byte, so that prefixes up to 16384 / 8192 still keep
+// every thread busy.  The votes are staged once in LDS
 // (padded by one word per 32 so that the stride-32 accesses do not collide), and the same
 // LDS later holds the retained indices for the gather.
 template <int NT, int PER>
@@ -467,7 +468,7 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
 
   __shared__ RadixShared sh;
   __shared__ uint32_t wave_tot[2][NT / 64];
-  static_assert(PER == 32 || PER == 8, "a thread owns a whole bitmap word or a byte of one");
+  static_assert(PER == 32 || PER == 16 || PER == 8, "a thread owns a whole bitmap word, a half or a byte of one");
   auto pad = [](int j) { return j + (j >> 5); };
 
   if (n <= a.B) {                       // nothing to evict: keep every position
@@ -596,11 +597,14 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
     if constexpr (PER == 32) {
       if (j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + tid] = word;
     } else {
-      // four neighbouring lanes hold the four bytes of a word (bits beyond the byte are zero;
-      // positions beyond the prefix were marked "skip" above)
-      const uint32_t w32 = (word & 0xFFu) | ((__shfl_down(word, 1) & 0xFFu) << 8) |
-                           ((__shfl_down(word, 2) & 0xFFu) << 16) | ((__shfl_down(word, 3) & 0xFFu) << 24);
-      if ((tid & 3) == 0 && j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + (j0 >> 5)] = w32;
+      // 32 / PER neighbouring lanes hold the pieces of one word (positions beyond the prefix were
+      // marked "skip" above, so the pieces of idle threads are all ones)
+      constexpr int LPW = 32 / PER;
+      constexpr uint32_t kMask = (1u << PER) - 1u;
+      uint32_t w32 = word & kMask;
+#pragma unroll
+      for (int q = 1; q < LPW; ++q) w32 |= (__shfl_down(word, q) & kMask) << (q * PER);
+      if ((tid & (LPW - 1)) == 0 && j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + (j0 >> 5)] = w32;
     }
     for (int r = tid; r < a.w; r += NT) { idx[k_sel + r] = P + r; s_idx[k_sel + r] = P + r; }
     if (cal) {                                                              // pad a short calibration set

@@ -57,6 +57,7 @@ def test_config2_bf16_llama8b_8k():
     small("fp32", 6, 2, 64, [300, 1000, 50, 257], 16, 64, 5, name="varlen_with_short_seq"),
     small("bf16", 32, 8, 128, [513, 2049, 100, 640], 32, 512, 7, name="varlen_bf16_budget_edge"),
     small("bf16", 4, 1, 128, [65], 1, 2, 1, name="window1_budget2"),
+    small("bf16", 8, 2, 64, [9000, 12000], 16, 300, 5, T=2, name="selection_16_positions_per_thread"),
     small("bf16", 28, 4, 128, [1500, 777], 32, 256, 7, name="g7_qwen_like"),
     small("bf16", 64, 8, 128, [2100], 32, 512, 7, T=2, name="g8_llama70b_like"),
     small("fp32", 10, 2, 64, [640], 16, 96, 5, name="g5_fp32"),
