@@ -197,6 +197,18 @@ int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, 
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * calidrop_append - decode-time growth of the compressed cache: tokens generated during decoding
+ * are appended and never evicted (the evicted set is fixed at prefill).  For every sequence b
+ * the rows k_new[b][g], v_new[b][g] ([batch][Hkv][D] dtype: K and V of the token just generated)
+ * are written to position cache_lens[b] of every KV head of k_c / v_c and cache_lens[b] grows by
+ * one.  A sequence whose capacity (cache_offsets[b+1] - cache_offsets[b]) is used up is left
+ * unchanged.  No workspace.  The next calidrop_decode must be given max_cache_len >= the new
+ * lengths (the capacity is always a valid choice).
+ */
+int calidrop_append(const calidrop_params* p, const void* k_new, const void* v_new, void* k_c,
+                    void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, void* stream);
+
+/*
  * calidrop_recalibrate - the rho < theta1 branch of Alg. 2 (steps 3-8), for the heads that the
  * preceding calidrop_decode call of the same step flagged CALIDROP_FLAG_RECOMPUTE.
  *

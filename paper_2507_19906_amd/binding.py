@@ -119,6 +119,8 @@ def lib() -> ctypes.CDLL:
         L.calidrop_compress_h2o.restype = ctypes.c_int
         L.calidrop_compress_h2o.argtypes = [pp, i32, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                             vp, sz, vp]
+        L.calidrop_append.restype = ctypes.c_int
+        L.calidrop_append.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -194,6 +196,11 @@ def calidrop_decode(p: Params, q_t, k_c, v_c, cache_offsets, cache_lens, max_cac
         ctypes.byref(p), _ptr(q_t), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens),
         max_cache_len, _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(out), _ptr(a_lse), _ptr(flags),
         _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def calidrop_append(p: Params, k_new, v_new, k_c, v_c, cache_offsets, cache_lens, stream=None) -> None:
+    _check(lib().calidrop_append(ctypes.byref(p), _ptr(k_new), _ptr(v_new), _ptr(k_c), _ptr(v_c),
+                                 _ptr(cache_offsets), _ptr(cache_lens), _stream(stream)))
 
 
 def calidrop_recalibrate_workspace_bytes(p: Params, max_seq_len: int) -> int:
@@ -431,6 +438,10 @@ class CompressBuffers:
         calidrop_decode(self.p, q_t, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
                         max_cache_len or self.max_cache_len, self.c_q, self.c_out, self.c_lse,
                         self.out, self.a_lse, self.flags, self.ws_decode, stream)
+
+    def append(self, k_new, v_new, stream=None):
+        """Append the K/V rows of the token just generated ([batch][Hkv][D]) to every sequence."""
+        calidrop_append(self.p, k_new, v_new, self.k_c, self.v_c, self.cache_offsets, self.cache_lens, stream)
 
     def recalibrate(self, q_t, k, v, seq_offsets, stream=None):
         """Recomputation branch for the heads the last decode() flagged (updates out/flags/state)."""

@@ -1043,4 +1043,24 @@ int calidrop_compress_h2o(const calidrop_params* p_in, int32_t n_local, const vo
 #undef CD_DISPATCH
 }
 
+int calidrop_append(const calidrop_params* p_in, const void* k_new, const void* v_new, void* k_c, void* v_c,
+                    const int32_t* cache_offsets, int32_t* cache_lens, void* stream) {
+  int rc;
+  calidrop_params pp; const calidrop_params* p = &pp;
+  if ((rc = load_params(p_in, &pp))) return rc;
+  if ((rc = check_params(p))) return rc;
+  const struct { const void* ptr; const char* name; } req[] = {
+      {k_new, "k_new"}, {v_new, "v_new"}, {k_c, "k_c"}, {v_c, "v_c"}, {cache_offsets, "cache_offsets"},
+      {cache_lens, "cache_lens"}};
+  for (const auto& r : req)
+    if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
+  for (const auto& r : req)
+    if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  cd::AppendArgs aa{};
+  aa.k_new = k_new; aa.v_new = v_new; aa.k_c = k_c; aa.v_c = v_c; aa.cache_off = cache_offsets; aa.cache_lens = cache_lens;
+  aa.batch = p->batch; aa.Hkv = p->n_kv_heads; aa.row_bytes = p->head_dim * (p->dtype == CALIDROP_BF16 ? 2 : 4);
+  hipLaunchKernelGGL(cd::append_rows_kernel, dim3(p->batch), dim3(256), 0, static_cast<hipStream_t>(stream), aa);
+  return launch_status("append_rows");
+}
+
 }  // extern "C"

@@ -167,4 +167,33 @@ __global__ __launch_bounds__(256) void pack_gather_kernel(PackArgs a) {
   st16(static_cast<char*>(a.v_e) + dof, vv);
 }
 
+// ---- decode-time growth of the compressed cache ----------------------------------------------
+struct AppendArgs {
+  const void* k_new; const void* v_new;     // [batch][Hkv][D]: the K/V rows of the token just generated
+  void* k_c; void* v_c;
+  const int32_t* cache_off;
+  int32_t* cache_lens;
+  int batch, Hkv, row_bytes;
+};
+
+// One workgroup per sequence: the new row of every KV head goes to position cache_lens[b], then
+// cache_lens[b] grows by one.  A sequence whose capacity is used up is left as it is.
+__global__ __launch_bounds__(256) void append_rows_kernel(AppendArgs a) {
+  const int b = blockIdx.x;
+  const int c0 = a.cache_off[b];
+  const int cap = a.cache_off[b + 1] - c0;
+  const int pos = a.cache_lens[b];
+  __syncthreads();                              // everyone has read the length before it changes
+  if (pos < 0 || pos >= cap) return;
+  const int vec_per_row = a.row_bytes / 16;
+  for (int t = threadIdx.x; t < a.Hkv * vec_per_row; t += 256) {
+    const int g = t / vec_per_row, vcol = t - g * vec_per_row;
+    const int64_t so = (static_cast<int64_t>(b) * a.Hkv + g) * a.row_bytes + vcol * 16;
+    const int64_t dof = ((static_cast<int64_t>(c0) * a.Hkv + static_cast<int64_t>(g) * cap + pos) * a.row_bytes) + vcol * 16;
+    st16(static_cast<char*>(a.k_c) + dof, ld16(static_cast<const char*>(a.k_new) + so));
+    st16(static_cast<char*>(a.v_c) + dof, ld16(static_cast<const char*>(a.v_new) + so));
+  }
+  if (threadIdx.x == 0) a.cache_lens[b] = pos + 1;
+}
+
 }  // namespace cd

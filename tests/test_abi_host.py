@@ -236,3 +236,13 @@ def test_probe_library_exports_its_header():
     assert L.calidrop_probe_stream_read(4096, (1 << 20) + 16, 64, 4096, None) == -1
     L.calidrop_probe_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
     assert L.calidrop_probe_mfma_loop(None, 8, 8, None) == -1
+
+
+def test_append_validates_on_the_host():
+    A = 4096
+    L = cd.lib()
+    p = good()
+    assert L.calidrop_append(ctypes.byref(p), A, A, A, A, A, None, None) == cd.EINVAL
+    assert "cache_lens is NULL" in cd.calidrop_last_error()
+    assert L.calidrop_append(ctypes.byref(p), A + 4, A, A, A, A, A, None) == cd.EALIGN
+    assert L.calidrop_append(ctypes.byref(good(head_dim=80)), A, A, A, A, A, A, None) == cd.EUNSUPPORTED

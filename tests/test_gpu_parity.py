@@ -506,3 +506,54 @@ def test_whole_step_under_hip_graph_replay(n):
             torch.cuda.synchronize()
             for k, want in eager[j].items():
                 assert torch.equal(getattr(bufs, k), want), (rep_i, j, k)
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("fp32", 64)])
+def test_append_grows_the_cache_on_the_device(dtype, D):
+    # decode-time tokens are appended (never evicted): calidrop_append writes the new rows at
+    # cache_lens and bumps it, all on the device; every step is checked against the oracle on the
+    # grown cache, a full cache stays unchanged, and the loop replays from a HIP graph
+    wl = small(dtype, 8, 2, D, [700, 60, 900], 16, 96, 5, T=6, name=f"append_{dtype}")
+    x = to_dev(synth.make_inputs(wl, 23))
+    bufs = H.gpu_compress(wl, x, extra_capacity=4)
+    g = torch.Generator(device=DEV).manual_seed(5)
+    news = [(torch.randn((3, 2, D), generator=g, device=DEV).to(bufs.k_c.dtype),
+             torch.randn((3, 2, D), generator=g, device=DEV).to(bufs.k_c.dtype)) for _ in range(6)]
+    lens0 = bufs.cache_lens.clone()
+    k0, v0 = bufs.k_c.clone(), bufs.v_c.clone()
+    rep = {}
+    outs = []
+    for t in range(6):
+        bufs.append(*news[t])
+        bufs.decode(x["q_dec"][t])
+        torch.cuda.synchronize()
+        for b in range(3):
+            L0 = int(lens0[b])
+            grown = min(t + 1, bufs.cap - L0)                     # capacity = budget + 4 rows per head
+            assert int(bufs.cache_lens[b]) == L0 + grown
+            for j in range(grown):
+                assert torch.equal(bufs.cache_view("k", b)[:, L0 + j], news[j][0][b])
+                assert torch.equal(bufs.cache_view("v", b)[:, L0 + j], news[j][1][b])
+            H.check_decode_step(wl, bufs, x["q_dec"][t], b, report=rep)
+        outs.append(bufs.out.clone())
+    # the same loop from a graph, starting from the same state
+    bufs.k_c.copy_(k0); bufs.v_c.copy_(v0); bufs.cache_lens.copy_(lens0)
+    got = [torch.empty_like(bufs.out) for _ in range(6)]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        bufs.decode(x["q_dec"][0], stream=side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            st = torch.cuda.current_stream()
+            for t in range(6):
+                bufs.append(*news[t], stream=st)
+                bufs.decode(x["q_dec"][t], stream=st)
+                got[t].copy_(bufs.out)
+    for rep_i in range(2):
+        bufs.k_c.copy_(k0); bufs.v_c.copy_(v0); bufs.cache_lens.copy_(lens0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t in range(6):
+            assert torch.equal(got[t], outs[t]), (rep_i, t)
