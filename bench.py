@@ -404,7 +404,7 @@ def main():
                              "one kernel per call"},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, x, layers=16, decode_steps=128)
+        out["cpu_baseline"] = cpu_baseline(wl, x, layers=24, decode_steps=128)
     print(json.dumps(out))
 
 
