@@ -557,3 +557,32 @@ def test_append_grows_the_cache_on_the_device(dtype, D):
         torch.cuda.synchronize()
         for t in range(6):
             assert torch.equal(got[t], outs[t]), (rep_i, t)
+
+
+def test_inconsistent_offsets_are_contained_by_the_kernels():
+    # seq_offsets lives in device memory, so the host cannot validate it; the kernels treat a
+    # sequence whose offsets break the contract (negative length, longer than max_seq_len, beyond
+    # total_tokens) as empty and touch nothing of it, while the other sequences are unaffected
+    wl = small("bf16", 8, 2, 128, [700, 500, 900], 16, 96, 5, T=1, name="bad_offsets")
+    x = to_dev(synth.make_inputs(wl, 31))
+    good = H.gpu_compress(wl, x)
+    p = H.params_for(wl)
+    for bad in ([0, 700, 600, 2100], [0, 700, 700 + 5000, 2100], [0, 700, 1200, 2100 + 64]):
+        bufs = cd.CompressBuffers(p, wl.seq_lens, DEV)
+        bufs.k_c.fill_(7.0); bufs.v_c.fill_(7.0)
+        so = torch.tensor(bad, dtype=torch.int32, device=DEV)
+        bufs.compress(x["q_win"], x["k"], x["v"], so)
+        bufs.decode(x["q_dec"][0])
+        torch.cuda.synchronize()
+        broken = [b for b in range(3) if not (0 <= bad[b + 1] - bad[b] <= 900 and bad[b + 1] <= 2100 and bad[b] >= 0)]
+        assert broken, bad
+        for b in range(3):
+            if b in broken:
+                assert int(bufs.cache_lens[b]) == 0 and torch.all(bufs.indices[b] == -1)
+                assert torch.all(bufs.cache_view("k", b) == 7.0) and torch.all(bufs.cache_view("v", b) == 7.0)
+                assert torch.all(torch.isinf(bufs.c_lse[b])) and torch.all(bufs.out[b] == 0)
+            elif bad[b] == [0, 700, 1200, 2100][b] and bad[b + 1] == [0, 700, 1200, 2100][b + 1]:
+                assert torch.equal(bufs.indices[b], good.indices[b])
+                assert torch.equal(bufs.cache_view("k", b), good.cache_view("k", b))
+                assert torch.equal(bufs.c_out[b], good.c_out[b])
+        assert torch.isfinite(bufs.out.float()).all()
