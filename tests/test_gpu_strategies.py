@@ -323,3 +323,32 @@ def test_random_sweep_over_strategies_shapes_and_offload():
             for b in range(wl.batch):
                 H.check_recalibrate(wl, x, bufs, q_t, b, before, report=rep)
     assert min(counts.values()) >= 4
+
+
+def test_pack_with_too_little_capacity_writes_nothing_for_that_sequence():
+    wl = small("fp32", 4, 2, 64, [400, 300], 8, 32, 1, T=1, name="pack_small_capacity")
+    x = to_dev(synth.make_inputs(wl, 9))
+    bufs = H.gpu_compress(wl, x)
+    p = bufs.p
+    rows = [cd.calidrop_packed_rows(p, n) for n in wl.seq_lens]            # 368, 268
+    caps = [rows[0] - 1, rows[1]]                                          # sequence 0 one row short
+    offs = torch.tensor([0, caps[0], caps[0] + caps[1]], dtype=torch.int32, device=DEV)
+    tot = (caps[0] + caps[1]) * 2
+    k_e = torch.full((tot * 64,), 5.0, device=DEV); v_e = torch.full((tot * 64,), 5.0, device=DEV)
+    lens = torch.full((2,), -3, dtype=torch.int32, device=DEV)
+    ev_idx = torch.full((tot,), -9, dtype=torch.int32, device=DEV)
+    ws = torch.empty(cd.calidrop_pack_evicted_workspace_bytes(p, bufs.max_seq_len), dtype=torch.uint8, device=DEV)
+    cd.calidrop_pack_evicted(p, x["k"], x["v"], x["seq_offsets"], bufs.total_tokens, bufs.max_seq_len, bufs.indices,
+                             None, k_e, v_e, offs, lens, ev_idx, ws)
+    torch.cuda.synchronize()
+    assert lens.tolist() == [0, rows[1]]
+    n0 = caps[0] * 2
+    assert torch.all(k_e[:n0 * 64] == 5.0) and torch.all(ev_idx[:n0] == -9)           # untouched
+    K1 = synth.seq_view(x["k"], wl, 1)
+    idx1 = bufs.indices[1].cpu().numpy()
+    for g in range(2):
+        want = np.setdiff1d(np.arange(300), idx1[g])
+        got = ev_idx[n0 + g * caps[1]: n0 + (g + 1) * caps[1]].cpu().numpy()
+        assert np.array_equal(got, want)
+        rows_g = k_e[(n0 + g * caps[1]) * 64:(n0 + (g + 1) * caps[1]) * 64].view(caps[1], 64)
+        assert torch.equal(rows_g, K1[g][torch.from_numpy(want).to(DEV)])
