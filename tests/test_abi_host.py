@@ -246,3 +246,19 @@ def test_append_validates_on_the_host():
     assert "cache_lens is NULL" in cd.calidrop_last_error()
     assert L.calidrop_append(ctypes.byref(p), A + 4, A, A, A, A, A, None) == cd.EALIGN
     assert L.calidrop_append(ctypes.byref(good(head_dim=80)), A, A, A, A, A, A, None) == cd.EUNSUPPORTED
+
+
+def test_public_headers_are_plain_c99(tmp_path):
+    # the boundary is a C ABI: both headers must compile as C (not only as C++), pedantically
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "abi.c"
+    src.write_text('#include "calidrop.h"\n#include "calidrop_probes.h"\n'
+                   "int main(void) { calidrop_params p; p.struct_size = (uint32_t)sizeof(p);\n"
+                   "  return (int)(sizeof(calidrop_params) != 52u) + (int)p.struct_size * 0; }\n")
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                          "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
