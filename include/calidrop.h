@@ -183,8 +183,10 @@ int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k
  *      otherwise out = o_a, flag NONE.
  *
  * Arguments: q_t [batch][Hq][D] dtype; k_c, v_c, cache_offsets, cache_lens as produced by
- * calidrop_compress (the caller may have appended rows and raised cache_lens);
- * max_cache_len >= every cache_lens[b] (host copy; sizes the grid); c_q, c_out, c_lse the
+ * calidrop_compress (the caller may have appended rows and raised cache_lens).  cache_offsets may
+ * be NULL when every sequence has the same capacity and that capacity is max_cache_len (sequence
+ * b then starts at token b * max_cache_len): the kernel then needs no offset loads before it can
+ * start streaming.  max_cache_len >= every cache_lens[b] (host copy; sizes the grid); c_q, c_out, c_lse the
  * calibration state; out [batch][Hq][D] dtype; a_lse optional out [batch][Hq] fp32 (may be
  * NULL); flags optional out [batch][Hq] uint8 (may be NULL); workspace >=
  * calidrop_decode_workspace_bytes(p, max_cache_len) bytes, 256-byte aligned.

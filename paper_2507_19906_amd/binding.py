@@ -434,10 +434,18 @@ class CompressBuffers:
         calidrop_streaming_indices(self.p, n_sink, seq_offsets, self.total_tokens, self.max_seq_len,
                                    self.indices, stream)
 
-    def decode(self, q_t, stream=None, max_cache_len=None):
-        calidrop_decode(self.p, q_t, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
-                        max_cache_len or self.max_cache_len, self.c_q, self.c_out, self.c_lse,
-                        self.out, self.a_lse, self.flags, self.ws_decode, stream)
+    def decode(self, q_t, stream=None, max_cache_len=None, pass_offsets=None):
+        # the layout here is uniform (capacity self.cap for every sequence): when the call's
+        # max_cache_len is that capacity the offsets need not be passed (pass_offsets=True still
+        # passes them)
+        mcl = max_cache_len or self.max_cache_len
+        if pass_offsets is None:
+            pass_offsets = mcl != self.cap
+        if not pass_offsets and mcl != self.cap:
+            raise ValueError("the offsets can only be left out when max_cache_len is the capacity")
+        offs = self.cache_offsets if pass_offsets else None
+        calidrop_decode(self.p, q_t, self.k_c, self.v_c, offs, self.cache_lens, mcl, self.c_q, self.c_out,
+                        self.c_lse, self.out, self.a_lse, self.flags, self.ws_decode, stream)
 
     def append(self, k_new, v_new, stream=None):
         """Append the K/V rows of the token just generated ([batch][Hkv][D]) to every sequence."""

@@ -726,12 +726,17 @@ int calidrop_decode(const calidrop_params* p_in, const void* q_t, const void* k_
   if ((rc = check_params(p))) return rc;
   if (max_cache_len < 1) return fail(CALIDROP_ESHAPE, "max_cache_len must be >= 1 (got %d)", max_cache_len);
   const struct { const void* ptr; const char* name; } req[] = {
-      {q_t, "q_t"}, {k_c, "k_c"}, {v_c, "v_c"}, {cache_offsets, "cache_offsets"}, {cache_lens, "cache_lens"},
+      {q_t, "q_t"}, {k_c, "k_c"}, {v_c, "v_c"}, {cache_lens, "cache_lens"},
       {c_q, "c_q"}, {c_out, "c_out"}, {c_lse, "c_lse"}, {out, "out"}};
   for (const auto& r : req)
     if (!r.ptr) return fail(CALIDROP_EINVAL, "%s is NULL", r.name);
   for (const auto& r : req)
     if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
+  if (cache_offsets) {
+    if (!aligned16(cache_offsets)) return fail(CALIDROP_EALIGN, "cache_offsets is not 16-byte aligned");
+  } else if (static_cast<int64_t>(p->batch) * max_cache_len > (static_cast<int64_t>(1) << 31) - 1) {
+    return fail(CALIDROP_EUNSUPPORTED, "batch * max_cache_len exceeds int32 offsets (uniform layout)");
+  }
   const DecodeLayout L = decode_layout(p, max_cache_len);
   if (!workspace || workspace_bytes < L.total)
     return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,

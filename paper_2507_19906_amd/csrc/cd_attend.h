@@ -42,8 +42,8 @@ __device__ __forceinline__ void attend_geometry(const AttendArgs& a, int b, int&
     head_stride = n;
     rows = (n > a.B) ? n - a.w : 0;
   } else {                                          // decode: live rows of the cache
-    off0 = a.row_off[b];
-    head_stride = a.row_off[b + 1] - off0;
+    if (a.row_off) { off0 = a.row_off[b]; head_stride = a.row_off[b + 1] - off0; }
+    else { head_stride = a.max_len; off0 = b * a.max_len; }      // uniform capacity
     int len = a.row_len[b];
     rows = (len < 0 || len > head_stride || len > a.max_len) ? 0 : len;
   }
@@ -158,12 +158,17 @@ struct AttendWave {
   template <bool kPrefetch = true, bool kLogits = false>
   __device__ __forceinline__ void run(const T* kbase, const T* vbase, const uint32_t* bm, int rows, int row_first,
                                       int row_end, int row_step, float sl2, int i, int c,
-                                      const float* zhead = nullptr, bool zvalid = false) {
-    if (row_first >= row_end) return;
+                                      const float* zhead = nullptr, bool zvalid = false, int first_clamp = 0) {
     u32x4 kf[2][NK];
     f32x4 zf[2];
+    if constexpr (!kLogits) {
+      // first_clamp > 0: the K rows of the first tile are requested before `rows` is known (it may
+      // still be on its way from memory), clamped to a row count that is certainly addressable
+      if (first_clamp > 0) load_k(kbase, row_first, first_clamp, i, c, kf);
+    }
+    if (row_first >= row_end) return;
     if constexpr (kLogits) load_z(zhead, row_first, c, zvalid, zf);
-    else load_k(kbase, row_first, rows, i, c, kf);
+    else if (first_clamp <= 0) load_k(kbase, row_first, rows, i, c, kf);
     for (int row0 = row_first; row0 < row_end; row0 += row_step) {
       // V of this tile first, then K of the next tile: both in flight during the QK product
       u32x4 vf[8];
@@ -217,16 +222,26 @@ struct AttendWave {
     const float lsum = col4_sum(l);
     if (i < G) {
       if (c == 0) s_ml[i] = make_float2(m, lsum);
-#pragma unroll
-      for (int xx = 0; xx < NACC; ++xx)
+      if constexpr (kBf16) {
+        // d = 8 * slot + xx: the 8 accumulators of one (c, r) are 8 consecutive outputs
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int slot = 4 * c + r;      // output row of the tile = d slot
-          int d;
-          if constexpr (kBf16) d = 8 * slot + xx;
-          else d = 4 * (slot + 16 * (xx >> 2)) + (xx & 3);
-          if (d < D) s_o[i * D + d] = acc_o[xx][r];
+          const int d0 = 8 * (4 * c + r);
+          if (d0 < D) {
+            f32x4* dst = reinterpret_cast<f32x4*>(s_o + i * D + d0);
+            dst[0] = f32x4{acc_o[0][r], acc_o[1][r], acc_o[2][r], acc_o[3][r]};
+            dst[1] = f32x4{acc_o[4][r], acc_o[5][r], acc_o[6][r], acc_o[7][r]};
+          }
         }
+      } else {
+#pragma unroll
+        for (int xx = 0; xx < NACC; ++xx)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int d = 4 * ((4 * c + r) + 16 * (xx >> 2)) + (xx & 3);     // output row of the tile = d slot
+            if (d < D) s_o[i * D + d] = acc_o[xx][r];
+          }
+      }
     }
   }
 };
@@ -273,7 +288,7 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
   }
 
   // ---- merge the 4 waves through LDS and write this split's partial ------------------------
-  __shared__ float s_o[kAttWaves][16 * D];
+  __shared__ __attribute__((aligned(16))) float s_o[kAttWaves][16 * D];
   __shared__ float2 s_ml[kAttWaves][16];
   w.publish(s_o[wv], s_ml[wv], a.G, i, c);
   __syncthreads();
@@ -337,7 +352,7 @@ __global__ __launch_bounds__(D) void attend_finalize_kernel(FinalArgs a) {
     int n = seq_len_checked(a.row_off, b, a.max_len, a.total_tokens, off0);
     rows = (n > a.B) ? n - a.w : 0;
   } else {
-    int cap = a.row_off[b + 1] - a.row_off[b];
+    int cap = a.row_off ? a.row_off[b + 1] - a.row_off[b] : a.max_len;
     int len = a.row_len[b];
     rows = (len < 0 || len > cap || len > a.max_len) ? 0 : len;
   }
@@ -461,8 +476,11 @@ __global__ __launch_bounds__(NW * 64) void decode_fused_kernel(DecodeFusedArgs a
   const int g = blockIdx.x, b = blockIdx.y;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int i = lane & 15, c = lane >> 4;
-  const int off0 = a.row_off[b];
-  const int cap = a.row_off[b + 1] - off0;
+  // row_off == NULL: every sequence has capacity max_len and starts at b * max_len, so the K/V
+  // addresses need no load and the first K tile can be requested before row_len[b] has arrived
+  const bool uniform = a.row_off == nullptr;
+  const int off0 = uniform ? b * a.max_len : a.row_off[b];
+  const int cap = uniform ? a.max_len : a.row_off[b + 1] - off0;
   const int len = a.row_len[b];
   const int rows = (len < 0 || len > cap || len > a.max_len) ? 0 : len;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * cap;
@@ -490,9 +508,10 @@ __global__ __launch_bounds__(NW * 64) void decode_fused_kernel(DecodeFusedArgs a
   w.init(qbase + static_cast<int64_t>(i) * D, i < a.G, c);
   // (issuing the loads of both tiles of a wave before any arithmetic was measured slower than this
   // one-tile-ahead pipeline: 15.8 vs 15.0 us at 512 rows)
-  w.template run<true>(kbase, vbase, nullptr, rows, wv * kTileRows, rows, NW * kTileRows, a.sl2, i, c);
+  w.template run<true>(kbase, vbase, nullptr, rows, wv * kTileRows, rows, NW * kTileRows, a.sl2, i, c, nullptr, false,
+                       (uniform && (wv + 1) * kTileRows <= cap) ? cap : 0);
 
-  extern __shared__ float s_dyn[];                 // [NW][G][D] outputs, then [NW][G] (max, sum)
+  extern __shared__ __attribute__((aligned(16))) float s_dyn[];                 // [NW][G][D] outputs, then [NW][G] (max, sum)
   float* s_o = s_dyn;
   float2* s_ml = reinterpret_cast<float2*>(s_dyn + NW * a.G * D);
   w.publish(s_o + wv * a.G * D, s_ml + wv * a.G, a.G, i, c);

@@ -586,3 +586,23 @@ def test_inconsistent_offsets_are_contained_by_the_kernels():
                 assert torch.equal(bufs.cache_view("k", b), good.cache_view("k", b))
                 assert torch.equal(bufs.c_out[b], good.c_out[b])
         assert torch.isfinite(bufs.out.float()).all()
+
+
+@pytest.mark.parametrize("dtype,D,lens,budget", [("bf16", 128, [900, 40, 3000, 517], 512), ("fp32", 64, [700, 100], 96),
+                                                 ("bf16", 64, [5000], 2048), ("bf16", 128, [9000, 300], 4096)])
+def test_decode_without_offsets_equals_decode_with_offsets(dtype, D, lens, budget):
+    # uniform capacity: leaving cache_offsets out must not change a bit, with full, partly filled
+    # (n < budget) and appended caches, in the one-workgroup and in the split form of the step
+    wl = small(dtype, 8, 2, D, lens, 16, budget, 5, T=3, name="uniform_offsets")
+    x = to_dev(synth.make_inputs(wl, 77))
+    bufs = H.gpu_compress(wl, x, extra_capacity=2)
+    gen = torch.Generator(device=DEV).manual_seed(9)
+    for t in range(3):
+        q_t = x["q_dec"][t]
+        bufs.decode(q_t, pass_offsets=True)
+        want = (bufs.out.clone(), bufs.a_lse.clone(), bufs.flags.clone())
+        bufs.out.zero_(); bufs.a_lse.zero_(); bufs.flags.zero_()
+        bufs.decode(q_t, pass_offsets=False)
+        torch.cuda.synchronize()
+        assert torch.equal(bufs.out, want[0]) and torch.equal(bufs.a_lse, want[1]) and torch.equal(bufs.flags, want[2])
+        bufs.append(*(torch.randn((len(lens), 2, D), generator=gen, device=DEV).to(bufs.k_c.dtype) for _ in range(2)))
