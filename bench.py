@@ -146,6 +146,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--rotate", type=int, default=0, help="cache copies cycled by decode (0 = enough for 512 MiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--offset-array", action="store_true",
+                    help="pass cache_offsets to calidrop_decode (default: NULL = uniform capacity)")
     ap.add_argument("--no-extra", action="store_true", help="skip the additional budget-2048 decode measurement")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy 4 times (calibrates the profiler's HBM byte counters)")
@@ -188,8 +190,12 @@ def main():
     T = wl.decode_steps
     stream = torch.cuda.current_stream()
 
+    # the compressed cache here has one capacity for every layer: cache_offsets is left out unless
+    # --offset-array asks for the general (variable-capacity) form of the call
+    offs = bufs.cache_offsets if args.offset_array else None
+
     def decode_call(t, kc, vc):
-        cd.calidrop_decode(p, x["q_dec"][t], kc, vc, bufs.cache_offsets, bufs.cache_lens, bufs.max_cache_len,
+        cd.calidrop_decode(p, x["q_dec"][t], kc, vc, offs, bufs.cache_lens, bufs.max_cache_len,
                            bufs.c_q, bufs.c_out, bufs.c_lse, bufs.out, bufs.a_lse, bufs.flags, bufs.ws_decode,
                            stream)
 
@@ -244,7 +250,7 @@ def main():
         kc2 = [b2.k_c, b2.k_c.clone(), b2.k_c.clone()]
         vc2 = [b2.v_c, b2.v_c.clone(), b2.v_c.clone()]
         def call2(t):
-            cd.calidrop_decode(p2, x["q_dec"][t % T], kc2[t % 3], vc2[t % 3], b2.cache_offsets, b2.cache_lens,
+            cd.calidrop_decode(p2, x["q_dec"][t % T], kc2[t % 3], vc2[t % 3], b2.cache_offsets if args.offset_array else None, b2.cache_lens,
                                b2.max_cache_len, b2.c_q, b2.c_out, b2.c_lse, b2.out, b2.a_lse, b2.flags,
                                b2.ws_decode, stream)
         for t in range(6):
@@ -268,7 +274,7 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
             decode_call_on = lambda t, st: cd.calidrop_decode(
-                p, x["q_dec"][t], k_copies[t % rotate], v_copies[t % rotate], bufs.cache_offsets, bufs.cache_lens,
+                p, x["q_dec"][t], k_copies[t % rotate], v_copies[t % rotate], offs, bufs.cache_lens,
                 bufs.max_cache_len, bufs.c_q, bufs.c_out, bufs.c_lse, bufs.out, bufs.a_lse, bufs.flags,
                 bufs.ws_decode, st)
             decode_call_on(0, side)
