@@ -324,7 +324,11 @@ int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, cons
     fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse; fa.out = out; fa.a_lse = a_lse; fa.flags = flags;
     const int tiles = ceil_div(max_cache_len, cd::kTileRows);
     const size_t lds_per_wave = static_cast<size_t>(G) * (D + 2) * sizeof(float);
-    int nw = tiles <= 4 ? 4 : 8;
+    // 8 waves per workgroup for mid-sized caches (one or two tiles per wave) and whenever the pairs
+    // do not fill the chip: with 1024 rows or more and enough pairs, 4-wave workgroups - three of which fit a compute unit, so that one's merge overlaps the
+    // others' streaming - measured 1-2 % faster (256 MiB per call: 5.79 vs 5.70 TB/s)
+    const bool many_pairs = p->batch * p->n_kv_heads >= kFusedMinPairs;
+    int nw = (tiles <= 4 || (tiles >= 32 && many_pairs)) ? 4 : 8;
     while (nw > 4 && nw * lds_per_wave > 64 * 1024) nw /= 2;
     const dim3 grid(p->n_kv_heads, p->batch);
     const size_t lds = nw * lds_per_wave;

@@ -471,8 +471,11 @@ __device__ __forceinline__ float wave_sum(float x) {
 // Whole decode step of one (sequence, KV head) in a single workgroup of NW waves: streaming
 // attention over the live cache rows (Alg. 2 step 1), merge of the waves' partials by
 // Eq. 1-2, cosine gate (step 2) and calibration merge (steps 9-11).  No workspace.
+#ifndef CD_DECODE_WAVES_PER_SIMD
+#define CD_DECODE_WAVES_PER_SIMD 1
+#endif
 template <typename T, int D, int NW>
-__global__ __launch_bounds__(NW * 64) void decode_fused_kernel(DecodeFusedArgs a) {
+__global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fused_kernel(DecodeFusedArgs a) {
   const int g = blockIdx.x, b = blockIdx.y;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int i = lane & 15, c = lane >> 4;
