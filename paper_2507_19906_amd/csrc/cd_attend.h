@@ -155,10 +155,14 @@ struct AttendWave {
   }
 
   // kLogits: the logits come from `zhead` (this lane's head, log2 units) instead of K Q^T.
-  template <bool kPrefetch = true, bool kLogits = false>
+  struct NoWork { __device__ __forceinline__ void operator()() const {} };
+  // `while_waiting` runs once, after the loads of the wave's first tile have been issued and before
+  // anything waits for them: arithmetic placed there is hidden behind the memory latency.
+  template <bool kPrefetch = true, bool kLogits = false, typename F = NoWork>
   __device__ __forceinline__ void run(const T* kbase, const T* vbase, const uint32_t* bm, int rows, int row_first,
                                       int row_end, int row_step, float sl2, int i, int c,
-                                      const float* zhead = nullptr, bool zvalid = false, int first_clamp = 0) {
+                                      const float* zhead = nullptr, bool zvalid = false, int first_clamp = 0,
+                                      F while_waiting = F()) {
     u32x4 kf[2][NK];
     f32x4 zf[2];
     if constexpr (!kLogits) {
@@ -166,13 +170,14 @@ struct AttendWave {
       // still be on its way from memory), clamped to a row count that is certainly addressable
       if (first_clamp > 0) load_k(kbase, row_first, first_clamp, i, c, kf);
     }
-    if (row_first >= row_end) return;
+    if (row_first >= row_end) { while_waiting(); return; }
     if constexpr (kLogits) load_z(zhead, row_first, c, zvalid, zf);
     else if (first_clamp <= 0) load_k(kbase, row_first, rows, i, c, kf);
     for (int row0 = row_first; row0 < row_end; row0 += row_step) {
       // V of this tile first, then K of the next tile: both in flight during the QK product
       u32x4 vf[8];
       if constexpr (kBf16) load_v(vbase, row0, rows, i, c, vf);
+      if (row0 == row_first) while_waiting();
       f32x4 acc_s[2];
       const int next0 = row0 + row_step;
       if constexpr (kLogits) {
@@ -326,8 +331,7 @@ struct FinalArgs {
 
 __device__ __forceinline__ float block_sum(float x, float* red, int nthreads) {
   // sum over the workgroup (nthreads = 64 or 128), fixed order; result in every thread
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) x += __shfl_xor(x, s);
+  x = wave_sum(x);
   const int wv = threadIdx.x >> 6;
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[wv] = x;
@@ -462,10 +466,18 @@ struct DecodeFusedArgs {
   void* out; float* a_lse; uint8_t* flags;
 };
 
-__device__ __forceinline__ float wave_sum(float x) {
+// cos(q, c) of two vectors spread over the wave (lane holds elements lane + 64 u); 0 when either is 0.
+template <int N>
+__device__ __forceinline__ float cosine_of(const float (&q)[N], const float (&cvec)[N]) {
+  float dot = 0.f, nq2 = 0.f, nc2 = 0.f;
 #pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) x += __shfl_xor(x, s);
-  return x;
+  for (int u = 0; u < N; ++u) {
+    dot += q[u] * cvec[u];
+    nq2 += q[u] * q[u];
+    nc2 += cvec[u] * cvec[u];
+  }
+  dot = wave_sum(dot); nq2 = wave_sum(nq2); nc2 = wave_sum(nc2);
+  return (nq2 > 0.f && nc2 > 0.f) ? dot / (sqrtf(nq2) * sqrtf(nc2)) : 0.f;
 }
 
 // Whole decode step of one (sequence, KV head) in a single workgroup of NW waves: streaming
@@ -511,8 +523,16 @@ __global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fuse
   w.init(qbase + static_cast<int64_t>(i) * D, i < a.G, c);
   // (issuing the loads of both tiles of a wave before any arithmetic was measured slower than this
   // one-tile-ahead pipeline: 15.8 vs 15.0 us at 512 rows)
-  w.template run<true>(kbase, vbase, nullptr, rows, wv * kTileRows, rows, NW * kTileRows, a.sl2, i, c, nullptr, false,
-                       (uniform && (wv + 1) * kTileRows <= cap) ? cap : 0);
+  // The gate of Alg. 2 step 2 depends on the query and C_q only: wave wv works out the cosine of its
+  // head while its first K/V tile is on the way (those operands were requested before the tile).
+  // The wave-wide sums are chains of cross-lane exchanges, about a microsecond of pure latency
+  // when they sit between the merge barrier and the output store instead.
+  float rho0 = 0.f;
+  auto gate_cosine = [&]() {
+    if (has_tail) rho0 = cosine_of(qd, cq);
+  };
+  w.template run<true, false>(kbase, vbase, nullptr, rows, wv * kTileRows, rows, NW * kTileRows, a.sl2, i, c, nullptr,
+                              false, (uniform && (wv + 1) * kTileRows <= cap) ? cap : 0, gate_cosine);
 
   extern __shared__ __attribute__((aligned(16))) float s_dyn[];                 // [NW][G][D] outputs, then [NW][G] (max, sum)
   float* s_o = s_dyn;
@@ -533,12 +553,14 @@ __global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fuse
       c_lse = a.c_lse[hd];
     }
     float mm = -INFINITY;
+#pragma unroll
     for (int ww = 0; ww < NW; ++ww) mm = fmaxf(mm, s_ml[ww * a.G + hh].x);
     const float ms = (mm == -INFINITY) ? 0.f : mm;
     float ll = 0.f;
     float o[D / 64];
 #pragma unroll
     for (int u = 0; u < D / 64; ++u) o[u] = 0.f;
+#pragma unroll
     for (int ww = 0; ww < NW; ++ww) {
       const float2 ml = s_ml[ww * a.G + hh];
       const float sc = fast_exp2(ml.x - ms);
@@ -548,16 +570,7 @@ __global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fuse
     }
     const bool any = ll > 0.f;
     const float lse = any ? (mm + fast_log2(ll)) * kLn2 : -INFINITY;
-    float dot = 0.f, nq2 = 0.f, nc2 = 0.f;
-#pragma unroll
-    for (int u = 0; u < D / 64; ++u) {
-      dot += qd[u] * cq[u];
-      nq2 += qd[u] * qd[u];
-      nc2 += cq[u] * cq[u];
-    }
-    dot = wave_sum(dot); nq2 = wave_sum(nq2); nc2 = wave_sum(nc2);
-    float rho = 0.f;
-    if (nq2 > 0.f && nc2 > 0.f) rho = dot / (sqrtf(nq2) * sqrtf(nc2));
+    const float rho = (hh == wv) ? rho0 : cosine_of(qd, cq);      // groups larger than the wave count recompute
     uint8_t flag = 0;
     float aj = 0.f;
     if (rho < a.theta1) flag = 2;

@@ -118,17 +118,43 @@ __device__ __forceinline__ float row16_max(float x) {
   x = fmaxf(x, dpp_f32<0x140>(x));
   return x;
 }
-// Reductions over the four lanes {i, i+16, i+32, i+48} (same column, different c).
+// Lane l's value together with that of lane l ^ 16 (pair16) or l ^ 32 (pair32), the lower lane's
+// first, through the gfx950 lane-swap instructions: two registers that start as copies of x trade
+// rows (odd rows of one with even rows of the other) or halves (upper half of one with the lower
+// half of the other), after which one holds the even-row / lower-half values in every lane and the
+// other the odd-row / upper-half values.  Plain vector-ALU instructions: no LDS round trip, unlike
+// a general lane permutation.
+typedef unsigned lane_pair_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void pair16(float x, float& lo, float& hi) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const lane_pair_t r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned r0 = r.x, r1 = r.y;
+  lo = __builtin_bit_cast(float, r0);
+  hi = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ void pair32(float x, float& lo, float& hi) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const lane_pair_t r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const unsigned r0 = r.x, r1 = r.y;
+  lo = __builtin_bit_cast(float, r0);
+  hi = __builtin_bit_cast(float, r1);
+}
+// Reductions over the four lanes {i, i+16, i+32, i+48} (same column, different c): every lane ends
+// with the same bits, (x_0 + x_16) + (x_32 + x_48).
 __device__ __forceinline__ float col4_max(float x) {
-  x = fmaxf(x, __shfl_xor(x, 16));
-  x = fmaxf(x, __shfl_xor(x, 32));
-  return x;
+  float lo, hi;
+  pair16(x, lo, hi);
+  pair32(fmaxf(lo, hi), lo, hi);
+  return fmaxf(lo, hi);
 }
 __device__ __forceinline__ float col4_sum(float x) {
-  x += __shfl_xor(x, 16);
-  x += __shfl_xor(x, 32);
-  return x;
+  float lo, hi;
+  pair16(x, lo, hi);
+  pair32(lo + hi, lo, hi);
+  return lo + hi;
 }
+// Sum over all 64 lanes, every lane ends with the same bits (fixed tree: inside rows of 16, then across).
+__device__ __forceinline__ float wave_sum(float x) { return col4_sum(row16_sum(x)); }
 
 // Three-input maximum in one instruction (operands are never NaN here, so no canonicalisation).
 __device__ __forceinline__ float max3(float a, float b, float c) {
