@@ -482,23 +482,38 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
     const int k_sel = a.B - a.w;
     // ---- stage the votes (row-block partials added first, fixed order) ---------------------
     {
+      // 16 bytes per lane from the 16-byte boundary at or below the head's first vote (the vote
+      // planes start 256-byte aligned and a head starts anywhere inside): vector v covers positions
+      // 4v - shift .. 4v - shift + 3.  All loads of a thread are in flight together.
       const int64_t plane = a.total_tokens * a.Hkv;
-      const float* vsrc = a.vote + head_tok;
-      float tmp[PER];
+      const int shift = static_cast<int>(head_tok & 3);
+      const float* vsrc = a.vote + (head_tok - shift);
+      f32x4 tmp[PER / 4];
 #pragma unroll
-      for (int u = 0; u < PER; ++u) {               // all loads of a thread in flight together
-        const int j = tid + u * NT;
-        float val = 0.f;
-        if (j < P) {
-          val = vsrc[j];
-          for (int rb = 1; rb < a.NRB; ++rb) val += vsrc[rb * plane + j];
+      for (int u = 0; u < PER / 4; ++u) {
+        const int v4 = tid + u * NT;
+        f32x4 val = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (4 * v4 - shift < P) {
+          val = *reinterpret_cast<const f32x4*>(vsrc + 4 * v4);
+          for (int rb = 1; rb < a.NRB; ++rb) val += *reinterpret_cast<const f32x4*>(vsrc + rb * plane + 4 * v4);
         }
         tmp[u] = val;
       }
 #pragma unroll
-      for (int u = 0; u < PER; ++u) {
-        const int j = tid + u * NT;
-        if (j < P) s_vote[pad(j)] = tmp[u];
+      for (int u = 0; u < PER / 4; ++u) {
+        const int jb = 4 * (tid + u * NT) - shift;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const int j = jb + x;
+          if (j >= 0 && j < P) s_vote[pad(j)] = tmp[u][x];
+        }
+      }
+      // the vectors end `shift` positions short of PER * NT: the last few of a full-length prefix
+      const int jt = PER * NT - shift + tid;
+      if (tid < shift && jt < P) {
+        float val = a.vote[head_tok + jt];
+        for (int rb = 1; rb < a.NRB; ++rb) val += a.vote[rb * plane + head_tok + jt];
+        s_vote[pad(jt)] = val;
       }
     }
     __syncthreads();
@@ -557,13 +572,20 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
 
     // ---- ordered compaction: exclusive scans of the per-thread (greater, equal) counts of
     //      both cuts, greater in the low half-word and equal in the high half-word -------------
-    uint32_t cnt1 = 0, cnt2 = 0;
+    // per-thread bit masks over its PER positions: key above the threshold / equal to it
+    constexpr uint32_t kAll = PER == 32 ? 0xFFFFFFFFu : (1u << (PER & 31)) - 1u;
+    const uint32_t valid = j0 >= P ? 0u : (P - j0 >= PER ? kAll : (1u << ((P - j0) & 31)) - 1u);
+    uint32_t gtm1 = 0, eqm1 = 0, gtm2 = 0, eqm2 = 0;
 #pragma unroll
-    for (int u = 0; u < PER; ++u)
-      if (j0 + u < P) {
-        cnt1 += (key[u] > c1.thr ? 1u : 0u) + (key[u] == c1.thr ? 0x10000u : 0u);
-        cnt2 += (key[u] > c2.thr ? 1u : 0u) + (key[u] == c2.thr ? 0x10000u : 0u);
-      }
+    for (int u = 0; u < PER; ++u) {
+      gtm1 |= (key[u] > c1.thr ? 1u : 0u) << u;
+      eqm1 |= (key[u] == c1.thr ? 1u : 0u) << u;
+      gtm2 |= (key[u] > c2.thr ? 1u : 0u) << u;
+      eqm2 |= (key[u] == c2.thr ? 1u : 0u) << u;
+    }
+    gtm1 &= valid; eqm1 &= valid; gtm2 &= valid; eqm2 &= valid;
+    const uint32_t cnt1 = __popc(gtm1) + (static_cast<uint32_t>(__popc(eqm1)) << 16);
+    const uint32_t cnt2 = __popc(gtm2) + (static_cast<uint32_t>(__popc(eqm2)) << 16);
     uint32_t inc1 = cnt1, inc2 = cnt2;
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) {
@@ -574,26 +596,37 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
     __syncthreads();                      // also: every thread is done reading the staged votes
     uint32_t bef1 = inc1 - cnt1, bef2 = inc2 - cnt2;
     for (int ww = 0; ww < wv; ++ww) { bef1 += wave_tot[0][ww]; bef2 += wave_tot[1][ww]; }
-    uint32_t gt1 = bef1 & 0xFFFFu, eq1 = bef1 >> 16, gt2 = bef2 & 0xFFFFu, eq2 = bef2 >> 16;
-    uint32_t word = 0;
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      const int j = j0 + u;
-      const bool in = j < P;
-      const bool keep = in && c1.inside(key[u], eq1);
-      const bool calib = in && !keep && c2.inside(key[u], eq2);
-      if (keep) {
-        const uint32_t pos = c1.rank(j, gt1, eq1);
+    const uint32_t gt1 = bef1 & 0xFFFFu, eq1 = bef1 >> 16, gt2 = bef2 & 0xFFFFu, eq2 = bef2 >> 16;
+    // positions of this thread inside a cut: everything above the threshold, and of the keys equal
+    // to it the first (need_eq - equal ones at earlier positions), i.e. ties go to the lower index
+    auto inside_mask = [&](const Cut& c, uint32_t gtm, uint32_t eqm, uint32_t eq_before) -> uint32_t {
+      if (c.all) return valid;
+      const uint32_t allow = c.need_eq > eq_before ? c.need_eq - eq_before : 0u;
+      if (allow < static_cast<uint32_t>(__popc(eqm))) {
+        uint32_t kept = 0;
+        for (uint32_t t = 0; t < allow; ++t) { const uint32_t low = eqm & (0u - eqm); kept |= low; eqm ^= low; }
+        eqm = kept;
+      }
+      return gtm | eqm;
+    };
+    const uint32_t keepm = inside_mask(c1, gtm1, eqm1, eq1);
+    const uint32_t calm = inside_mask(c2, gtm2, eqm2, eq2) & ~keepm;
+    // the cut's members are emitted in position order: a thread's first one lands at the number of
+    // members at earlier positions
+    const uint32_t base1 = c1.rank(j0, gt1, eq1);
+    {
+      uint32_t pos = base1;
+      for (uint32_t m = keepm; m; m &= m - 1u, ++pos) {
+        const int j = j0 + (__ffs(m) - 1);
         idx[pos] = j;
         s_idx[pos] = j;
       }
-      if (calib && cal) cal[c2.rank(j, gt2, eq2) - c1.rank(j, gt1, eq1)] = j;
-      if (in) {
-        gt1 += key[u] > c1.thr; eq1 += key[u] == c1.thr;
-        gt2 += key[u] > c2.thr; eq2 += key[u] == c2.thr;
-      }
-      word |= (calib ? 0u : 1u) << u;       // bit = skip in the calibration pass
     }
+    if (cal) {
+      uint32_t pos = c2.rank(j0, gt2, eq2) - base1;
+      for (uint32_t m = calm; m; m &= m - 1u, ++pos) cal[pos] = j0 + (__ffs(m) - 1);
+    }
+    const uint32_t word = ~calm;            // bit = skip in the calibration pass
     if constexpr (PER == 32) {
       if (j0 < P) a.bitmap[static_cast<int64_t>(bg) * a.W32 + tid] = word;
     } else {

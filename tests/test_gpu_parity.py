@@ -64,6 +64,9 @@ def test_config2_bf16_llama8b_8k():
     small("bf16", 6, 1, 64, [999], 8, 60, 3, name="g6_d64"),
     small("bf16", 8, 2, 128, [20000, 300, 8300], 32, 1024, 17, T=2, name="multi_workgroup_select_bf16"),
     small("fp32", 4, 2, 64, [16500], 16, 200, 21, T=2, name="multi_workgroup_select_fp32"),
+    # longest prefix one workgroup selects over (32768 positions), heads starting 1, 2 and 3 floats
+    # past a 16-byte boundary in the vote buffer, and shorter odd-length neighbours
+    small("bf16", 4, 4, 64, [32768 + 17, 8193 + 17, 16390 + 17], 17, 90, 5, T=1, name="full_length_prefix_misaligned_heads"),
 ], ids=lambda w: w.name)
 def test_shapes_and_ragged_tails(wl):
     run_case(wl)
