@@ -103,6 +103,28 @@ __device__ __forceinline__ float dpp_f32(float x) {
   return __builtin_bit_cast(
       float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
 }
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive adds only (no LDS
+// round trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane whose source falls outside
+// its row adds 0), then the last lane of row 0 / 2 is added to rows 1 / 3 and the last lane of
+// row 1 - by then the total of rows 0 and 1 - to rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_u32_or_zero(uint32_t x) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
+  x += dpp_u32_or_zero<0x111, 0xF>(x);   // row_shr:1
+  x += dpp_u32_or_zero<0x112, 0xF>(x);   // row_shr:2
+  x += dpp_u32_or_zero<0x114, 0xF>(x);   // row_shr:4
+  x += dpp_u32_or_zero<0x118, 0xF>(x);   // row_shr:8
+  x += dpp_u32_or_zero<0x142, 0xA>(x);   // row_bcast:15 into rows 1 and 3
+  x += dpp_u32_or_zero<0x143, 0xC>(x);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+// the value lane 63 holds, in every lane
+__device__ __forceinline__ uint32_t last_lane(uint32_t x) {
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 63));
+}
+
 // Sum over the 16 lanes that share l/16; every lane ends with the same bits (fixed tree).
 __device__ __forceinline__ float row16_sum(float x) {
   x += dpp_f32<0xB1>(x);    // quad_perm [1,0,3,2]

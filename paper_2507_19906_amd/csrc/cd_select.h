@@ -57,6 +57,7 @@ __device__ __forceinline__ void radix_select(RadixShared& sh, uint32_t rank, For
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   uint32_t prefix = 0;            // bits decided so far (the high bits of the answer)
   uint32_t remaining = rank;      // rank of the answer among the keys matching `prefix`
+#pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t himask = (pass == 0) ? 0u : (0xFFFFFFFFu << (shift + 8));
@@ -82,13 +83,9 @@ __device__ __forceinline__ void radix_select(RadixShared& sh, uint32_t rank, For
       const uint32_t h0 = sh.hist[4 * lane], h1 = sh.hist[4 * lane + 1], h2 = sh.hist[4 * lane + 2],
                      h3 = sh.hist[4 * lane + 3];
       const uint32_t mine = h0 + h1 + h2 + h3;
-      uint32_t acc = mine;
-#pragma unroll
-      for (int s = 1; s < 64; s <<= 1) {        // suffix-inclusive scan over lanes
-        const uint32_t o = __shfl_down(acc, s);
-        if (lane + s < 64) acc += o;
-      }
-      const uint32_t above = acc - mine;        // keys in bins owned by higher lanes
+      const uint32_t upto = wave_inclusive_scan(mine);
+      const uint32_t above = last_lane(upto) - upto;    // keys in bins owned by higher lanes
+      const uint32_t acc = above + mine;
       if (above < remaining && remaining <= acc) {      // exactly one lane
         uint32_t cum = above;
         int bin;
@@ -100,10 +97,12 @@ __device__ __forceinline__ void radix_select(RadixShared& sh, uint32_t rank, For
       }
     }
     __syncthreads();
+    // (no barrier after these reads: sh.prefix is next written two barriers further on, and the
+    // histogram, which the next pass clears right away, was last read before the barrier above)
     prefix = sh.prefix;
     remaining = sh.remaining;
-    __syncthreads();
   }
+  __syncthreads();                  // the caller may reuse `sh` at once
   thr = prefix;
   need_eq = remaining;
 }
@@ -586,12 +585,7 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
     gtm1 &= valid; eqm1 &= valid; gtm2 &= valid; eqm2 &= valid;
     const uint32_t cnt1 = __popc(gtm1) + (static_cast<uint32_t>(__popc(eqm1)) << 16);
     const uint32_t cnt2 = __popc(gtm2) + (static_cast<uint32_t>(__popc(eqm2)) << 16);
-    uint32_t inc1 = cnt1, inc2 = cnt2;
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) {
-      const uint32_t o1 = __shfl_up(inc1, s), o2 = __shfl_up(inc2, s);
-      if (lane >= s) { inc1 += o1; inc2 += o2; }
-    }
+    const uint32_t inc1 = wave_inclusive_scan(cnt1), inc2 = wave_inclusive_scan(cnt2);
     if (lane == 63) { wave_tot[0][wv] = inc1; wave_tot[1][wv] = inc2; }
     __syncthreads();                      // also: every thread is done reading the staged votes
     uint32_t bef1 = inc1 - cnt1, bef2 = inc2 - cnt2;
