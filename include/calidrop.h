@@ -171,6 +171,30 @@ int calidrop_compress(const calidrop_params* p, const void* q_win, const void* k
                       void* stream);
 
 /*
+ * calidrop_compress_with_lse - calidrop_compress with step 1's normalisers supplied by the caller.
+ *
+ * The softmax of step 1 needs, for every window query i of every query head, the log-sum-exp of
+ * its logits over the keys it may attend to (positions 0..P+i).  The prefill attention that
+ * produced the prompt's outputs (Alg. 1 steps 1-2, outside this library) has that number for
+ * every query row as the by-product of its own softmax; passing it in saves the pass over K that
+ * calidrop_compress spends on it (K is then read once, for the votes, instead of twice).
+ *
+ *   win_lse   [batch][Hq][w] fp32, natural-log units: log sum_{j <= P+i} exp(scale q_win[h][i].K[g][j])
+ *             with the same scale as params.scale.  NULL = compute it (exactly calidrop_compress).
+ *             The values are used as given: votes are exp(logit - win_lse), so an lse that is off
+ *             by delta scales that row's votes by exp(-delta) and nothing else.
+ *
+ * Every other argument, the outputs, the workspace and the errors are those of calidrop_compress.
+ */
+int calidrop_compress_with_lse(const calidrop_params* p, const void* q_win, const void* k,
+                               const void* v, const int32_t* seq_offsets, int64_t total_tokens,
+                               int32_t max_seq_len, const float* win_lse, const void* q_cal,
+                               void* k_c, void* v_c, const int32_t* cache_offsets,
+                               int32_t* cache_lens, int32_t* indices, int32_t* cal_indices,
+                               float* c_q, float* c_out, float* c_lse, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/*
  * calidrop_decode - Alg. 2 for one decode step of `batch` sequences.
  *
  * Per sequence b and query head h (KV head g = h / G):

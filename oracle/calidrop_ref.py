@@ -75,13 +75,17 @@ def merge(out_i, lse_i, out_j, lse_j):
 # --------------------------------------------------------------------------------------------
 # Eviction strategy f (Alg. 1 step 3), SnapKV-style (Sec. 4.1.3)
 # --------------------------------------------------------------------------------------------
-def window_votes(q_win_group, K_g, w, scale):
+def window_votes(q_win_group, K_g, w, scale, win_lse=None):
     """Accumulated attention of the observation window onto the prefix, for one KV head.
 
     q_win_group [G][w][D]: the window queries of the G query heads that share this KV head;
     query i of the window sits at position P + i (P = n - w) and may attend positions
     0..P+i.  Returns vote [P]: sum over heads and window rows of the softmax probability that
-    lands on each prefix column.  Window columns take part in the softmax but get no vote."""
+    lands on each prefix column.  Window columns take part in the softmax but get no vote.
+
+    win_lse [G][w] (optional): the rows' log-sum-exp as handed over by whoever ran the prompt's
+    attention (Alg. 1 steps 1-2); the probabilities are then exp(z - win_lse) with the values as
+    given, instead of being normalised here."""
     q = np.asarray(q_win_group, F)
     K = np.asarray(K_g, F)
     n = K.shape[0]
@@ -90,8 +94,11 @@ def window_votes(q_win_group, K_g, w, scale):
     for h in range(q.shape[0]):
         for i in range(w):
             z = logits(q[h, i], K[:P + i + 1], scale)       # causal: columns 0..P+i
-            e = np.exp(z - z.max())
-            p = e / e.sum()
+            if win_lse is None:
+                e = np.exp(z - z.max())
+                p = e / e.sum()
+            else:
+                p = np.exp(z - F(win_lse[h][i]))
             vote += p[:P]
     return vote
 
@@ -144,7 +151,7 @@ def calibration_state(q_cal, K, V, evicted, G, scale):
     return q_cal.copy(), c_out, c_lse
 
 
-def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=None, calib_size=0):
+def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=None, calib_size=0, win_lse=None):
     """Alg. 1 steps 3-8 for one sequence.
 
     calib_size = m > 0 keeps only the m evicted tokens of highest importance (pooled score, ties
@@ -155,6 +162,7 @@ def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=Non
     k = pooling kernel; q_cal [Hq][D] calibration query (default Q_{-1} = q_win[:, -1]).
     retained_override: optional list over KV heads of ascending position arrays to use instead
     of the selection (lets a test evaluate downstream values for a given retained set).
+    win_lse [Hq][w]: optional log-sum-exp of the window rows, taken as given (see window_votes).
 
     Returns dict: idx [Hkv][min(B,n)] ascending retained positions, K_c, V_c [Hkv][len][D],
     c_q, c_out [Hq][D], c_lse [Hq], vote/score (lists per KV head, None if n <= B),
@@ -180,7 +188,8 @@ def compress(q_win, K, V, w, B, k, q_cal=None, scale=None, retained_override=Non
             margins.append(np.inf)
             evicted.append(np.zeros(0, np.int64))
             continue
-        vote = window_votes(q_win[g * G:(g + 1) * G], K[g], w, scale)
+        vote = window_votes(q_win[g * G:(g + 1) * G], K[g], w, scale,
+                            None if win_lse is None else np.asarray(win_lse, F)[g * G:(g + 1) * G])
         score = avg_pool(vote, k)
         if retained_override is not None:
             sel = np.asarray(retained_override[g])[:B - w]

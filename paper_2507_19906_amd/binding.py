@@ -87,6 +87,9 @@ def lib() -> ctypes.CDLL:
         L.calidrop_compress.restype = ctypes.c_int
         L.calidrop_compress.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp,
                                         vp, vp, vp, sz, vp]
+        L.calidrop_compress_with_lse.restype = ctypes.c_int
+        L.calidrop_compress_with_lse.argtypes = [pp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                 vp, vp, vp, sz, vp]
         L.calidrop_decode.restype = ctypes.c_int
         L.calidrop_decode.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz,
                                       vp]
@@ -186,6 +189,16 @@ def calidrop_compress(p: Params, q_win, k, v, seq_offsets, total_tokens: int, ma
     _check(lib().calidrop_compress(
         ctypes.byref(p), _ptr(q_win), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
         _ptr(q_cal), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens), _ptr(indices),
+        _ptr(cal_indices), _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def calidrop_compress_with_lse(p: Params, q_win, k, v, seq_offsets, total_tokens: int, max_seq_len: int,
+                               win_lse, q_cal, k_c, v_c, cache_offsets, cache_lens, indices, cal_indices, c_q,
+                               c_out, c_lse, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().calidrop_compress_with_lse(
+        ctypes.byref(p), _ptr(q_win), _ptr(k), _ptr(v), _ptr(seq_offsets), total_tokens, max_seq_len,
+        _ptr(win_lse), _ptr(q_cal), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens), _ptr(indices),
         _ptr(cal_indices), _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
@@ -400,11 +413,19 @@ class CompressBuffers:
         self.a_lse = torch.zeros((nb, Hq), dtype=torch.float32, device=device)
         self.flags = torch.zeros((nb, Hq), dtype=torch.uint8, device=device)
 
-    def compress(self, q_win, k, v, seq_offsets, q_cal=None, stream=None):
-        calidrop_compress(self.p, q_win, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
-                          q_cal, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
-                          self.indices, self.cal_indices, self.c_q, self.c_out, self.c_lse,
-                          self.ws_compress, stream)
+    def compress(self, q_win, k, v, seq_offsets, q_cal=None, stream=None, win_lse=None):
+        """win_lse: [batch][Hq][w] fp32 log-sum-exp of the window rows from the caller's prefill
+        attention (natural log); None = the library computes it."""
+        if win_lse is None:
+            calidrop_compress(self.p, q_win, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
+                              q_cal, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
+                              self.indices, self.cal_indices, self.c_q, self.c_out, self.c_lse,
+                              self.ws_compress, stream)
+        else:
+            calidrop_compress_with_lse(self.p, q_win, k, v, seq_offsets, self.total_tokens, self.max_seq_len,
+                                       win_lse, q_cal, self.k_c, self.v_c, self.cache_offsets, self.cache_lens,
+                                       self.indices, self.cal_indices, self.c_q, self.c_out, self.c_lse,
+                                       self.ws_compress, stream)
 
     def compress_given(self, q_cal, k, v, seq_offsets, stream=None):
         """Alg. 1 steps 4-8 for the retained lists already in self.indices."""

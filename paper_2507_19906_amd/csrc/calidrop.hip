@@ -235,10 +235,10 @@ int run_selection(const calidrop_params* p, int window, int pool_k, int max_seq_
 
 template <typename T, int D>
 int compress_impl(const calidrop_params* p, const void* q_win, const void* k, const void* v,
-                  const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, const void* q_cal,
-                  void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
-                  int32_t* cal_indices, float* c_q, float* c_out, float* c_lse, char* ws, const CompressLayout& L,
-                  hipStream_t st) {
+                  const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len, const float* win_lse,
+                  const void* q_cal, void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens,
+                  int32_t* indices, int32_t* cal_indices, float* c_q, float* c_out, float* c_lse, char* ws,
+                  const CompressLayout& L, hipStream_t st) {
   const int G = p->n_q_heads / p->n_kv_heads;
   const float sl2 = logit_scale(p) * cd::kLog2e;
   int rc;
@@ -260,11 +260,17 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   const int bg = p->batch * p->n_kv_heads;
   if (max_seq_len > p->budget) {       // otherwise no sequence can need eviction
     dim3 grid_s(L.NCH, bg * L.NRB);
-    hipLaunchKernelGGL((cd::score_rowstats_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
-    if ((rc = launch_status("score_rowstats"))) return rc;
     const int64_t rows = static_cast<int64_t>(bg) * L.NRB * cd::kRowBlock;
-    hipLaunchKernelGGL(cd::rowstats_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, sa);
-    if ((rc = launch_status("rowstats_merge"))) return rc;
+    if (win_lse) {      // pass 1 is the caller's: only a unit conversion into the row table
+      hipLaunchKernelGGL(cd::rowlse_import_kernel, dim3(static_cast<unsigned>((rows + 255) / 256)), dim3(256), 0, st, sa,
+                         win_lse);
+      if ((rc = launch_status("rowlse_import"))) return rc;
+    } else {
+      hipLaunchKernelGGL((cd::score_rowstats_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
+      if ((rc = launch_status("score_rowstats"))) return rc;
+      hipLaunchKernelGGL(cd::rowstats_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, sa);
+      if ((rc = launch_status("rowstats_merge"))) return rc;
+    }
     hipLaunchKernelGGL((cd::score_votes_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
     if ((rc = launch_status("score_votes"))) return rc;
   }
@@ -681,6 +687,17 @@ int calidrop_compress(const calidrop_params* p_in, const void* q_win, const void
                       void* k_c, void* v_c, const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
                       int32_t* cal_indices, float* c_q, float* c_out, float* c_lse, void* workspace,
                       size_t workspace_bytes, void* stream) {
+  return calidrop_compress_with_lse(p_in, q_win, k, v, seq_offsets, total_tokens, max_seq_len, nullptr, q_cal, k_c, v_c,
+                                    cache_offsets, cache_lens, indices, cal_indices, c_q, c_out, c_lse, workspace,
+                                    workspace_bytes, stream);
+}
+
+int calidrop_compress_with_lse(const calidrop_params* p_in, const void* q_win, const void* k, const void* v,
+                               const int32_t* seq_offsets, int64_t total_tokens, int32_t max_seq_len,
+                               const float* win_lse, const void* q_cal, void* k_c, void* v_c,
+                               const int32_t* cache_offsets, int32_t* cache_lens, int32_t* indices,
+                               int32_t* cal_indices, float* c_q, float* c_out, float* c_lse, void* workspace,
+                               size_t workspace_bytes, void* stream) {
   int rc;
   calidrop_params pp; const calidrop_params* p = &pp;
   if ((rc = load_params(p_in, &pp))) return rc;
@@ -695,6 +712,7 @@ int calidrop_compress(const calidrop_params* p_in, const void* q_win, const void
   for (const auto& r : req)
     if (!aligned16(r.ptr)) return fail(CALIDROP_EALIGN, "%s is not 16-byte aligned", r.name);
   if (q_cal && !aligned16(q_cal)) return fail(CALIDROP_EALIGN, "q_cal is not 16-byte aligned");
+  if (win_lse && !aligned16(win_lse)) return fail(CALIDROP_EALIGN, "win_lse is not 16-byte aligned");
   if (p->calib_size > 0) {
     if (!cal_indices) return fail(CALIDROP_EINVAL, "cal_indices is NULL although calib_size is %d", p->calib_size);
     if (!aligned16(cal_indices)) return fail(CALIDROP_EALIGN, "cal_indices is not 16-byte aligned");
@@ -709,7 +727,7 @@ int calidrop_compress(const calidrop_params* p_in, const void* q_win, const void
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
 #define CD_DISPATCH(T, D)                                                                                       \
-  return compress_impl<T, D>(p, q_win, k, v, seq_offsets, total_tokens, max_seq_len, q_cal, k_c, v_c,           \
+  return compress_impl<T, D>(p, q_win, k, v, seq_offsets, total_tokens, max_seq_len, win_lse, q_cal, k_c, v_c,  \
                              cache_offsets, cache_lens, indices, cal_indices, c_q, c_out, c_lse, ws, L, st)
   if (p->dtype == CALIDROP_BF16) {
     if (p->head_dim == 128) CD_DISPATCH(cd::bf16_t, 128);

@@ -334,6 +334,26 @@ __global__ __launch_bounds__(256) void rowstats_merge_kernel(ScoreArgs a) {
   if (lane == 0) a.row_lse[gr] = (l > 0.f && rho < a.R) ? m + fast_log2(l) : INFINITY;   // padding rows: +inf
 }
 
+// The row log-sum-exp taken from the caller instead of pass 1: win_lse [batch][Hq][w] holds, in
+// natural-log units, log sum_j exp(scale q_i.K_j) of window query i over the keys it may attend to
+// (positions 0..P+i) - the by-product a prefill attention kernel has for these rows anyway.  One
+// thread per row slot; padding rows get +inf like above.
+__global__ __launch_bounds__(256) void rowlse_import_kernel(ScoreArgs a, const float* win_lse) {
+  const int64_t gr = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int64_t rows_total = static_cast<int64_t>(a.batch) * a.Hkv * a.NRB * kRowBlock;
+  if (gr >= rows_total) return;
+  const int y = static_cast<int>(gr / kRowBlock);
+  const int bg = y / a.NRB;
+  const int g = bg % a.Hkv, b = bg / a.Hkv;
+  const int rho = (y % a.NRB) * kRowBlock + static_cast<int>(gr % kRowBlock);    // row inside the KV head
+  float val = INFINITY;
+  if (rho < a.R) {
+    const int hh = rho / a.w, wi = rho - hh * a.w;
+    val = win_lse[(static_cast<int64_t>(b) * a.Hq + g * a.G + hh) * a.w + wi] * kLog2e;
+  }
+  a.row_lse[gr] = val;
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256, sizeof(T) == 2 ? CD_VOTES_WAVES : 2) void score_votes_kernel(ScoreArgs a) {
   using KS = KeyStream<T, D>;

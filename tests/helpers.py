@@ -29,19 +29,19 @@ def to64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to("cpu").to(torch.float64).numpy()
 
 
-def gpu_compress(wl, x, q_cal=None, extra_capacity=0, **over):
+def gpu_compress(wl, x, q_cal=None, extra_capacity=0, win_lse=None, **over):
     """x: dict from synth.make_inputs already on the GPU.  Returns CompressBuffers."""
     p = params_for(wl, **over)
     dev = x["k"].device
     bufs = cd.CompressBuffers(p, wl.seq_lens, dev, extra_capacity=extra_capacity)
     cd.calidrop_set_inspection(True)          # the parity checks read the pooled scores
-    bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], q_cal=q_cal)
+    bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], q_cal=q_cal, win_lse=win_lse)
     torch.cuda.synchronize()
     return bufs
 
 
 def oracle_compress(wl, x, b, heads=None, q_cal=None, override=None, budget=None, pool_kernel=None,
-                    calib_size=0):
+                    calib_size=0, win_lse=None):
     """Oracle compress of sequence b (optionally only the KV heads in `heads`)."""
     G = wl.group
     heads = list(range(wl.n_kv_heads)) if heads is None else list(heads)
@@ -50,8 +50,9 @@ def oracle_compress(wl, x, b, heads=None, q_cal=None, override=None, budget=None
     qh = [g * G + j for g in heads for j in range(G)]
     q_win = to64(x["q_win"][b])[qh]
     qc = None if q_cal is None else to64(q_cal[b])[qh]
+    lse = None if win_lse is None else to64(win_lse[b])[qh]
     return ref.compress(q_win, K, V, wl.window, budget or wl.budget, pool_kernel or wl.pool_kernel,
-                        q_cal=qc, retained_override=override, calib_size=calib_size)
+                        q_cal=qc, retained_override=override, calib_size=calib_size, win_lse=lse)
 
 
 def check_indices(gpu_idx: np.ndarray, orc: dict, dtype: str, k_sel: int, report: dict):
@@ -108,7 +109,7 @@ def check_calibration_set(gpu_cal, orc, dtype, k_sel, m, report):
     return lists
 
 
-def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_scores=True):
+def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_scores=True, win_lse=None):
     """Compare everything calidrop_compress wrote for sequence b against the oracle."""
     report = {} if report is None else report
     dt = wl.dtype
@@ -116,7 +117,7 @@ def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_sc
     n = wl.seq_lens[b]
     heads = list(range(wl.n_kv_heads)) if heads is None else list(heads)
     m = int(bufs.p.calib_size)
-    orc = oracle_compress(wl, x, b, heads, q_cal, calib_size=m)
+    orc = oracle_compress(wl, x, b, heads, q_cal, calib_size=m, win_lse=win_lse)
     length = min(B, n)
     assert int(bufs.cache_lens[b].item()) == length
     gpu_idx = bufs.indices[b].cpu().numpy()[heads]
@@ -124,7 +125,7 @@ def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_sc
         assert np.all(gpu_idx[:, n:] == -1)
     override = check_indices(gpu_idx, orc, dt, B - w, report)
     if override is not None:        # evaluate downstream values for the GPU's retained set
-        orc = oracle_compress(wl, x, b, heads, q_cal, override=override, calib_size=m)
+        orc = oracle_compress(wl, x, b, heads, q_cal, override=override, calib_size=m, win_lse=win_lse)
     if m > 0:
         gpu_cal = bufs.cal_indices[b].cpu().numpy()[heads]
         if n <= B:

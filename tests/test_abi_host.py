@@ -89,6 +89,11 @@ def test_bad_struct_size_null_align_workspace():
     assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A, need - 1, None) == cd.EWORKSPACE
     assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, None, 0, None) == cd.EWORKSPACE
     assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A, A + 16, need, None) == cd.EALIGN
+    # the variant with the window rows' log-sum-exp supplied: same checks, plus its own pointer
+    assert L.calidrop_compress_with_lse(ctypes.byref(p), A, A, A, A, 16384, 8192, A + 4, None, A, A, A, A, A, None, A, A, A, A, need, None) == cd.EALIGN
+    assert "win_lse" in cd.calidrop_last_error()
+    assert L.calidrop_compress_with_lse(ctypes.byref(p), A, None, A, A, 16384, 8192, A, None, A, A, A, A, A, None, A, A, A, A, need, None) == cd.EINVAL
+    assert L.calidrop_compress_with_lse(ctypes.byref(p), A, A, A, A, 16384, 8192, A, None, A, A, A, A, A, None, A, A, A, A, need - 1, None) == cd.EWORKSPACE
     # inconsistent sizes
     assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 100, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == cd.ESHAPE
     assert L.calidrop_compress(ctypes.byref(p), A, A, A, A, 3 * 8192, 8192, None, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == cd.ESHAPE      # batch*max < total

@@ -609,3 +609,39 @@ def test_decode_without_offsets_equals_decode_with_offsets(dtype, D, lens, budge
         torch.cuda.synchronize()
         assert torch.equal(bufs.out, want[0]) and torch.equal(bufs.a_lse, want[1]) and torch.equal(bufs.flags, want[2])
         bufs.append(*(torch.randn((len(lens), 2, D), generator=gen, device=DEV).to(bufs.k_c.dtype) for _ in range(2)))
+
+
+def window_lse_by_library(wl, x):
+    """[batch][Hq][w] fp32 log-sum-exp of the window rows over their causal span, by torch.logsumexp
+    on dense fp64 logits (what a prefill attention kernel would hand over)."""
+    G, w, D = wl.group, wl.window, wl.head_dim
+    out = torch.zeros((wl.batch, wl.n_q_heads, w), dtype=torch.float64)
+    for b in range(wl.batch):
+        n = wl.seq_lens[b]
+        if n < w:
+            continue
+        K = synth.seq_view(x["k"], wl, b).cpu().double()                    # [Hkv][n][D]
+        q = x["q_win"][b].cpu().double()                                    # [Hq][w][D]
+        S = torch.einsum("hwd,hnd->hwn", q, K.repeat_interleave(G, dim=0)) * D ** -0.5
+        col = torch.arange(n).view(1, 1, n)
+        row = torch.arange(w).view(1, w, 1)
+        out[b] = torch.logsumexp(S.masked_fill(col > n - w + row, float("-inf")), dim=-1)
+    return out.to(torch.float32).to(x["k"].device)
+
+
+@pytest.mark.parametrize("dtype,D,lens,w,B,m", [("fp32", 64, [700, 50, 1300], 16, 96, 0), ("bf16", 128, [2100, 9000], 32, 256, 0),
+                                                ("bf16", 64, [20000], 16, 300, 500), ("bf16", 128, [900], 12, 64, 0)])
+def test_compress_with_the_window_log_sum_exp_supplied(dtype, D, lens, w, B, m):
+    # pass 1 skipped: the normalisers come from the caller.  Exact ones reproduce the default call's
+    # result (same oracle, same protocol); ones that are off by per-row constants are used as given
+    wl = small(dtype, 8, 2, D, lens, w, B, 5, T=1, name="supplied_lse")
+    x = to_dev(synth.make_inputs(wl, 41))
+    lse = window_lse_by_library(wl, x)
+    bufs = H.gpu_compress(wl, x, win_lse=lse, calib_size=m)
+    for b in range(wl.batch):
+        H.check_compress(wl, x, bufs, b)
+    g = torch.Generator(device=DEV).manual_seed(3)
+    skew = lse + torch.randn(lse.shape, generator=g, device=DEV) * 0.7
+    bufs2 = H.gpu_compress(wl, x, win_lse=skew, calib_size=m)
+    for b in range(wl.batch):
+        H.check_compress(wl, x, bufs2, b, win_lse=skew)

@@ -145,6 +145,40 @@ def test_votes_last_window_row_sees_all_first_row_sees_P_plus_1():
     np.testing.assert_allclose(vote, np.full(P, expect), rtol=1e-9)
 
 
+def test_votes_with_supplied_row_lse():
+    # the rows' log-sum-exp from an independent routine (torch.logsumexp over the causal span)
+    # reproduces the self-normalised votes; an lse that is off by log 2 on one head halves that
+    # head's contribution and nothing else; uniform keys give the closed form exp(-delta)/(P+i+1)
+    G, w, D, n = 2, 6, 8, 45
+    P = n - w
+    q = RNG.standard_normal((G, w, D))
+    K = RNG.standard_normal((n, D)) * 1.5
+    S = torch.from_numpy(q) @ torch.from_numpy(K).T * 0.35
+    col = torch.arange(n).view(1, 1, n)
+    row = torch.arange(w).view(1, w, 1)
+    lse = torch.logsumexp(S.masked_fill(col > P + row, float("-inf")), dim=-1).numpy()      # [G][w]
+    base = ref.window_votes(q, K, w, 0.35)
+    np.testing.assert_allclose(ref.window_votes(q, K, w, 0.35, win_lse=lse), base, rtol=1e-12)
+    off = lse.copy()
+    off[1] += np.log(2.0)
+    head0 = ref.window_votes(q[:1], K, w, 0.35)
+    head1 = ref.window_votes(q[1:], K, w, 0.35)
+    np.testing.assert_allclose(ref.window_votes(q, K, w, 0.35, win_lse=off), head0 + 0.5 * head1, rtol=1e-12)
+    Ku = np.tile(RNG.standard_normal(D), (n, 1))
+    zu = 0.35 * q @ Ku[0]                                                                       # [G][w] the common logit
+    delta = RNG.standard_normal((G, w))
+    true_lse = zu + np.log(P + np.arange(w) + 1.0)
+    got = ref.window_votes(q, Ku, w, 0.35, win_lse=true_lse + delta)
+    expect = sum(np.exp(-delta[h, i]) / (P + i + 1) for h in range(G) for i in range(w))
+    np.testing.assert_allclose(got, np.full(P, expect), rtol=1e-12)
+    # compress passes it through: same retained set and calibration state as without it
+    V = RNG.standard_normal((1, n, D))
+    r0 = ref.compress(q, K[None], V, w, 16, 3, scale=0.35)
+    r1 = ref.compress(q, K[None], V, w, 16, 3, scale=0.35, win_lse=lse)
+    np.testing.assert_array_equal(r0["idx"], r1["idx"])
+    np.testing.assert_allclose(r0["c_out"], r1["c_out"], atol=1e-13)
+
+
 @pytest.mark.parametrize("k", [1, 3, 5, 7])
 @pytest.mark.parametrize("P", [1, 2, 5, 33])
 def test_avg_pool_matches_library(k, P):
