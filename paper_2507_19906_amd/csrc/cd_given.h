@@ -113,12 +113,7 @@ __global__ __launch_bounds__(256) void evict_list_kernel(PackArgs a) {
   int cnt = 0;
   for (int wd = w_lo; wd < w_hi; ++wd) cnt += __popc(clear_bits(wd));
   // exclusive scan over the 256 threads
-  int incl = cnt;
-#pragma unroll
-  for (int s = 1; s < 64; s <<= 1) {
-    const int up = __shfl_up(incl, s);
-    if (lane >= s) incl += up;
-  }
+  const int incl = static_cast<int>(wave_inclusive_scan(static_cast<uint32_t>(cnt)));
   __shared__ int s_wave[4];
   if (lane == 63) s_wave[wv] = incl;
   __syncthreads();

@@ -183,13 +183,9 @@ __device__ __forceinline__ void wide_pick(const u32x4 hb, int shift, uint32_t& p
   const int lane = threadIdx.x & 63;
   const uint32_t h0 = hb[0], h1 = hb[1], h2 = hb[2], h3 = hb[3];
   const uint32_t mine = h0 + h1 + h2 + h3;
-  uint32_t acc = mine;
-#pragma unroll
-  for (int sft = 1; sft < 64; sft <<= 1) {          // suffix-inclusive scan over lanes
-    const uint32_t o = __shfl_down(acc, sft);
-    if (lane + sft < 64) acc += o;
-  }
-  const uint32_t above = acc - mine;
+  const uint32_t upto = wave_inclusive_scan(mine);
+  const uint32_t above = last_lane(upto) - upto;      // keys in bins owned by higher lanes
+  const uint32_t acc = above + mine;
   const bool hit = above < remaining && remaining <= acc;
   uint32_t cum = above;
   int bin = 0;
@@ -386,12 +382,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_emit_kernel(WideArgs a) {
       cnt1 += (key[u] > c1.thr ? 1u : 0u) + (key[u] == c1.thr ? 0x10000u : 0u);
       cnt2 += (key[u] > c2.thr ? 1u : 0u) + (key[u] == c2.thr ? 0x10000u : 0u);
     }
-  uint32_t inc1 = cnt1, inc2 = cnt2;
-#pragma unroll
-  for (int sft = 1; sft < 64; sft <<= 1) {
-    const uint32_t o1 = __shfl_up(inc1, sft), o2 = __shfl_up(inc2, sft);
-    if (lane >= sft) { inc1 += o1; inc2 += o2; }
-  }
+  const uint32_t inc1 = wave_inclusive_scan(cnt1), inc2 = wave_inclusive_scan(cnt2);
   if (lane == 63) { wave_tot[0][wv] = inc1; wave_tot[1][wv] = inc2; }
   __syncthreads();
   uint32_t bef1 = inc1 - cnt1, bef2 = inc2 - cnt2;
