@@ -101,6 +101,7 @@ def machine_probes(dev, stream):
     path = os.path.join(os.path.dirname(os.path.abspath(paper_2507_19906_amd.__file__)), "libcalidrop_probes.so")
     L = ctypes.CDLL(path)
     L.calidrop_probe_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    L.calidrop_probe_stream_read_nt.argtypes = L.calidrop_probe_stream_read.argtypes
     L.calidrop_probe_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
     st = stream.cuda_stream or None
     buf = torch.ones(2 << 30, dtype=torch.uint8, device=dev)
@@ -109,19 +110,20 @@ def machine_probes(dev, stream):
     res = {}
     for label, nbytes, blocks, reps in (("64MiB", 64 << 20, 2048, 32), ("256MiB", 256 << 20, 8192, 16), ("2GiB", 2 << 30, 32768, 6)):
         nrot = (2 << 30) // nbytes                 # rotate through the buffer: never re-read cached data
-        def launch(r):
-            rc = L.calidrop_probe_stream_read(buf.data_ptr() + (r % nrot) * nbytes, nbytes, blocks, out.data_ptr(), st)
-            assert rc == 0
-        for r in range(3):
-            launch(r)
-        e0, e1 = ev(), ev()
-        e0.record(stream)
-        for r in range(reps):
-            launch(r + 3)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
-        res["stream_read_" + label] = {"us_per_launch": us, "GBps": nbytes / us / 1e3}
+        for kind, fn in (("", L.calidrop_probe_stream_read), ("_nontemporal", L.calidrop_probe_stream_read_nt)):
+            def launch(r):
+                rc = fn(buf.data_ptr() + (r % nrot) * nbytes, nbytes, blocks, out.data_ptr(), st)
+                assert rc == 0
+            for r in range(3):
+                launch(r)
+            e0, e1 = ev(), ev()
+            e0.record(stream)
+            for r in range(reps):
+                launch(r + 3)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            res["stream_read" + kind + "_" + label] = {"us_per_launch": us, "GBps": nbytes / us / 1e3}
     blocks, iters = 2048, 20000
     for _ in range(2):
         assert L.calidrop_probe_mfma_loop(out.data_ptr(), blocks, 2000, st) == 0

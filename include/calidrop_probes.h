@@ -20,6 +20,9 @@ extern "C" {
  * on its own contiguous slice).  bytes must be a multiple of 16 * blocks; `out`: blocks uint32. */
 int calidrop_probe_stream_read(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream);
 
+/* The same read issued as non-temporal loads (the hint for data that is not read again soon). */
+int calidrop_probe_stream_read_nt(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream);
+
 /* `blocks` workgroups of 4 waves; every wave executes iters * 8 independent-chain
  * v_mfma_f32_16x16x32_bf16 instructions (16384 flop each) and nothing else.  `out`: blocks * 256
  * floats.  Total flop = blocks * 4 * iters * 8 * 16384. */

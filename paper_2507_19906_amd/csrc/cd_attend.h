@@ -77,7 +77,7 @@ struct AttendWave {
       const int krow = min(row0 + 16 * g2 + i, rows - 1);
       const T* kp = kbase + static_cast<int64_t>(krow) * D + c * EPL;
 #pragma unroll
-      for (int kk = 0; kk < NK; ++kk) kf[g2][kk] = ld16(kp + kk * KD);
+      for (int kk = 0; kk < NK; ++kk) kf[g2][kk] = ld16_stream(kp + kk * KD);
     }
   }
 
@@ -87,7 +87,7 @@ struct AttendWave {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int vrow = min(row0 + 16 * (e >> 2) + 4 * c + (e & 3), rows - 1);
-      vf[e] = (i < D / 8) ? ld16(vbase + static_cast<int64_t>(vrow) * D + i * 8) : zero16();
+      vf[e] = (i < D / 8) ? ld16_stream(vbase + static_cast<int64_t>(vrow) * D + i * 8) : zero16();
     }
   }
 
@@ -151,7 +151,8 @@ struct AttendWave {
   __device__ __forceinline__ static void load_z(const float* zhead, int row0, int c, bool valid, f32x4 (&z)[2]) {
 #pragma unroll
     for (int g2 = 0; g2 < 2; ++g2)
-      z[g2] = valid ? *reinterpret_cast<const f32x4*>(zhead + row0 + 16 * g2 + 4 * c) : f32x4{0.f, 0.f, 0.f, 0.f};
+      z[g2] = valid ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(zhead + row0 + 16 * g2 + 4 * c))
+                    : f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
   // kLogits: the logits come from `zhead` (this lane's head, log2 units) instead of K Q^T.
@@ -208,7 +209,7 @@ struct AttendWave {
           const float pe = p[e >> 2][e & 3];
 #pragma unroll
           for (int dh = 0; dh < D / 64; ++dh) {
-            u32x4 v4 = ld16(vbase + static_cast<int64_t>(vrow) * D + (i + 16 * dh) * 4);
+            u32x4 v4 = ld16_stream(vbase + static_cast<int64_t>(vrow) * D + (i + 16 * dh) * 4);
 #pragma unroll
             for (int xx = 0; xx < 4; ++xx)
               acc_o[dh * 4 + xx] =

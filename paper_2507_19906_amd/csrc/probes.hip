@@ -12,13 +12,18 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
 // Every workgroup reads its own contiguous slice, 16 bytes per lane, 8 loads in flight per lane.
+// kNonTemporal: the loads carry the non-temporal hint (data that is not read again soon).
+template <bool kNonTemporal>
 __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ p, uint64_t vec_per_block, uint32_t* out) {
   const u32x4* q = p + static_cast<uint64_t>(blockIdx.x) * vec_per_block;
   u32x4 acc = {0u, 0u, 0u, 0u};
   for (uint64_t i = threadIdx.x; i < vec_per_block; i += 256 * 8) {
     u32x4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = (i + u * 256 < vec_per_block) ? q[i + u * 256] : u32x4{0u, 0u, 0u, 0u};
+    for (int u = 0; u < 8; ++u) {
+      v[u] = u32x4{0u, 0u, 0u, 0u};
+      if (i + u * 256 < vec_per_block) v[u] = kNonTemporal ? __builtin_nontemporal_load(q + i + u * 256) : q[i + u * 256];
+    }
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc ^= v[u];
   }
@@ -51,7 +56,15 @@ extern "C" {
 // needs `blocks` uint32.  Returns 0, or -1 on bad arguments / launch failure.
 int calidrop_probe_stream_read(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream) {
   if (!buf || !out || blocks < 1 || bytes == 0 || bytes % (16ull * blocks) != 0) return -1;
-  hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+  hipLaunchKernelGGL(stream_read_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4*>(buf), bytes / 16 / blocks, static_cast<uint32_t*>(out));
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// The same read with non-temporal loads.
+int calidrop_probe_stream_read_nt(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream) {
+  if (!buf || !out || blocks < 1 || bytes == 0 || bytes % (16ull * blocks) != 0) return -1;
+  hipLaunchKernelGGL(stream_read_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(buf), bytes / 16 / blocks, static_cast<uint32_t*>(out));
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }

@@ -232,7 +232,7 @@ def test_probe_library_exports_its_header():
     hdr = open(os.path.join(ROOT, "include", "calidrop_probes.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(calidrop_probe_[a-z_]+)\s*\(", hdr))
-    assert names == {"calidrop_probe_stream_read", "calidrop_probe_mfma_loop"}
+    assert names == {"calidrop_probe_stream_read", "calidrop_probe_stream_read_nt", "calidrop_probe_mfma_loop"}
     L = ctypes.CDLL(os.path.join(ROOT, "paper_2507_19906_amd", "libcalidrop_probes.so"))
     for n in names:
         assert hasattr(L, n), n
