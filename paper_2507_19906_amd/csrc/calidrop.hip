@@ -248,6 +248,9 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   sa.batch = p->batch; sa.Hq = p->n_q_heads; sa.Hkv = p->n_kv_heads; sa.G = G; sa.w = p->window;
   sa.B = p->budget; sa.R = G * p->window; sa.NRB = L.NRB; sa.NCH = L.NCH; sa.max_seq_len = max_seq_len;
   sa.pool_k = p->pool_kernel; sa.sl2 = sl2; sa.chunk_keys = L.chunk_keys;
+  // K of the whole call well inside the 256 MB last-level cache: pass 1 reads it with cached loads so
+  // that pass 2 finds it there; larger calls stream it both times
+  sa.keep_k = static_cast<int64_t>(total_tokens) * p->n_kv_heads * D * static_cast<int64_t>(sizeof(T)) <= (160ll << 20);
   sa.rowpart = reinterpret_cast<float2*>(ws + L.rowpart);
   sa.row_lse = reinterpret_cast<float*>(ws + L.row_lse);
   sa.vote = reinterpret_cast<float*>(ws + L.vote);

@@ -28,6 +28,7 @@ struct ScoreArgs {
   int batch, Hq, Hkv, G, w, B, R, NRB, NCH, max_seq_len, pool_k;
   int chunk_keys;       // keys per workgroup (multiple of 64); each wave takes chunk_keys/4 contiguous keys
   float sl2;            // scale * log2(e)
+  int keep_k;           // pass 1 leaves K in the last-level cache for pass 2 (K of the whole call fits it)
   float2* rowpart;      // [batch*Hkv*NRB*128][NCH] (max, sum) per chunk
   float* row_lse;       // [batch*Hkv*NRB*128] log2-domain row log-sum-exp
   float* vote;          // [NRB][total_tokens*Hkv]
@@ -71,20 +72,27 @@ struct KeyStream {
   // registers of one in-flight stage
   struct Regs { u32x4 v[NLD]; };
 
-  __device__ __forceinline__ static void load(Regs& r, const T* kbase, int key0, int n) {
+  // keep: the stream is read again soon and fits the last-level cache (cached loads); otherwise
+  // the loads are non-temporal
+  __device__ __forceinline__ static void load(Regs& r, const T* kbase, int key0, int n, bool keep = false) {
     const char* base = reinterpret_cast<const char*>(kbase);
     if (key0 + kStageKeys <= n) {
       // whole stage in range: rows are contiguous, so slot order is memory order - one uniform
       // base per stage plus a per-thread constant, no per-load address arithmetic
-      const char* sbase = base + static_cast<int64_t>(key0) * (CH * 16);
+      const char* sbase = base + static_cast<int64_t>(key0) * (CH * 16) + threadIdx.x * 16;
+      if (keep) {
 #pragma unroll
-      for (int u = 0; u < NLD; ++u) r.v[u] = ld16_stream(sbase + u * 4096 + threadIdx.x * 16);
+        for (int u = 0; u < NLD; ++u) r.v[u] = ld16(sbase + u * 4096);
+      } else {
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) r.v[u] = ld16_stream(sbase + u * 4096);
+      }
     } else {
 #pragma unroll
       for (int u = 0; u < NLD; ++u) {
         const int slot = threadIdx.x + u * 256;        // (key, chunk) in row-major order
         const int key = min(key0 + slot / CH, n - 1);  // the tail repeats the last row
-        r.v[u] = ld16_stream(base + static_cast<int64_t>(key) * (CH * 16) + (slot % CH) * 16);
+        r.v[u] = ld16(base + static_cast<int64_t>(key) * (CH * 16) + (slot % CH) * 16);
       }
     }
   }
@@ -203,8 +211,8 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
   float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
 
   typename KS::Regs r0, r1;
-  KS::load(r0, kbase, key_base, n);
-  if (nstages > 1) KS::load(r1, kbase, key_base + SK, n);
+  KS::load(r0, kbase, key_base, n, a.keep_k != 0);
+  if (nstages > 1) KS::load(r1, kbase, key_base + SK, n, a.keep_k != 0);
   KS::store(r0, s_k[0]);
   __syncthreads();
 
@@ -289,13 +297,13 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
 
   for (int s = 0; s < nstages; s += 2) {
     // even stage: buffer 0 holds stage s; r1 holds (or is receiving) stage s+1
-    if (s + 2 < nstages) KS::load(r0, kbase, key_base + (s + 2) * SK, n);
+    if (s + 2 < nstages) KS::load(r0, kbase, key_base + (s + 2) * SK, n, a.keep_k != 0);
     compute(s_k[0], key_base + s * SK);
     if (s + 1 < nstages) KS::store(r1, s_k[1]);
     __syncthreads();
     if (s + 1 >= nstages) break;
     // odd stage: buffer 1 holds stage s+1; r0 holds stage s+2
-    if (s + 3 < nstages) KS::load(r1, kbase, key_base + (s + 3) * SK, n);
+    if (s + 3 < nstages) KS::load(r1, kbase, key_base + (s + 3) * SK, n, a.keep_k != 0);
     compute(s_k[1], key_base + (s + 1) * SK);
     if (s + 2 < nstages) KS::store(r0, s_k[0]);
     __syncthreads();
