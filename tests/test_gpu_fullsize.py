@@ -45,8 +45,8 @@ def test_config3_stack_32_layers_budget_512():
 
 @pytest.mark.parametrize("budget", [128, 2048])
 def test_config3_other_budgets(budget):
-    wl = synth.config(3, layers=8, budget=budget, decode_steps=2)
-    sampled(wl, [(5, 3), (0, 0)])
+    wl = synth.config(3, layers=32, budget=budget, decode_steps=2)       # the stack bench.py times these budgets on
+    sampled(wl, [(5, 3), (30, 0)])
 
 
 def test_config4_batch64_varlen():
