@@ -62,6 +62,8 @@ def test_config2_bf16_llama8b_8k():
     small("bf16", 64, 8, 128, [2100], 32, 512, 7, T=2, name="g8_llama70b_like"),
     small("fp32", 10, 2, 64, [640], 16, 96, 5, name="g5_fp32"),
     small("bf16", 6, 1, 64, [999], 8, 60, 3, name="g6_d64"),
+    small("bf16", 16, 1, 64, [1500, 90], 16, 200, 5, name="g16_largest_group"),
+    small("fp32", 32, 2, 128, [700], 8, 100, 3, T=2, name="g16_fp32_d128"),
     small("bf16", 8, 2, 128, [20000, 300, 8300], 32, 1024, 17, T=2, name="multi_workgroup_select_bf16"),
     small("fp32", 4, 2, 64, [16500], 16, 200, 21, T=2, name="multi_workgroup_select_fp32"),
     # longest prefix one workgroup selects over (32768 positions), heads starting 1, 2 and 3 floats
