@@ -335,7 +335,7 @@ int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, cons
     const size_t lds_per_wave = static_cast<size_t>(G) * (D + 2) * sizeof(float);
     // 8 waves per workgroup for mid-sized caches (one or two tiles per wave) and whenever the pairs
     // do not fill the chip: with 1024 rows or more and enough pairs, 4-wave workgroups - three of which fit a compute unit, so that one's merge overlaps the
-    // others' streaming - measured 1-2 % faster (256 MiB per call: 5.79 vs 5.70 TB/s)
+    // others' streaming - measured 2-4 % faster (256 MiB per call: 6.6 vs 6.3 TB/s)
     const bool many_pairs = p->batch * p->n_kv_heads >= kFusedMinPairs;
     int nw = (tiles <= 4 || (tiles >= 32 && many_pairs)) ? 4 : 8;
     while (nw > 4 && nw * lds_per_wave > 64 * 1024) nw /= 2;
