@@ -105,6 +105,16 @@ def test_bad_struct_size_null_align_workspace():
                              None) == cd.ESHAPE
     assert L.calidrop_decode(ctypes.byref(p), A, A, A, A, A, 512, A, A, A, None, None, None, A,
                              needd, None) == cd.EINVAL
+    # cache_offsets may be NULL (uniform capacity): validation goes on to the next check ...
+    assert L.calidrop_decode(ctypes.byref(p), A, A, A, None, A, 512, A, A, A, A, None, None, A,
+                             needd - 1, None) == cd.EWORKSPACE
+    assert L.calidrop_decode(ctypes.byref(p), A, A, A, A + 4, A, 512, A, A, A, A, None, None, A,
+                             needd, None) == cd.EALIGN
+    # ... unless the implied token offsets batch * max_cache_len leave the int32 range
+    big = good(batch=4096)
+    assert L.calidrop_decode(ctypes.byref(big), A, A, A, None, A, 1 << 20, A, A, A, A, None, None, A,
+                             1 << 40, None) == cd.EUNSUPPORTED
+    assert "uniform" in cd.calidrop_last_error()
     with pytest.raises(cd.CalidropError):
         cd.calidrop_compress_workspace_bytes(good(head_dim=100), 16384, 8192)
     # recalibrate
