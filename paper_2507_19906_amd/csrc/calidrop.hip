@@ -271,7 +271,7 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
     } else {
       hipLaunchKernelGGL((cd::score_rowstats_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
       if ((rc = launch_status("score_rowstats"))) return rc;
-      hipLaunchKernelGGL(cd::rowstats_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, sa);
+      hipLaunchKernelGGL(cd::rowstats_merge_kernel, dim3(static_cast<unsigned>((rows + 255) / 256)), dim3(256), 0, st, sa);
       if ((rc = launch_status("rowstats_merge"))) return rc;
     }
     hipLaunchKernelGGL((cd::score_votes_kernel<T, D>), grid_s, dim3(256), 0, st, sa);

@@ -319,10 +319,10 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
   }
 }
 
-// One wave per query row: merge its chunk partials into the log2-domain row log-sum-exp.
+// One thread per query row: merge its chunk partials, in chunk order, into the log2-domain row
+// log-sum-exp.
 __global__ __launch_bounds__(256) void rowstats_merge_kernel(ScoreArgs a) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int64_t gr = static_cast<int64_t>(blockIdx.x) * 4 + wv;
+  const int64_t gr = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   const int64_t rows_total = static_cast<int64_t>(a.batch) * a.Hkv * a.NRB * kRowBlock;
   if (gr >= rows_total) return;
   const int y = static_cast<int>(gr / kRowBlock);
@@ -331,15 +331,15 @@ __global__ __launch_bounds__(256) void rowstats_merge_kernel(ScoreArgs a) {
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   if (n <= a.B) return;
   const int nch = (n + a.chunk_keys - 1) / a.chunk_keys;
+  // (a row's partials share a cache line or two: after the first load the rest are cache hits)
+  const float2* part = a.rowpart + gr * a.NCH;
   float m = -INFINITY, l = 0.f;
-  for (int ch = lane; ch < nch; ch += 64) {
-    float2 v = a.rowpart[gr * a.NCH + ch];
+  for (int ch = 0; ch < nch; ++ch) {
+    const float2 v = part[ch];
     merge_ml(m, l, v.x, v.y);
   }
-#pragma unroll
-  for (int s = 1; s < 64; s <<= 1) merge_ml(m, l, __shfl_xor(m, s), __shfl_xor(l, s));
   const int rho = (y % a.NRB) * kRowBlock + static_cast<int>(gr % kRowBlock);    // row inside the KV head
-  if (lane == 0) a.row_lse[gr] = (l > 0.f && rho < a.R) ? m + fast_log2(l) : INFINITY;   // padding rows: +inf
+  a.row_lse[gr] = (l > 0.f && rho < a.R) ? m + fast_log2(l) : INFINITY;          // padding rows: +inf
 }
 
 // The row log-sum-exp taken from the caller instead of pass 1: win_lse [batch][Hq][w] holds, in
