@@ -184,6 +184,23 @@ __device__ __forceinline__ float col4_sum(float x) {
 // Sum over all 64 lanes, every lane ends with the same bits (fixed tree: inside rows of 16, then across).
 __device__ __forceinline__ float wave_sum(float x) { return col4_sum(row16_sum(x)); }
 
+// Workgroups are dealt to the 8 XCDs (each with its own L2) round-robin in launch order.  For a
+// grid of (blocks, heads) whose heads divide by 8, this re-reads the launch index so that every
+// XCD works through whole heads, the blocks of a head one after the other: the workgroups that
+// stream the same operand at the same time then share one L2 instead of every L2 fetching the
+// stream for itself.  vx in [0, gridDim.x), vh in [0, gridDim.y * gridDim.z); a bijection.
+__device__ __forceinline__ void xcd_head_major(int& vx, int& vh) {
+  vx = static_cast<int>(blockIdx.x);
+  vh = static_cast<int>(blockIdx.y + gridDim.y * blockIdx.z);
+  const int gx = static_cast<int>(gridDim.x), H = static_cast<int>(gridDim.y * gridDim.z);
+  if (H % 8 == 0) {
+    const int L = vx + gx * vh;
+    const int slot = L / 8;
+    vx = slot % gx;
+    vh = (L % 8) * (H / 8) + slot / gx;
+  }
+}
+
 // Three-input maximum in one instruction (operands are never NaN here, so no canonicalisation).
 __device__ __forceinline__ float max3(float a, float b, float c) {
   float d;

@@ -39,17 +39,19 @@ __global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
   using KS = KeyStream<T, D>;
   constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys, EPL = KS::EPL, KD = KS::KD;
   constexpr int WR = 16 * RT, BR = 4 * WR;
-  const int hq = blockIdx.y % a.Hq, b = blockIdx.y / a.Hq, g = hq / a.G;
+  int vx, vh;                                    // row block and (sequence, query head) of this workgroup
+  xcd_head_major(vx, vh);
+  const int hq = vh % a.Hq, b = vh / a.Hq, g = hq / a.G;
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   const T* qbase = static_cast<const T*>(a.q_full) + (static_cast<int64_t>(off0) * a.Hq + static_cast<int64_t>(hq) * n) * D;
   // Q_{-1} of this head, the calibration query of Alg. 1 step 5 (also for prompts within the budget)
-  if (blockIdx.x == 0 && n > 0 && threadIdx.x < D)
+  if (vx == 0 && n > 0 && threadIdx.x < D)
     store_elem<T>(static_cast<T*>(a.q_last), static_cast<int64_t>(b * a.Hq + hq) * D + threadIdx.x,
                   load_elem<T>(qbase, static_cast<int64_t>(n - 1) * D + threadIdx.x));
   if (n <= a.B) return;
   const int nrb = (n + BR - 1) / BR;
-  const int rbp = nrb - 1 - static_cast<int>(blockIdx.x);      // late rows (most keys) are launched first
+  const int rbp = nrb - 1 - vx;                  // late rows (most keys) are launched first
   if (rbp < 0) return;
   const int i0 = rbp * BR;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -184,7 +186,9 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
   // rows, late keys by few, so every workgroup gets the same amount of work), y = (sequence, KV
   // head), z = query head of the group; each query head writes its own plane of votes, which
   // the selection adds up in a fixed order.
-  const int bg = blockIdx.y, hh = blockIdx.z;
+  int vx, vh;                                    // block pair and ((sequence, KV head), head in group) of this workgroup
+  xcd_head_major(vx, vh);
+  const int bg = vh / static_cast<int>(gridDim.z), hh = vh % static_cast<int>(gridDim.z);   // a group's heads side by side
   const int g = bg % a.Hkv, b = bg / a.Hkv;
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
@@ -205,9 +209,9 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
   ks.init();
 
   for (int job = 0; job < 2; ++job) {
-    const int blk = job == 0 ? static_cast<int>(blockIdx.x) : nblk - 1 - static_cast<int>(blockIdx.x);
+    const int blk = job == 0 ? vx : nblk - 1 - vx;
     // uniform over the workgroup: the first half of the blocks as job 0, their mirrors as job 1
-    if (job == 0 ? 2 * blk >= nblk : (blk < 0 || blk <= static_cast<int>(blockIdx.x))) continue;
+    if (job == 0 ? 2 * blk >= nblk : (blk < 0 || blk <= vx)) continue;
     const int j0 = blk * BR;
     const int wkey0 = j0 + wv * WR;                // first key of this wave
     u32x4 kf[RT][NK];
