@@ -269,7 +269,7 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
     if (!any) return;
   }
   const int row_end = min(rows, row_begin + a.rows_per_split);
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wv = wave_index();
   const int i = lane & 15, c = lane >> 4;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * head_stride;
   const T* kbase = static_cast<const T*>(a.k) + head_tok * D;
@@ -333,7 +333,7 @@ struct FinalArgs {
 __device__ __forceinline__ float block_sum(float x, float* red, int nthreads) {
   // sum over the workgroup (nthreads = 64 or 128), fixed order; result in every thread
   x = wave_sum(x);
-  const int wv = threadIdx.x >> 6;
+  const int wv = wave_index();
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[wv] = x;
   __syncthreads();
@@ -490,7 +490,7 @@ __device__ __forceinline__ float cosine_of(const float (&q)[N], const float (&cv
 template <typename T, int D, int NW>
 __global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fused_kernel(DecodeFusedArgs a) {
   const int g = blockIdx.x, b = blockIdx.y;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wv = wave_index();
   const int i = lane & 15, c = lane >> 4;
   // row_off == NULL: every sequence has capacity max_len and starts at b * max_len, so the K/V
   // addresses need no load and the first K tile can be requested before row_len[b] has arrived

@@ -34,6 +34,14 @@ template <> struct Elem<float> {
   static constexpr int kStepK = 16;
 };
 
+// Index of the calling wave inside its workgroup, as a value the compiler knows to be the same in
+// every lane: what is derived from it (tile ranges, "is this stage fully visible" flags, LDS buffer
+// addresses) then lives in scalar registers and branches on it are scalar branches, instead of
+// per-lane arithmetic and exec-masked execution of both sides.
+__device__ __forceinline__ int wave_index() {
+  return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+}
+
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 // The same for data that is read once and not again soon (the K/V streams): a non-temporal load,
 // which leaves the caches to data that is reused (measured on the decode stream of a 256 MiB

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void evict_list_kernel(PackArgs a) {
   const int bg = blockIdx.x;
   const int g = bg % a.Hkv;
   const int b = bg / a.Hkv;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wv = wave_index();
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   const int e0 = a.evict_off[b];

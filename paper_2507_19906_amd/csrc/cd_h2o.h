@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void h2o_rowlse_kernel(H2oArgs a) {
   const int rbp = nrb - 1 - vx;                  // late rows (most keys) are launched first
   if (rbp < 0) return;
   const int i0 = rbp * BR;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wv = wave_index();
   const int i = lane & 15, c = lane >> 4;
   const T* kbase = static_cast<const T*>(a.k) + (static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n) * D;
   const int wrow0 = i0 + wv * WR;                // first row of this wave
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   if (n <= a.B) return;
   const int nblk = (n + BR - 1) / BR;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wv = wave_index();
   const int i = lane & 15, c = lane >> 4;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
   const T* kbase = static_cast<const T*>(a.k) + head_tok * D;

@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void score_rowstats_kernel(ScoreArgs a) {
   const int key_end = min(n, key_base + a.chunk_keys);
   const int nstages = (key_end - key_base + SK - 1) / SK;
   const int P = n - a.w;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wv = wave_index();
   const int i = lane & 15, c = lane >> 4;
   const T* kbase = static_cast<const T*>(a.k) + (static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n) * D;
 
@@ -384,7 +384,7 @@ __global__ __launch_bounds__(256, sizeof(T) == 2 ? CD_VOTES_WAVES : 2) void scor
   if (key_base >= P) return;
   const int key_end = min(P, key_base + a.chunk_keys);
   const int nstages = (key_end - key_base + SK - 1) / SK;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wv = wave_index();
   const int i = lane & 15, c = lane >> 4;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
   const T* kbase = static_cast<const T*>(a.k) + head_tok * D;

@@ -54,7 +54,7 @@ struct RadixShared {
 template <int NT, typename ForEach>
 __device__ __forceinline__ void radix_select(RadixShared& sh, uint32_t rank, ForEach&& for_each_key, uint32_t& thr,
                                              uint32_t& need_eq) {
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wv = wave_index();
   uint32_t prefix = 0;            // bits decided so far (the high bits of the answer)
   uint32_t remaining = rank;      // rank of the answer among the keys matching `prefix`
 #pragma unroll
@@ -286,7 +286,7 @@ __device__ __forceinline__ void wide_cuts(const WideArgs& a, const WideHead& h, 
 
 // Sum over the workgroup of four counters; result in every thread.  `red` holds 4 x 4 words.
 __device__ __forceinline__ void wide_block_sum4(uint32_t (&v)[4], uint32_t (*red)[4]) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wv = wave_index();
 #pragma unroll
   for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_emit_kernel(WideArgs a) {
   const WideHead h = wide_head(s, blockIdx.y);
   const int seg = blockIdx.x;
   const int lo = seg * kWideSeg;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wv = wave_index();
   int32_t* idx = s.indices + static_cast<int64_t>(h.bg) * s.B;
   int32_t* cal = (s.cal_indices && s.calib > 0) ? s.cal_indices + static_cast<int64_t>(h.bg) * s.calib : nullptr;
   if (seg == 0 && h.g == 0 && tid == 0) s.cache_lens[h.b] = min(h.n, s.B);
@@ -447,7 +447,7 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
   const int bg = blockIdx.x;
   const int g = bg % a.Hkv;
   const int b = bg / a.Hkv;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wv = wave_index();
   int off0;
   const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
   int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
