@@ -30,8 +30,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per decode launch measured with rocprofv3 counters on the default workload
-# (profiles/bench_cfg3_B512_pmc_hbm_bytes.md): FETCH_SIZE 33565.4 KiB x 2.0 + WRITE_SIZE 272 KiB x 1.0
-DECODE_TRAFFIC_BYTES_PMC = 69020565
+# (profiles/bench_cfg3_B512_pmc_hbm_bytes.md): FETCH_SIZE 33597.4 KiB x 2.0 + WRITE_SIZE 272 KiB x 1.0
+DECODE_TRAFFIC_BYTES_PMC = 69085933
 
 
 def decode_bytes(wl, cache_len: int) -> int:
