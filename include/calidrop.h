@@ -18,8 +18,8 @@
  *   - All data pointers are DEVICE pointers owned by the caller (for example a torch
  *     tensor's data_ptr(); the one exception is stated at calidrop_recalibrate_packed); they
  *     must stay alive until `stream` has executed the enqueued work.  `p` and the returned strings are HOST memory.  The library keeps no pointer
- *     after a call returns; its only state is a thread-local error string and the
- *     process-wide inspection switch below.
+ *     after a call returns and has no process-wide switches: its only state is a thread-local
+ *     error string.
  *   - Calls validate their arguments on the host first (no HIP call is made before
  *     validation passes), then enqueue kernels on `stream` (a hipStream_t; NULL = default
  *     stream) and return without synchronising.  They never allocate or free device memory.
@@ -68,8 +68,9 @@ enum {
 };
 
 typedef struct {
-  uint32_t struct_size; /* = sizeof(calidrop_params); also accepted: 48, the layout without
-                           calib_size (calib_size is then 0)                                  */
+  uint32_t struct_size; /* = sizeof(calidrop_params); also accepted: 52, the layout without
+                           flags, and 48, the layout without calib_size and flags (the missing
+                           fields are then 0)                                                 */
   int32_t dtype;        /* calidrop_dtype                                                   */
   int32_t batch;        /* sequences; a stack of layers is passed as batch = layers * seqs   */
   int32_t n_q_heads;    /* Hq                                                               */
@@ -85,7 +86,20 @@ typedef struct {
                            of highest pooled score (ties to the lower position) form the
                            calibration / offload set, the others are dropped; 0 = every evicted
                            token                                                              */
+  uint32_t flags;       /* per-call options, an OR of CALIDROP_OPT_* (0 = none)               */
 } calidrop_params;
+
+/* Per-call options in calidrop_params.flags.  They change how a compress call works, never what
+ * it returns.
+ *   CALIDROP_OPT_WRITE_SCORES    also store the pooled scores in the SCORE workspace region for every
+ *                                sequence (otherwise that region is only written for prompts too long
+ *                                for the in-LDS selection); costs one extra pass of stores.  For
+ *                                inspection by tests and tools.
+ *   CALIDROP_OPT_WIDE_SELECTION  run the per-head top-k as the multi-workgroup chain of launches for
+ *                                every call (normally only prompts longer than 32768, or pooling widths
+ *                                above 15, take it).  Same results (integer selection); for tests and
+ *                                tuning.                                                             */
+enum { CALIDROP_OPT_WRITE_SCORES = 1u, CALIDROP_OPT_WIDE_SELECTION = 2u };
 
 /* Bytes of device workspace calidrop_compress needs for these shapes (0 on invalid params).
  * total_tokens = sum of prompt lengths, max_seq_len = longest prompt.                       */
@@ -95,19 +109,8 @@ size_t calidrop_compress_workspace_bytes(const calidrop_params* p, int64_t total
 /* Bytes of device workspace calidrop_decode needs (0 on invalid params).                     */
 size_t calidrop_decode_workspace_bytes(const calidrop_params* p, int32_t max_cache_len);
 
-/* Inspection switch (process-wide, default off).  When on, calidrop_compress also stores the
- * pooled scores in the SCORE workspace region for every sequence; when off that region is only
- * written for prompts too long for the in-LDS selection.  Costs one extra pass of stores.      */
-void calidrop_set_inspection(int enabled);
-
-/* Selection variant switch (process-wide, default off).  The per-head top-k normally runs as one
- * workgroup per head and switches to the multi-workgroup chain of launches only for prompts longer
- * than 32768 (or pooling widths above 15); when on, the multi-workgroup chain is used for every
- * call.  Same results either way (integer selection); for tests and tuning.                     */
-void calidrop_set_wide_selection(int enabled);
-
 /* Named regions inside the compress workspace, for inspection by tests and tools after the
- * stream has finished (SCORE needs calidrop_set_inspection(1) before the compress call).
+ * stream has finished (SCORE needs CALIDROP_OPT_WRITE_SCORES in the compress call's params).
  * Layouts:
  *   ROW_LSE   float [batch][Hkv][NRB*128]: per window-query row, log2 of its softmax
  *             denominator over all visible keys (logits in log2 units); rows of a KV head are
@@ -332,7 +335,7 @@ size_t calidrop_compress_h2o_workspace_bytes(const calidrop_params* p, int32_t n
  *           (logits in log2 units), stride = bytes / (batch * Hq * 4) >= max_seq_len, +inf padded;
  *   SCORE   float, packed like K with D = 1: vote of position j of KV head g of sequence b at
  *           [seq_offsets[b]*Hkv + g*n_b + j], for the candidates j < n_b - n_local (needs
- *           calidrop_set_inspection(1) before the call unless the prompt is longer than 32768);
+ *           CALIDROP_OPT_WRITE_SCORES in the call's params unless the prompt is longer than 32768);
  *   VOTE_PLANES float [G][total_tokens*Hkv] (H2O only): plane hh holds, packed like SCORE and for
  *           every position j < n_b, the probability mass position j received from the queries
  *           of query head hh of its group; the score is the sum of the G planes.                  */

@@ -11,13 +11,13 @@ from typing import Optional
 import torch
 
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-# CALIDROP_LIB selects another build of the same library (e.g. a tuning variant)
-LIB_PATH = os.environ.get("CALIDROP_LIB") or os.path.join(_PKG_DIR, "libcalidrop.so")
+LIB_PATH = os.path.join(_PKG_DIR, "libcalidrop.so")
 
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6
 BF16, FP32 = 0, 1
 FLAG_NONE, FLAG_CALIBRATED, FLAG_RECOMPUTE, FLAG_RECOMPUTED = 0, 1, 2, 3
 REGION_ROW_LSE, REGION_SCORE, REGION_VOTE_PLANES = 0, 1, 2
+OPT_WRITE_SCORES, OPT_WIDE_SELECTION = 1, 2
 
 
 class CalidropError(RuntimeError):
@@ -42,17 +42,18 @@ class Params(ctypes.Structure):
         ("theta1", ctypes.c_float),
         ("theta2", ctypes.c_float),
         ("calib_size", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
     ]
 
 
 def make_params(*, dtype, batch, n_q_heads, n_kv_heads, head_dim, window, budget, pool_kernel,
-                scale=0.0, theta1=0.7, theta2=0.85, calib_size=0) -> Params:
+                scale=0.0, theta1=0.7, theta2=0.85, calib_size=0, flags=0) -> Params:
     if isinstance(dtype, torch.dtype):
         dtype = BF16 if dtype == torch.bfloat16 else FP32
     elif isinstance(dtype, str):
         dtype = BF16 if dtype == "bf16" else FP32
     return Params(ctypes.sizeof(Params), dtype, batch, n_q_heads, n_kv_heads, head_dim, window,
-                  budget, pool_kernel, scale, theta1, theta2, calib_size)
+                  budget, pool_kernel, scale, theta1, theta2, calib_size, flags)
 
 
 _lib = None
@@ -73,10 +74,6 @@ def lib() -> ctypes.CDLL:
         L.calidrop_last_error.argtypes = []
         L.calidrop_version.restype = ctypes.c_int
         L.calidrop_version.argtypes = []
-        L.calidrop_set_inspection.restype = None
-        L.calidrop_set_inspection.argtypes = [ctypes.c_int]
-        L.calidrop_set_wide_selection.restype = None
-        L.calidrop_set_wide_selection.argtypes = [ctypes.c_int]
         L.calidrop_compress_workspace_bytes.restype = sz
         L.calidrop_compress_workspace_bytes.argtypes = [pp, i64, i32]
         L.calidrop_decode_workspace_bytes.restype = sz
@@ -130,14 +127,6 @@ def lib() -> ctypes.CDLL:
 
 def calidrop_last_error() -> str:
     return lib().calidrop_last_error().decode()
-
-
-def calidrop_set_inspection(enabled: bool) -> None:
-    lib().calidrop_set_inspection(1 if enabled else 0)
-
-
-def calidrop_set_wide_selection(enabled: bool) -> None:
-    lib().calidrop_set_wide_selection(1 if enabled else 0)
 
 
 def _check(status: int) -> None:
@@ -325,12 +314,14 @@ class EvictedStore:
     `host=True` moves the packed rows to page-locked host memory after packing (the offloaded
     form); recalibrate() then reads them from there."""
 
-    def __init__(self, bufs: "CompressBuffers", seq_lens, host: bool = False):
+    def __init__(self, bufs: "CompressBuffers", seq_lens, host: bool = False, extra_rows=None):
         p = bufs.p
         dev = bufs.out.device
         dt = torch.bfloat16 if p.dtype == BF16 else torch.float32
         rows = [calidrop_packed_rows(p, int(n)) for n in seq_lens]
         caps = [max(r, 1) for r in rows]                      # every sequence owns at least one row slot
+        if extra_rows is not None:                            # slack behind each sequence's rows
+            caps = [c + int(e) for c, e in zip(caps, extra_rows)]
         offs = [0]
         for c in caps:
             offs.append(offs[-1] + c)
@@ -382,20 +373,29 @@ class EvictedStore:
 # ---- device-memory plumbing (allocation only) ----------------------------------------------
 class CompressBuffers:
     """Output and workspace tensors for calidrop_compress / calidrop_decode, allocated with
-    torch on `device`.  cache capacity per sequence = budget + extra_capacity."""
+    torch on `device`.  Cache capacity per sequence = budget + extra_capacity, or, with
+    `capacities` (one row count per sequence, each >= min(budget, n_b)), exactly those: the
+    compressed caches are then packed back to back behind cache_offsets with no slack."""
 
-    def __init__(self, p: Params, seq_lens, device, extra_capacity: int = 0):
+    def __init__(self, p: Params, seq_lens, device, extra_capacity: int = 0, capacities=None):
         dt = torch.bfloat16 if p.dtype == BF16 else torch.float32
         self.p = p
         B, Hq, Hkv, D, nb = p.budget, p.n_q_heads, p.n_kv_heads, p.head_dim, p.batch
         assert len(seq_lens) == nb
         self.total_tokens = int(sum(seq_lens))
         self.max_seq_len = int(max(seq_lens))
-        cap = B + extra_capacity
-        self.cap = cap
-        self.cache_offsets = torch.arange(0, (nb + 1) * cap, cap, dtype=torch.int32, device=device)
-        self.k_c = torch.zeros(nb * Hkv * cap * D, dtype=dt, device=device)
-        self.v_c = torch.zeros(nb * Hkv * cap * D, dtype=dt, device=device)
+        caps = [B + extra_capacity] * nb if capacities is None else [int(c) for c in capacities]
+        assert len(caps) == nb
+        offs = [0]
+        for c in caps:
+            offs.append(offs[-1] + c)
+        self.caps, self.offs = caps, offs
+        cap = max(caps)
+        self.cap = cap                                  # the largest capacity (= every capacity when uniform)
+        self.uniform = all(c == cap for c in caps)
+        self.cache_offsets = torch.tensor(offs, dtype=torch.int32, device=device)
+        self.k_c = torch.zeros(offs[-1] * Hkv * D, dtype=dt, device=device)
+        self.v_c = torch.zeros(offs[-1] * Hkv * D, dtype=dt, device=device)
         self.cache_lens = torch.zeros(nb, dtype=torch.int32, device=device)
         self.indices = torch.zeros((nb, Hkv, B), dtype=torch.int32, device=device)
         self.cal_indices = (torch.zeros((nb, Hkv, p.calib_size), dtype=torch.int32, device=device)
@@ -456,14 +456,13 @@ class CompressBuffers:
                                    self.indices, stream)
 
     def decode(self, q_t, stream=None, max_cache_len=None, pass_offsets=None):
-        # the layout here is uniform (capacity self.cap for every sequence): when the call's
-        # max_cache_len is that capacity the offsets need not be passed (pass_offsets=True still
-        # passes them)
+        # when every sequence has the same capacity and the call's max_cache_len is that capacity the
+        # offsets need not be passed (pass_offsets=True still passes them)
         mcl = max_cache_len or self.max_cache_len
         if pass_offsets is None:
-            pass_offsets = mcl != self.cap
-        if not pass_offsets and mcl != self.cap:
-            raise ValueError("the offsets can only be left out when max_cache_len is the capacity")
+            pass_offsets = mcl != self.cap or not self.uniform
+        if not pass_offsets and (mcl != self.cap or not self.uniform):
+            raise ValueError("the offsets can only be left out when every capacity equals max_cache_len")
         offs = self.cache_offsets if pass_offsets else None
         calidrop_decode(self.p, q_t, self.k_c, self.v_c, offs, self.cache_lens, mcl, self.c_q, self.c_out,
                         self.c_lse, self.out, self.a_lse, self.flags, self.ws_decode, stream)
@@ -487,11 +486,11 @@ class CompressBuffers:
         return self.ws_compress[off:off + nbytes].view(torch.float32)
 
     def cache_view(self, which: str, b: int) -> torch.Tensor:
-        """[Hkv][cap][D] view of sequence b inside k_c / v_c."""
+        """[Hkv][cap_b][D] view of sequence b inside k_c / v_c."""
         t = self.k_c if which == "k" else self.v_c
         Hkv, D = self.p.n_kv_heads, self.p.head_dim
-        sz = Hkv * self.cap * D
-        return t[b * sz:(b + 1) * sz].view(Hkv, self.cap, D)
+        lo, cap = self.offs[b] * Hkv * D, self.caps[b]
+        return t[lo:lo + Hkv * cap * D].view(Hkv, cap, D)
 
 
 def default_scale(head_dim: int) -> float:

@@ -20,8 +20,6 @@
 namespace {
 
 thread_local char g_err[512] = "";
-std::atomic<int> g_inspection{0};   // calidrop_set_inspection
-std::atomic<int> g_wide_select{0};  // calidrop_set_wide_selection
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -34,15 +32,19 @@ int fail(int code, const char* fmt, ...) {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+// floats per vote plane: a multiple of 64, so that every plane starts 256-byte aligned
+inline int64_t vote_plane(int64_t total_tokens, int n_kv_heads) { return (total_tokens * n_kv_heads + 63) / 64 * 64; }
 
-constexpr uint32_t kParamsSizeV1 = 48;      // layout up to theta2, without calib_size
+constexpr uint32_t kParamsSizeV1 = 48;      // layout up to theta2, without calib_size and flags
+constexpr uint32_t kParamsSizeV2 = 52;      // layout up to calib_size, without flags
 
 // Copies the caller's struct (either known layout) into `q` with every field defined.
 int load_params(const calidrop_params* in, calidrop_params* q) {
   if (!in) return fail(CALIDROP_EINVAL, "params is NULL");
-  if (in->struct_size != sizeof(calidrop_params) && in->struct_size != kParamsSizeV1)
-    return fail(CALIDROP_EINVAL, "params.struct_size is %u, this library expects %zu (or %u)", in->struct_size,
-                sizeof(calidrop_params), kParamsSizeV1);
+  if (in->struct_size != sizeof(calidrop_params) && in->struct_size != kParamsSizeV1 &&
+      in->struct_size != kParamsSizeV2)
+    return fail(CALIDROP_EINVAL, "params.struct_size is %u, this library expects %zu (or %u, %u)", in->struct_size,
+                sizeof(calidrop_params), kParamsSizeV2, kParamsSizeV1);
   std::memset(q, 0, sizeof(*q));
   std::memcpy(q, in, in->struct_size);
   q->struct_size = sizeof(calidrop_params);
@@ -74,6 +76,8 @@ int check_params(const calidrop_params* p) {
   if (std::isnan(p->theta1) || std::isnan(p->theta2) || p->theta1 > p->theta2)
     return fail(CALIDROP_EINVAL, "thresholds must satisfy theta1 <= theta2 and not be NaN");
   if (p->calib_size < 0) return fail(CALIDROP_EINVAL, "calib_size must be >= 0 (got %d)", p->calib_size);
+  if (p->flags & ~(CALIDROP_OPT_WRITE_SCORES | CALIDROP_OPT_WIDE_SELECTION))
+    return fail(CALIDROP_EINVAL, "flags 0x%x holds bits that are no CALIDROP_OPT_* option", p->flags);
   {  // launch grids put (sequence, KV head, row block) on one grid axis of at most 65535
     const int64_t nrb = (static_cast<int64_t>(p->n_q_heads / p->n_kv_heads) * p->window + cd::kRowBlock - 1) / cd::kRowBlock;
     if (static_cast<int64_t>(p->batch) * p->n_kv_heads * nrb > 65535 || p->n_q_heads > 65535)
@@ -132,7 +136,7 @@ CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, i
   size_t off = 0;
   L.rowpart = off; off += round256(rows * L.NCH * sizeof(float2));
   L.row_lse = off; off += round256(rows * sizeof(float));
-  L.vote = off;    off += round256(toks * L.NRB * sizeof(float));
+  L.vote = off;    off += round256(static_cast<size_t>(vote_plane(total_tokens, p->n_kv_heads)) * L.NRB * sizeof(float));
   L.score = off;   off += round256(toks * sizeof(float));
   L.bitmap = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.W32 * sizeof(uint32_t));
   L.zstride = ceil_div(max_seq_len, 32) * 32;
@@ -178,6 +182,26 @@ int launch_status(const char* what) {
   return CALIDROP_OK;
 }
 
+// The single-workgroup selection kernels stage up to kSelMaxLdsKeys votes (padded) in dynamic LDS, more
+// than the 48 KiB a kernel may use without asking.  The limit is raised to the largest size any call
+// can need, once per (kernel variant, device) at that variant's first use on the device - a host-side
+// setting that enqueues nothing - and never again, so that calls on the enqueue path (also under
+// stream capture) only launch.
+constexpr size_t kSelMaxLdsBytes = (static_cast<size_t>(cd::kSelMaxLdsKeys) + cd::kSelMaxLdsKeys / 32 + 1) * sizeof(float);
+constexpr int kMaxDevices = 64;
+std::atomic<uint8_t> g_sel_lds_ready[3][kMaxDevices];     // zero-initialised: nothing raised yet
+
+int ensure_select_lds(int variant, const void* fn) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(CALIDROP_EHIP, "hipGetDevice failed or device index %d is beyond %d", dev, kMaxDevices - 1);
+  if (g_sel_lds_ready[variant][dev].load(std::memory_order_acquire)) return CALIDROP_OK;
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSelMaxLdsBytes));
+  if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
+  g_sel_lds_ready[variant][dev].store(1, std::memory_order_release);
+  return CALIDROP_OK;
+}
+
 // Pooling + selection + gather for scores already in sa.vote.  Heads whose pooled scores fit in
 // LDS are pooled inside the single-workgroup selection kernel; longer ones go through the
 // pooled-score buffer and the multi-workgroup chain.  `window` = trailing positions always kept.
@@ -186,9 +210,9 @@ int run_selection(const calidrop_params* p, int window, int pool_k, int max_seq_
   int rc;
   const int bg = p->batch * p->n_kv_heads;
   const int max_prefix = max_seq_len - window;
-  se.write_scores = g_inspection.load(std::memory_order_relaxed);
+  se.write_scores = (p->flags & CALIDROP_OPT_WRITE_SCORES) ? 1 : 0;
   if (max_prefix <= cd::kSelMaxLdsKeys && p->budget <= cd::kSelMaxLdsKeys && pool_k <= cd::kSelMaxPool &&
-      !g_wide_select.load(std::memory_order_relaxed)) {
+      !(p->flags & CALIDROP_OPT_WIDE_SELECTION)) {
     // dynamic LDS: staged votes (padded), later reused for the retained indices
     size_t lds = static_cast<size_t>(p->budget) * sizeof(int32_t);
     if (max_seq_len > p->budget) {
@@ -200,10 +224,7 @@ int run_selection(const calidrop_params* p, int window, int pool_k, int max_seq_
     const void* fn = per == 8    ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 8>)
                      : per == 16 ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 16>)
                                  : reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 32>);
-    if (lds > 48 * 1024) {
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-      if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
-    }
+    if ((rc = ensure_select_lds(per == 8 ? 0 : per == 16 ? 1 : 2, fn))) return rc;
     const dim3 grid(bg), block(cd::kSelThreads);
     if (per == 8) hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 8>), grid, block, lds, st, se);
     else if (per == 16) hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 16>), grid, block, lds, st, se);
@@ -254,6 +275,7 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   sa.rowpart = reinterpret_cast<float2*>(ws + L.rowpart);
   sa.row_lse = reinterpret_cast<float*>(ws + L.row_lse);
   sa.vote = reinterpret_cast<float*>(ws + L.vote);
+  sa.plane = vote_plane(total_tokens, p->n_kv_heads);
   sa.score = reinterpret_cast<float*>(ws + L.score);
   // default calibration query = last window query: the vote pass exports its logits
   sa.cal_logit = (q_cal || G > cd::kMaxCalHeads || p->window % 4 != 0)
@@ -284,7 +306,7 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   se.seq_off = seq_offsets; se.cache_off = cache_offsets; se.total_tokens = total_tokens; se.batch = p->batch;
   se.Hkv = p->n_kv_heads; se.w = p->window; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
   se.NRB = L.NRB; se.pool_k = p->pool_kernel; se.row_bytes = D * static_cast<int>(sizeof(T));
-  se.vote = sa.vote; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
+  se.vote = sa.vote; se.plane = sa.plane; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
   se.calib = p->calib_size; se.cal_indices = cal_indices;
   se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
   se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
@@ -338,7 +360,7 @@ int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, cons
     // others' streaming - measured 2-4 % faster (256 MiB per call: 6.6 vs 6.3 TB/s)
     const bool many_pairs = p->batch * p->n_kv_heads >= kFusedMinPairs;
     int nw = (tiles <= 4 || (tiles >= 32 && many_pairs)) ? 4 : 8;
-    while (nw > 4 && nw * lds_per_wave > 64 * 1024) nw /= 2;
+    while (nw > 4 && nw * lds_per_wave > 48 * 1024) nw /= 2;     // what a launch may use without raising the limit
     const dim3 grid(p->n_kv_heads, p->batch);
     const size_t lds = nw * lds_per_wave;
     if (nw == 8) hipLaunchKernelGGL((cd::decode_fused_kernel<T, D, 8>), grid, dim3(512), lds, st, fa);
@@ -562,7 +584,8 @@ H2oLayout h2o_layout(const calidrop_params* p, int64_t total_tokens, int32_t max
   const size_t slots = static_cast<size_t>(p->batch) * p->n_q_heads * L.sp.NS;
   size_t off = 0;
   L.row_lse = off; off += round256(static_cast<size_t>(p->batch) * p->n_q_heads * L.lse_stride * sizeof(float));
-  L.vote = off;    off += round256(toks * (p->n_q_heads / p->n_kv_heads) * sizeof(float));   // one plane per head of a group
+  L.vote = off;    // one plane per head of a group
+  off += round256(static_cast<size_t>(vote_plane(total_tokens, p->n_kv_heads)) * (p->n_q_heads / p->n_kv_heads) * sizeof(float));
   L.score = off;   off += round256(toks * sizeof(float));
   L.bitmap = off;  off += round256(static_cast<size_t>(p->batch) * p->n_kv_heads * L.W32 * sizeof(uint32_t));
   L.q_last = off;  off += round256(static_cast<size_t>(p->batch) * p->n_q_heads * p->head_dim * sizeof(float));
@@ -591,6 +614,7 @@ int h2o_impl(const calidrop_params* p, int n_local, const void* q_full, const vo
   ha.lse_stride = L.lse_stride; ha.sl2 = sl2;
   ha.row_lse = reinterpret_cast<float*>(ws + L.row_lse);
   ha.vote = reinterpret_cast<float*>(ws + L.vote);
+  ha.plane = vote_plane(total_tokens, p->n_kv_heads);
   ha.q_last = ws + L.q_last;
   const int nblk = ceil_div(max_seq_len, kH2oBlock);
   // always launched: it also extracts Q_{-1}, which prompts within the budget need as C_q
@@ -605,12 +629,12 @@ int h2o_impl(const calidrop_params* p, int n_local, const void* q_full, const vo
   cd::ScoreArgs sa{};
   sa.seq_off = seq_offsets; sa.total_tokens = total_tokens; sa.batch = p->batch; sa.Hq = p->n_q_heads;
   sa.Hkv = p->n_kv_heads; sa.G = G; sa.w = n_local; sa.B = p->budget; sa.NRB = G; sa.max_seq_len = max_seq_len;
-  sa.pool_k = 1; sa.vote = ha.vote; sa.score = reinterpret_cast<float*>(ws + L.score);
+  sa.pool_k = 1; sa.vote = ha.vote; sa.plane = ha.plane; sa.score = reinterpret_cast<float*>(ws + L.score);
   cd::SelectArgs se{};
   se.seq_off = seq_offsets; se.cache_off = cache_offsets; se.total_tokens = total_tokens; se.batch = p->batch;
   se.Hkv = p->n_kv_heads; se.w = n_local; se.B = p->budget; se.max_seq_len = max_seq_len; se.W32 = L.W32;
   se.NRB = G; se.pool_k = 1; se.row_bytes = D * static_cast<int>(sizeof(T));
-  se.vote = sa.vote; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
+  se.vote = sa.vote; se.plane = sa.plane; se.score = sa.score; se.indices = indices; se.cache_lens = cache_lens;
   se.calib = p->calib_size; se.cal_indices = cal_indices;
   se.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap);
   se.k = k; se.v = v; se.k_c = k_c; se.v_c = v_c;
@@ -646,8 +670,6 @@ extern "C" {
 
 const char* calidrop_last_error(void) { return g_err; }
 int calidrop_version(void) { return 200; }
-void calidrop_set_inspection(int enabled) { g_inspection.store(enabled ? 1 : 0, std::memory_order_relaxed); }
-void calidrop_set_wide_selection(int enabled) { g_wide_select.store(enabled ? 1 : 0, std::memory_order_relaxed); }
 
 size_t calidrop_compress_workspace_bytes(const calidrop_params* p_in, int64_t total_tokens, int32_t max_seq_len) {
   calidrop_params pp; const calidrop_params* p = &pp;
@@ -1020,7 +1042,7 @@ int calidrop_compress_h2o_workspace_region(const calidrop_params* p_in, int32_t 
     *bytes = static_cast<size_t>(total_tokens) * p->n_kv_heads * sizeof(float);
   } else if (region == CALIDROP_REGION_VOTE_PLANES) {
     *offset = L.vote;
-    *bytes = static_cast<size_t>(total_tokens) * p->n_kv_heads * (p->n_q_heads / p->n_kv_heads) * sizeof(float);
+    *bytes = static_cast<size_t>(vote_plane(total_tokens, p->n_kv_heads)) * (p->n_q_heads / p->n_kv_heads) * sizeof(float);
   } else {
     return fail(CALIDROP_EINVAL, "unknown workspace region %d", region);
   }

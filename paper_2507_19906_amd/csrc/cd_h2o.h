@@ -29,7 +29,8 @@ struct H2oArgs {
   int lse_stride;            // floats per (sequence, query head) in row_lse; a multiple of the row block
   float sl2;                 // scale * log2(e)
   float* row_lse;            // [batch*Hq][lse_stride], log2 units; rows >= n_b hold +inf
-  float* vote;               // [G][total_tokens*Hkv]: one plane per query head of the group, each packed like K with one float per row
+  float* vote;               // [G][plane]: one plane per query head of the group, each packed like K with one float per row
+  int64_t plane;             // floats per plane: total_tokens*Hkv rounded up to a multiple of 64
   void* q_last;              // [batch][Hq][D]: the last prompt query of every head (Q_{-1})
 };
 
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(256) void h2o_votes_kernel(H2oArgs a) {
   const int hq = g * a.G + hh;
   const T* qbase = static_cast<const T*>(a.q_full) + (static_cast<int64_t>(off0) * a.Hq + static_cast<int64_t>(hq) * n) * D;
   const float* lse_row = a.row_lse + static_cast<int64_t>(b * a.Hq + hq) * a.lse_stride;
-  float* vote = a.vote + static_cast<int64_t>(hh) * a.total_tokens * a.Hkv + head_tok;
+  float* vote = a.vote + static_cast<int64_t>(hh) * a.plane + head_tok;
 
   __shared__ __attribute__((aligned(16))) char s_q[2][KS::kStageBytes];
   __shared__ __attribute__((aligned(16))) float s_z[2][64];      // row log-sum-exp of the staged rows

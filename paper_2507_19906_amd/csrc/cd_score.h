@@ -31,7 +31,8 @@ struct ScoreArgs {
   int keep_k;           // pass 1 leaves K in the last-level cache for pass 2 (K of the whole call fits it)
   float2* rowpart;      // [batch*Hkv*NRB*128][NCH] (max, sum) per chunk
   float* row_lse;       // [batch*Hkv*NRB*128] log2-domain row log-sum-exp
-  float* vote;          // [NRB][total_tokens*Hkv]
+  float* vote;          // [NRB][plane]: one plane of votes per row block, each packed like K with one float per row
+  int64_t plane;        // floats per plane: total_tokens*Hkv rounded up to a multiple of 64 (planes stay 256-byte aligned)
   float* score;         // [total_tokens*Hkv]
   float* cal_logit;     // [batch*Hq][zstride] log2-unit logits of the last window query, or NULL
   int zstride;
@@ -388,7 +389,7 @@ __global__ __launch_bounds__(256, sizeof(T) == 2 ? CD_VOTES_WAVES : 2) void scor
   const int i = lane & 15, c = lane >> 4;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
   const T* kbase = static_cast<const T*>(a.k) + head_tok * D;
-  float* vote = a.vote + static_cast<int64_t>(rb) * a.total_tokens * a.Hkv + head_tok;
+  float* vote = a.vote + static_cast<int64_t>(rb) * a.plane + head_tok;
 
   __shared__ __attribute__((aligned(16))) char s_k[2][KS::kStageBytes];
   __shared__ float s_v[2][4][SK];                  // per-wave partial votes of a stage
@@ -490,7 +491,7 @@ __global__ __launch_bounds__(256) void pool_scores_kernel(ScoreArgs a) {
   const int j = blockIdx.x * 256 + threadIdx.x;
   if (j >= P) return;
   const int64_t head_tok = static_cast<int64_t>(off0) * a.Hkv + static_cast<int64_t>(g) * n;
-  const int64_t plane = a.total_tokens * a.Hkv;
+  const int64_t plane = a.plane;
   const int half = a.pool_k / 2;
   float sum = 0.f;
   for (int d = -half; d <= half; ++d) {

@@ -33,7 +33,8 @@ struct SelectArgs {
   int batch, Hkv, w, B, max_seq_len, W32, NRB, pool_k, row_bytes;
   int calib;               // calibration size m (0 = every evicted token)
   int write_scores;        // LDS variant: also store the pooled scores (inspection only)
-  const float* vote;       // [NRB][total_tokens*Hkv]   (LDS-key variant pools these itself)
+  const float* vote;       // [NRB][plane]   (LDS-key variant pools these itself)
+  int64_t plane;           // floats per vote plane, a multiple of 64
   float* score;            // [total_tokens*Hkv] pooled scores: written (LDS variant) or read
   int32_t* indices;        // [batch][Hkv][B]
   int32_t* cal_indices;    // [batch][Hkv][calib] positions of the calibration set, or NULL
@@ -472,10 +473,11 @@ __global__ __launch_bounds__(NT) void select_gather_lds_kernel(SelectArgs a) {
     const int k_sel = a.B - a.w;
     // ---- stage the votes (row-block partials added first, fixed order) ---------------------
     {
-      // 16 bytes per lane from the 16-byte boundary at or below the head's first vote (the vote
-      // planes start 256-byte aligned and a head starts anywhere inside): vector v covers positions
+      // 16 bytes per lane from the 16-byte boundary at or below the head's first vote (every vote
+      // plane starts 256-byte aligned - the plane stride is a multiple of 64 floats - and a head
+      // starts anywhere inside): vector v covers positions
       // 4v - shift .. 4v - shift + 3.  All loads of a thread are in flight together.
-      const int64_t plane = a.total_tokens * a.Hkv;
+      const int64_t plane = a.plane;
       const int shift = static_cast<int>(head_tok & 3);
       const float* vsrc = a.vote + (head_tok - shift);
       f32x4 tmp[PER / 4];

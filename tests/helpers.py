@@ -17,8 +17,13 @@ TOL_LSE = {"bf16": 2e-3, "fp32": 1e-4}
 TIE_BAND = {"bf16": 1e-4, "fp32": 1e-5}
 
 
+# per-call options every test's params carry unless it says otherwise: the parity checks read the
+# pooled scores; the `wide_selection` fixtures add OPT_WIDE_SELECTION for the duration of a test
+TEST_FLAGS = cd.OPT_WRITE_SCORES
+
+
 def params_for(wl: synth.Workload, **over) -> cd.Params:
-    kw = dict(dtype=wl.dtype, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+    kw = dict(flags=TEST_FLAGS, dtype=wl.dtype, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
               head_dim=wl.head_dim, window=wl.window, budget=wl.budget, pool_kernel=wl.pool_kernel,
               theta1=wl.theta1, theta2=wl.theta2)
     kw.update(over)
@@ -34,7 +39,6 @@ def gpu_compress(wl, x, q_cal=None, extra_capacity=0, win_lse=None, **over):
     p = params_for(wl, **over)
     dev = x["k"].device
     bufs = cd.CompressBuffers(p, wl.seq_lens, dev, extra_capacity=extra_capacity)
-    cd.calidrop_set_inspection(True)          # the parity checks read the pooled scores
     bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], q_cal=q_cal, win_lse=win_lse)
     torch.cuda.synchronize()
     return bufs
@@ -152,7 +156,7 @@ def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_sc
         report["c_lse_err"] = max(report.get("c_lse_err", 0), err_l)
         assert err_o <= TOL_OUT[dt], f"c_out max-abs error {err_o}"
         assert err_l <= TOL_LSE[dt], f"c_lse max-abs error {err_l}"
-        if check_scores:
+        if check_scores and (bufs.p.flags & cd.OPT_WRITE_SCORES):
             score = bufs.region(cd.REGION_SCORE).cpu().numpy().astype(np.float64)
             off = int(sum(wl.seq_lens[:b])) * wl.n_kv_heads
             for j, g in enumerate(heads):

@@ -25,12 +25,12 @@ def test_header_symbols_are_exported():
     assert {"calidrop_compress", "calidrop_decode", "calidrop_last_error",
             "calidrop_compress_workspace_bytes", "calidrop_decode_workspace_bytes",
             "calidrop_compress_workspace_region", "calidrop_version",
-            "calidrop_set_inspection", "calidrop_recalibrate", "calidrop_recalibrate_workspace_bytes"} <= names
+            "calidrop_recalibrate", "calidrop_recalibrate_workspace_bytes"} <= names
     L = cd.lib()
     for n in names:
         assert hasattr(L, n), n
     assert L.calidrop_version() >= 100
-    assert ctypes.sizeof(cd.Params) == 52
+    assert ctypes.sizeof(cd.Params) == 56
 
 
 def test_workspace_sizes():
@@ -154,6 +154,25 @@ def test_older_params_layout_is_accepted():
                                       A, need - 1, None) == cd.EWORKSPACE
 
 
+def test_layout_without_flags_is_accepted_and_unknown_flags_are_rejected():
+    # a caller compiled against the 52-byte struct (calib_size, no flags) keeps working: flags reads as 0
+    p = good(calib_size=7)
+    p.struct_size = 52
+    p.flags = 0xFFFF                # must be ignored: it lies outside the declared size
+    assert cd.calidrop_decode_workspace_bytes(p, 512) > 0
+    A = 4096
+    assert cd.lib().calidrop_compress(ctypes.byref(p), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A,
+                                      A, 1 << 40, None) == cd.EINVAL
+    assert "cal_indices" in cd.calidrop_last_error()       # calib_size was read, flags were not
+    # per-call options: the two defined bits pass, anything else is an error before any launch
+    for ok in (0, cd.OPT_WRITE_SCORES, cd.OPT_WIDE_SELECTION, cd.OPT_WRITE_SCORES | cd.OPT_WIDE_SELECTION):
+        assert cd.calidrop_compress_workspace_bytes(good(flags=ok), 16384, 8192) > 0
+    bad = good(flags=4)
+    assert cd.lib().calidrop_compress(ctypes.byref(bad), A, A, A, A, 16384, 8192, None, A, A, A, A, A, None, A, A, A,
+                                      A, 1 << 40, None) == cd.EINVAL
+    assert "flags" in cd.calidrop_last_error()
+
+
 def test_given_strategy_entry_points_validate_on_the_host():
     A = 4096
     L = cd.lib()
@@ -232,10 +251,9 @@ def test_h2o_entry_point_validates_on_the_host():
     assert L.calidrop_compress_h2o(ctypes.byref(good(batch=4096)), 0, A, A, A, A, 4096 * 8192, 8192, A, A, A, A, A, None,
                                    A, A, A, A, 1 << 44, None) == cd.EUNSUPPORTED              # batch * Hq > 65535
     off, nbytes = cd.calidrop_compress_h2o_workspace_region(p, 0, 16384, 8192, cd.REGION_VOTE_PLANES)
-    assert nbytes == 16384 * 8 * 4 * 4 and off % 256 == 0 and off + nbytes <= need
+    assert nbytes == 16384 * 8 * 4 * 4 and off % 256 == 0 and off + nbytes <= need      # 16384*8 is a multiple of 64
     off, nbytes = cd.calidrop_compress_h2o_workspace_region(p, 0, 16384, 8192, cd.REGION_ROW_LSE)
     assert nbytes == 2 * 32 * 8192 * 4
-    cd.calidrop_set_wide_selection(True); cd.calidrop_set_wide_selection(False)
 
 
 def test_probe_library_exports_its_header():
@@ -273,7 +291,7 @@ def test_public_headers_are_plain_c99(tmp_path):
     src = tmp_path / "abi.c"
     src.write_text('#include "calidrop.h"\n#include "calidrop_probes.h"\n'
                    "int main(void) { calidrop_params p; p.struct_size = (uint32_t)sizeof(p);\n"
-                   "  return (int)(sizeof(calidrop_params) != 52u) + (int)p.struct_size * 0; }\n")
+                   "  return (int)(sizeof(calidrop_params) != 56u) + (int)p.struct_size * 0; }\n")
     res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
                           "-fsyntax-only", str(src)], capture_output=True, text=True)
     assert res.returncode == 0, res.stderr

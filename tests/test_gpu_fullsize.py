@@ -74,7 +74,6 @@ def test_h2o_one_layer_32k_properties_and_samples():
     x = synth.make_inputs(wl, synth.BASE_SEED, device=DEV)
     q_full = synth.full_queries(wl, x, synth.BASE_SEED, DEV)
     bufs = cd.CompressBuffers(H.params_for(wl), wl.seq_lens, DEV)
-    cd.calidrop_set_inspection(True)
     bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
     torch.cuda.synchronize()
     lse = bufs.h2o_region(cd.REGION_ROW_LSE).view(wl.n_q_heads, -1).cpu().numpy().astype(np.float64)

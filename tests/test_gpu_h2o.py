@@ -90,7 +90,6 @@ def test_h2o_strategy(wl, n_local):
     q_full = synth.full_queries(wl, x, 61, DEV)
     p = H.params_for(wl)
     bufs = cd.CompressBuffers(p, wl.seq_lens, DEV)
-    cd.calidrop_set_inspection(True)          # the parity checks read the candidates' scores
     bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"], n_local=n_local)
     torch.cuda.synchronize()
     rep = {}
@@ -115,7 +114,6 @@ def test_h2o_is_deterministic():
     x = to_dev(synth.make_inputs(wl, 62))
     q_full = synth.full_queries(wl, x, 62, DEV)
     outs = []
-    cd.calidrop_set_inspection(True)
     for _ in range(2):
         bufs = cd.CompressBuffers(H.params_for(wl), wl.seq_lens, DEV)
         bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
@@ -128,9 +126,10 @@ def test_h2o_is_deterministic():
 
 @pytest.fixture
 def wide_selection():
-    cd.calidrop_set_wide_selection(True)
+    old = H.TEST_FLAGS
+    H.TEST_FLAGS = old | cd.OPT_WIDE_SELECTION
     yield
-    cd.calidrop_set_wide_selection(False)
+    H.TEST_FLAGS = old
 
 
 def test_h2o_with_multi_workgroup_selection(wide_selection):
@@ -140,12 +139,10 @@ def test_h2o_with_multi_workgroup_selection(wide_selection):
     x = to_dev(synth.make_inputs(wl, 63))
     q_full = synth.full_queries(wl, x, 63, DEV)
     bufs = cd.CompressBuffers(H.params_for(wl, calib_size=700), wl.seq_lens, DEV)
-    cd.calidrop_set_inspection(True)
     bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
     torch.cuda.synchronize()
     # same lists as the single-workgroup variant
-    cd.calidrop_set_wide_selection(False)
-    twin = cd.CompressBuffers(H.params_for(wl, calib_size=700), wl.seq_lens, DEV)
+    twin = cd.CompressBuffers(H.params_for(wl, calib_size=700, flags=cd.OPT_WRITE_SCORES), wl.seq_lens, DEV)
     twin.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
     torch.cuda.synchronize()
     assert torch.equal(bufs.indices, twin.indices) and torch.equal(bufs.cal_indices, twin.cal_indices)
@@ -180,7 +177,6 @@ def test_h2o_rows_whose_logits_outgrow_the_reference(dtype):
     x = to_dev(x)
     q_full = synth.full_queries(wl, x, 64, DEV)
     bufs = cd.CompressBuffers(H.params_for(wl), wl.seq_lens, DEV)
-    cd.calidrop_set_inspection(True)
     bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"])
     torch.cuda.synchronize()
     rep = {}

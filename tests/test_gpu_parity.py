@@ -426,9 +426,10 @@ def test_calibration_size_with_multi_workgroup_selection(dtype, m):
 
 @pytest.fixture
 def wide_selection():
-    cd.calidrop_set_wide_selection(True)
+    old = H.TEST_FLAGS
+    H.TEST_FLAGS = old | cd.OPT_WIDE_SELECTION
     yield
-    cd.calidrop_set_wide_selection(False)
+    H.TEST_FLAGS = old
 
 
 @pytest.mark.parametrize("wl", [

@@ -296,7 +296,6 @@ def test_random_sweep_over_strategies_shapes_and_offload():
         else:
             n_local = int(rng.integers(1, B))
             q_full = synth.full_queries(wl, x, 1000 + case, DEV)
-            cd.calidrop_set_inspection(True)
             bufs.compress_h2o(q_full, x["k"], x["v"], x["seq_offsets"], n_local=n_local)
             torch.cuda.synchronize()
             check_h2o(wl, x, q_full, bufs, n_local, rep)
