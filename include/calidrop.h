@@ -226,6 +226,31 @@ int calidrop_decode(const calidrop_params* p, const void* q_t, const void* k_c, 
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * calidrop_decode_static - calidrop_decode for callers that cannot allocate or bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ *
+ * Same arguments (minus workspace / workspace_bytes), same validation, same kernels and bit-identical
+ * results.  The scratch of the call - the per-split partial outputs of the form of the step that spreads
+ * a long cache over several workgroups - lives in a fixed array of CALIDROP_STATIC_SCRATCH_BYTES of
+ * device memory inside the library, one copy per GPU, held from the library's load until the process
+ * ends.  The call allocates nothing and frees nothing.
+ *   - A call whose scratch need, calidrop_decode_workspace_bytes(p, max_cache_len), exceeds
+ *     CALIDROP_STATIC_SCRATCH_BYTES returns CALIDROP_EWORKSPACE and enqueues nothing: use
+ *     calidrop_decode with a workspace for such shapes.
+ *   - Every call on a GPU shares that GPU's array, which keeps the previous call's contents.  Nothing in
+ *     it needs to start at zero (every partial a call reads, it has written before), so consecutive
+ *     calls on one stream are safe; calls that overlap in time on one GPU (different streams, or
+ *     different host threads) race on it and must not be made.
+ *   - The array's address on the current device is looked up on the first call on that device
+ *     (CALIDROP_EHIP if the lookup fails).
+ */
+#define CALIDROP_STATIC_SCRATCH_BYTES (8u << 20)
+int calidrop_decode_static(const calidrop_params* p, const void* q_t, const void* k_c, const void* v_c,
+                           const int32_t* cache_offsets, const int32_t* cache_lens,
+                           int32_t max_cache_len, const float* c_q, const float* c_out,
+                           const float* c_lse, void* out, float* a_lse, uint8_t* flags, void* stream);
+
+/*
  * calidrop_append - decode-time growth of the compressed cache: tokens generated during decoding
  * are appended and never evicted (the evicted set is fixed at prefill).  For every sequence b
  * the rows k_new[b][g], v_new[b][g] ([batch][Hkv][D] dtype: K and V of the token just generated)

@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.calidrop_decode.restype = ctypes.c_int
         L.calidrop_decode.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz,
                                       vp]
+        L.calidrop_decode_static.restype = ctypes.c_int
+        L.calidrop_decode_static.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.calidrop_recalibrate_workspace_bytes.restype = sz
         L.calidrop_recalibrate_workspace_bytes.argtypes = [pp, i32]
         L.calidrop_recalibrate.restype = ctypes.c_int
@@ -198,6 +200,17 @@ def calidrop_decode(p: Params, q_t, k_c, v_c, cache_offsets, cache_lens, max_cac
         ctypes.byref(p), _ptr(q_t), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens),
         max_cache_len, _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(out), _ptr(a_lse), _ptr(flags),
         _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 8 << 20      # CALIDROP_STATIC_SCRATCH_BYTES
+
+
+def calidrop_decode_static(p: Params, q_t, k_c, v_c, cache_offsets, cache_lens, max_cache_len: int, c_q,
+                           c_out, c_lse, out, a_lse, flags, stream=None) -> None:
+    _check(lib().calidrop_decode_static(
+        ctypes.byref(p), _ptr(q_t), _ptr(k_c), _ptr(v_c), _ptr(cache_offsets), _ptr(cache_lens),
+        max_cache_len, _ptr(c_q), _ptr(c_out), _ptr(c_lse), _ptr(out), _ptr(a_lse), _ptr(flags),
+        _stream(stream)))
 
 
 def calidrop_append(p: Params, k_new, v_new, k_c, v_c, cache_offsets, cache_lens, stream=None) -> None:

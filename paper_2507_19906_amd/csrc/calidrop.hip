@@ -17,6 +17,13 @@
 #include "cd_score.h"
 #include "cd_select.h"
 
+// Fixed device memory for calidrop_decode_static, the decode entry point for callers that cannot
+// bring a workspace: every GPU the library runs on holds its own copy of this array until the
+// process ends.  Host code never uses the array's name as an address: the per-device address comes
+// from hipGetSymbolAddress (static_scratch_ptr below).
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(CALIDROP_STATIC_SCRATCH_BYTES);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -199,6 +206,24 @@ int ensure_select_lds(int variant, const void* fn) {
   hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSelMaxLdsBytes));
   if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
   g_sel_lds_ready[variant][dev].store(1, std::memory_order_release);
+  return CALIDROP_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+std::atomic<void*> g_scratch_ptr[kMaxDevices];            // zero-initialised: not looked up yet
+
+int static_scratch_ptr(char** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(CALIDROP_EHIP, "hipGetDevice failed or device index %d is beyond %d", dev, kMaxDevices - 1);
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(CALIDROP_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = static_cast<char*>(ptr);
   return CALIDROP_OK;
 }
 
@@ -763,10 +788,13 @@ int calidrop_compress_with_lse(const calidrop_params* p_in, const void* q_win, c
 #undef CD_DISPATCH
 }
 
-int calidrop_decode(const calidrop_params* p_in, const void* q_t, const void* k_c, const void* v_c,
-                    const int32_t* cache_offsets, const int32_t* cache_lens, int32_t max_cache_len,
-                    const float* c_q, const float* c_out, const float* c_lse, void* out, float* a_lse,
-                    uint8_t* flags, void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+// calidrop_decode and calidrop_decode_static: the same validation and launches; they differ in where
+// the scratch for the split partials comes from (the caller's workspace, or the fixed per-GPU array).
+int decode_entry(const calidrop_params* p_in, const void* q_t, const void* k_c, const void* v_c,
+                 const int32_t* cache_offsets, const int32_t* cache_lens, int32_t max_cache_len, const float* c_q,
+                 const float* c_out, const float* c_lse, void* out, float* a_lse, uint8_t* flags, void* workspace,
+                 size_t workspace_bytes, bool fixed_scratch, void* stream) {
   int rc;
   calidrop_params pp; const calidrop_params* p = &pp;
   if ((rc = load_params(p_in, &pp))) return rc;
@@ -785,12 +813,19 @@ int calidrop_decode(const calidrop_params* p_in, const void* q_t, const void* k_
     return fail(CALIDROP_EUNSUPPORTED, "batch * max_cache_len exceeds int32 offsets (uniform layout)");
   }
   const DecodeLayout L = decode_layout(p, max_cache_len);
-  if (!workspace || workspace_bytes < L.total)
-    return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
-                L.total);
-  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
-  hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
+  if (fixed_scratch) {
+    if (L.total > kStaticScratchBytes)
+      return fail(CALIDROP_EWORKSPACE, "this call needs %zu bytes of scratch and the fixed array holds %zu: use "
+                  "calidrop_decode with a workspace", L.total, kStaticScratchBytes);
+    if ((rc = static_scratch_ptr(&ws))) return rc;       // the first HIP call, after all validation
+  } else {
+    if (!workspace || workspace_bytes < L.total)
+      return fail(CALIDROP_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : 0,
+                  L.total);
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(CALIDROP_EALIGN, "workspace is not 256-byte aligned");
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
 #define CD_DISPATCH(T, D)                                                                                      \
   return decode_impl<T, D>(p, q_t, k_c, v_c, cache_offsets, cache_lens, max_cache_len, c_q, c_out, c_lse, out, \
                            a_lse, flags, ws, L, st)
@@ -801,6 +836,23 @@ int calidrop_decode(const calidrop_params* p_in, const void* q_t, const void* k_
   if (p->head_dim == 128) CD_DISPATCH(float, 128);
   CD_DISPATCH(float, 64);
 #undef CD_DISPATCH
+}
+}  // namespace
+
+int calidrop_decode(const calidrop_params* p_in, const void* q_t, const void* k_c, const void* v_c,
+                    const int32_t* cache_offsets, const int32_t* cache_lens, int32_t max_cache_len,
+                    const float* c_q, const float* c_out, const float* c_lse, void* out, float* a_lse,
+                    uint8_t* flags, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_entry(p_in, q_t, k_c, v_c, cache_offsets, cache_lens, max_cache_len, c_q, c_out, c_lse, out, a_lse,
+                      flags, workspace, workspace_bytes, false, stream);
+}
+
+int calidrop_decode_static(const calidrop_params* p_in, const void* q_t, const void* k_c, const void* v_c,
+                           const int32_t* cache_offsets, const int32_t* cache_lens, int32_t max_cache_len,
+                           const float* c_q, const float* c_out, const float* c_lse, void* out, float* a_lse,
+                           uint8_t* flags, void* stream) {
+  return decode_entry(p_in, q_t, k_c, v_c, cache_offsets, cache_lens, max_cache_len, c_q, c_out, c_lse, out, a_lse,
+                      flags, nullptr, 0, true, stream);
 }
 
 size_t calidrop_recalibrate_workspace_bytes(const calidrop_params* p_in, int32_t max_seq_len) {
