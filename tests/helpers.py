@@ -49,10 +49,10 @@ def oracle_compress(wl, x, b, heads=None, q_cal=None, override=None, budget=None
     """Oracle compress of sequence b (optionally only the KV heads in `heads`)."""
     G = wl.group
     heads = list(range(wl.n_kv_heads)) if heads is None else list(heads)
-    K = to64(synth.seq_view(x["k"], wl, b))[heads]
-    V = to64(synth.seq_view(x["v"], wl, b))[heads]
+    K = to64(synth.seq_view(x["k"], wl, b)[heads])          # only the sampled heads leave the device
+    V = to64(synth.seq_view(x["v"], wl, b)[heads])
     qh = [g * G + j for g in heads for j in range(G)]
-    q_win = to64(x["q_win"][b])[qh]
+    q_win = to64(x["q_win"][b][qh])
     qc = None if q_cal is None else to64(q_cal[b])[qh]
     lse = None if win_lse is None else to64(win_lse[b])[qh]
     return ref.compress(q_win, K, V, wl.window, budget or wl.budget, pool_kernel or wl.pool_kernel,
@@ -137,12 +137,12 @@ def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_sc
         else:
             lists = check_calibration_set(gpu_cal, orc, dt, B - w, m, report)
             if any(not np.array_equal(lists[j], orc["evicted"][j]) for j in range(len(heads))):
-                Kh = to64(synth.seq_view(x["k"], wl, b))[heads]
-                Vh = to64(synth.seq_view(x["v"], wl, b))[heads]
+                Kh = to64(synth.seq_view(x["k"], wl, b)[heads])
+                Vh = to64(synth.seq_view(x["v"], wl, b)[heads])
                 _, orc["c_out"], orc["c_lse"] = ref.calibration_state(orc["c_q"], Kh, Vh, lists, G, wl.head_dim ** -0.5)
     # gathered rows are copies: bit-exact
-    Kc = to64(bufs.cache_view("k", b))[heads][:, :length]
-    Vc = to64(bufs.cache_view("v", b))[heads][:, :length]
+    Kc = to64(bufs.cache_view("k", b)[heads][:, :length])
+    Vc = to64(bufs.cache_view("v", b)[heads][:, :length])
     assert np.array_equal(Kc, orc["K_c"]) and np.array_equal(Vc, orc["V_c"])
     qh = [g * G + j for g in heads for j in range(G)]
     c_q, c_out, c_lse = (to64(bufs.c_q[b])[qh], to64(bufs.c_out[b])[qh], to64(bufs.c_lse[b])[qh])
@@ -157,10 +157,11 @@ def check_compress(wl, x, bufs, b, heads=None, q_cal=None, report=None, check_sc
         assert err_o <= TOL_OUT[dt], f"c_out max-abs error {err_o}"
         assert err_l <= TOL_LSE[dt], f"c_lse max-abs error {err_l}"
         if check_scores and (bufs.p.flags & cd.OPT_WRITE_SCORES):
-            score = bufs.region(cd.REGION_SCORE).cpu().numpy().astype(np.float64)
+            score = bufs.region(cd.REGION_SCORE)
             off = int(sum(wl.seq_lens[:b])) * wl.n_kv_heads
             for j, g in enumerate(heads):
-                s_gpu = score[off + g * n: off + g * n + (n - w)]
+                # only the prefix positions are written: slice before leaving the device
+                s_gpu = score[off + g * n: off + g * n + (n - w)].cpu().numpy().astype(np.float64)
                 s_ref = orc["score"][j]
                 rel = np.abs(s_gpu - s_ref) / (np.abs(s_ref) + 1e-30)
                 big = s_ref > 1e-12 * s_ref.max()
@@ -175,7 +176,7 @@ def oracle_state_from_gpu(wl, bufs, b, heads=None):
     G = wl.group
     heads = list(range(wl.n_kv_heads)) if heads is None else list(heads)
     qh = [g * G + j for g in heads for j in range(G)]
-    return dict(K_c=to64(bufs.cache_view("k", b))[heads], V_c=to64(bufs.cache_view("v", b))[heads],
+    return dict(K_c=to64(bufs.cache_view("k", b)[heads]), V_c=to64(bufs.cache_view("v", b)[heads]),
                 c_q=to64(bufs.c_q[b])[qh], c_out=to64(bufs.c_out[b])[qh],
                 c_lse=to64(bufs.c_lse[b])[qh], qh=qh)
 
@@ -224,8 +225,8 @@ def check_recalibrate(wl, x, bufs, q_t, b, before, heads=None, report=None):
     G = wl.group
     heads = list(range(wl.n_kv_heads)) if heads is None else list(heads)
     qh = [g * G + j for g in heads for j in range(G)]
-    K = to64(synth.seq_view(x["k"], wl, b))[heads]
-    V = to64(synth.seq_view(x["v"], wl, b))[heads]
+    K = to64(synth.seq_view(x["k"], wl, b)[heads])
+    V = to64(synth.seq_view(x["v"], wl, b)[heads])
     idx = bufs.indices[b].cpu().numpy()[heads]
     cal_idx = bufs.cal_indices[b].cpu().numpy()[heads] if bufs.p.calib_size > 0 else None
     out, flags, c_q, c_out, c_lse = ref.recalibrate(

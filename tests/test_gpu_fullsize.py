@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2507_19906_amd import binding as cd
 from paper_2507_19906_amd import synth
 from tests import helpers as H
 
@@ -11,54 +12,113 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def sampled(wl, samples, decode_steps=2, seed=synth.BASE_SEED):
+def sampled(wl, samples, decode_steps=2, seed=synth.BASE_SEED, capacities=None, recalibrate=False):
+    """samples: (sequence, KV head) pairs checked against the oracle; everything else gets the
+    properties that hold for every pair.  `capacities`: per-sequence cache capacities (packed caches
+    behind an offsets array) instead of one capacity for all."""
     x = synth.make_inputs(wl, seed, device=DEV)
-    bufs = H.gpu_compress(wl, x)
-    rep = {}
+    bufs = cd.CompressBuffers(H.params_for(wl), wl.seq_lens, DEV, capacities=capacities)
+    bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"])
+    torch.cuda.synchronize()
+    by_seq = {}
     for b, g in samples:
-        H.check_compress(wl, x, bufs, b, heads=[g], report=rep)
+        by_seq.setdefault(b, []).append(g)
+    rep = {}
+    for b, heads in by_seq.items():
+        H.check_compress(wl, x, bufs, b, heads=heads, report=rep)
     for t in range(decode_steps):
-        bufs.decode(x["q_dec"][t])
+        q_t = x["q_dec"][t]
+        bufs.decode(q_t)
         torch.cuda.synchronize()
-        for b, g in samples:
-            H.check_decode_step(wl, bufs, x["q_dec"][t], b, heads=[g], report=rep)
+        for b, heads in by_seq.items():
+            H.check_decode_step(wl, bufs, q_t, b, heads=heads, report=rep)
+        if recalibrate:                      # Alg. 2 complete: the state is carried on the GPU from step to step
+            before = H.snapshot_state(bufs)
+            bufs.recalibrate(q_t, x["k"], x["v"], x["seq_offsets"])
+            torch.cuda.synchronize()
+            for b, heads in by_seq.items():
+                H.check_recalibrate(wl, x, bufs, q_t, b, before, heads=heads, report=rep)
+            assert not torch.any(bufs.flags == cd.FLAG_RECOMPUTE)
     # properties that hold for every (sequence, head), checked on all of them
     idx = bufs.indices.cpu().numpy()
+    lens_gpu = bufs.cache_lens.cpu().numpy()
     for b, n in enumerate(wl.seq_lens):
         L = min(wl.budget, n)
-        assert int(bufs.cache_lens[b]) == L
+        assert int(lens_gpu[b]) == L
         assert np.all(np.diff(idx[b, :, :L], axis=1) > 0)
         if n > wl.budget:
             assert np.array_equal(idx[b, :, L - wl.window:L],
                                   np.tile(np.arange(n - wl.window, n), (wl.n_kv_heads, 1)))
             assert np.all(idx[b, :, 0] >= 0) and np.all(idx[b, :, L - 1] == n - 1)
     assert torch.isfinite(bufs.c_out).all() and torch.isfinite(bufs.out.float()).all()
-    print(wl.name, {k: (v if k != "flags" else np.bincount(v, minlength=3).tolist()) for k, v in rep.items()},
-          flush=True)
+    flags = np.bincount(rep.pop("flags"), minlength=4).tolist()
+    print(wl.name, f"{len(samples)} (sequence, KV head) pairs x {decode_steps} decode steps;",
+          "tie-band heads:", rep.get("tie_band_heads", 0), "| flags [none, calibrated, recompute, recomputed]:", flags,
+          "|", {k: float(v) for k, v in rep.items()}, flush=True)
     return rep
 
 
+def spread(n_seq, n_heads, count):
+    """`count` sequences spread over the batch, each with a different KV head: every head is covered
+    when count >= n_heads."""
+    seqs = sorted({int(round(i * (n_seq - 1) / max(count - 1, 1))) for i in range(count)})
+    return [(b, (3 * i + 1) % n_heads) for i, b in enumerate(seqs)]
+
+
 def test_config3_stack_32_layers_budget_512():
-    wl = synth.config(3, layers=32, budget=512, decode_steps=2)
-    sampled(wl, [(0, 1), (31, 6), (13, 0), (22, 7)])
+    # 16 layers with all their 8 KV heads (128 of the 256 pairs), and more layers with one head each
+    wl = synth.config(3, layers=32, budget=512, decode_steps=8)
+    full_layers = list(range(0, 32, 2))
+    samples = [(b, g) for b in full_layers for g in range(8)] + [(b, g) for b, g in spread(32, 8, 12) if b not in full_layers]
+    sampled(wl, samples, decode_steps=8)
 
 
 @pytest.mark.parametrize("budget", [128, 2048])
 def test_config3_other_budgets(budget):
-    wl = synth.config(3, layers=32, budget=budget, decode_steps=2)       # the stack bench.py times these budgets on
-    sampled(wl, [(5, 3), (30, 0)])
+    # the stack bench.py times these budgets on: 4 layers with all their KV heads, 10 more with one each
+    wl = synth.config(3, layers=32, budget=budget, decode_steps=4)
+    full = [(b, g) for b in (1, 12, 20, 30) for g in range(8)]
+    sampled(wl, full + [s for s in spread(32, 8, 10) if s[0] not in (1, 12, 20, 30)], decode_steps=4)
+
+
+def test_config3_decode_and_recomputation_loop():
+    # the stateful loop of Alg. 2 at full size: 16 steps of decode + recomputation branch over the whole
+    # 32-layer stack, the state of the sampled heads checked against the oracle at every step
+    wl = synth.config(3, layers=32, budget=512, decode_steps=16)
+    rep = sampled(wl, spread(32, 8, 8), decode_steps=16, recalibrate=True)
+    assert rep["recal_heads"] > 0
+
+
+def test_config2_decode_and_recomputation_loop_all_heads():
+    # one 8k-context layer, all 8 KV heads, 24 steps of Alg. 2 with the state carried on the GPU
+    wl = synth.config(2, decode_steps=24)
+    rep = sampled(wl, [(0, g) for g in range(8)], decode_steps=24, recalibrate=True)
+    assert rep["recal_heads"] > 0
 
 
 def test_config4_batch64_varlen():
-    wl = synth.config(4, decode_steps=2)
+    # the batched workload as stated: variable-length retained caches laid out contiguously behind an
+    # offsets array (capacity = budget + 0..40 rows per sequence); shortest, longest and 14 other
+    # sequences, all 8 KV heads of each
+    wl = synth.config(4, decode_steps=4)
     lens = wl.seq_lens
+    rng = np.random.default_rng(4)
+    caps = [min(wl.budget, n) + int(e) for n, e in zip(lens, rng.integers(0, 41, len(lens)))]
     b_short, b_long = int(np.argmin(lens)), int(np.argmax(lens))
-    sampled(wl, [(b_short, 0), (b_long, 7), (17, 4)])
+    seqs = sorted({b_short, b_long} | set(range(0, 64, 9)) | {5, 17, 26, 33, 41, 50, 58})
+    sampled(wl, [(b, g) for b in seqs for g in range(8)], decode_steps=4, capacities=caps)
+
+
+def test_config4_uniform_capacity_without_offsets():
+    # the same workload with one capacity for all: decode takes the form without the offsets array
+    wl = synth.config(4, decode_steps=2)
+    sampled(wl, spread(64, 8, 8), decode_steps=2)
 
 
 def test_config5_long_context_131k():
-    wl = synth.config(5, decode_steps=2)
-    sampled(wl, [(0, 2)])
+    # all 8 KV heads; the selection runs as the multi-workgroup chain (prefix > 32768)
+    wl = synth.config(5, decode_steps=6)
+    sampled(wl, [(0, g) for g in range(8)], decode_steps=6, recalibrate=True)
 
 
 def test_h2o_one_layer_32k_properties_and_samples():
@@ -67,7 +127,6 @@ def test_h2o_one_layer_32k_properties_and_samples():
     # oracle, conservation of probability mass over all columns, and the selection checked
     # against a brute-force ranking of the scores the GPU itself reports.
     from oracle import calidrop_ref as ref
-    from paper_2507_19906_amd import binding as cd
     wl = synth.config(3, layers=1, budget=512, decode_steps=1)
     n, G, D, B = wl.seq_lens[0], wl.group, wl.head_dim, wl.budget
     loc = B // 2
