@@ -29,9 +29,30 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
-# HBM bytes per decode launch measured with rocprofv3 counters on the default workload
-# (profiles/bench_cfg3_B512_pmc_hbm_bytes.md): FETCH_SIZE 33597.4 KiB x 2.0 + WRITE_SIZE 272 KiB x 1.0
-DECODE_TRAFFIC_BYTES_PMC = 69085933
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
+HBM_PROFILE = os.path.join(ROOT, "profiles", "bench_cfg3_B512_pmc_hbm_bytes.md")
+
+
+def decode_traffic_from_profile(kernel: str):
+    """HBM bytes per launch of `kernel` as the committed rocprofv3 counter summary states them
+    (FETCH_SIZE and WRITE_SIZE in KiB per launch, scaled by the factors the same file derives from a
+    plain 1 GiB copy).  None when the file is missing or lists the decode kernel under another name
+    (a summary that belongs to another build of the kernel must not be quoted for this one)."""
+    import re
+    try:
+        text = open(HBM_PROFILE).read()
+    except OSError:
+        return None, f"{os.path.relpath(HBM_PROFILE, ROOT)} not found"
+    m = re.search(r"scale factors are x([0-9.]+) \(fetch\) and x([0-9.]+) \(write\)", text)
+    row = [l for l in text.splitlines() if l.startswith("| `decode_fused_kernel")]
+    if not m or not row:
+        return None, "no decode kernel row / scale factors in the profile summary"
+    cells = [c.strip() for c in row[0].strip("|").split("|")]
+    name = cells[0].strip("`")
+    if name.replace(" ", "") != kernel.replace(" ", ""):
+        return None, f"profile summary lists {name}, this run timed {kernel}"
+    fetch_kib, write_kib = float(cells[2]), float(cells[3])
+    return int(round((fetch_kib * float(m.group(1)) + write_kib * float(m.group(2))) * 1024)), os.path.relpath(HBM_PROFILE, ROOT)
 
 
 def decode_bytes(wl, cache_len: int) -> int:
@@ -139,6 +160,117 @@ def machine_probes(dev, stream):
     return res
 
 
+def timed(fn, stream, n, warm=2):
+    """Mean microseconds per call of fn(i), HIP events on `stream` around n calls after `warm` calls."""
+    import torch
+    for i in range(warm):
+        fn(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(n):
+        fn(warm + i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n
+
+
+def other_configs(dev, stream):
+    """The other workloads of the brief, each through the same two entry points: the single 8k-context
+    layer (config 2), the batch of 64 variable-length sequences with the compressed caches packed behind an
+    offsets array (config 4) and the 131k-context layer (config 5).  Compress time per call, decode time per
+    call with the calls cycling over address-distinct copies of the compressed cache (more than the 256 MB
+    Infinity Cache in total whenever one call moves at least 16 MiB), and for the window scoring the time of
+    its first pass, taken as the difference between compress and compress with the window rows' log-sum-exp
+    supplied (which skips exactly that pass)."""
+    import numpy as np
+    import torch
+    from paper_2507_19906_amd import binding as cd
+    from paper_2507_19906_amd import synth
+    res = {}
+    for idx in (2, 4, 5):
+        wl = synth.config(idx, decode_steps=8)
+        x = synth.make_inputs(wl, device=dev)
+        p = cd.make_params(dtype=wl.dtype, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                           head_dim=wl.head_dim, window=wl.window, budget=wl.budget, pool_kernel=wl.pool_kernel,
+                           theta1=wl.theta1, theta2=wl.theta2)
+        caps = None
+        if idx == 4:        # variable capacities: budget + 0..40 rows per sequence, packed back to back
+            rng = np.random.default_rng(4)
+            caps = [min(wl.budget, n) + int(e) for n, e in zip(wl.seq_lens, rng.integers(0, 41, wl.batch))]
+        bufs = cd.CompressBuffers(p, wl.seq_lens, dev, capacities=caps)
+        comp_us = timed(lambda i: bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=stream), stream, 5)
+        G, w = wl.group, wl.window
+        nrb = -(-G * w // 128)
+        tab = bufs.region(cd.REGION_ROW_LSE).view(wl.batch, wl.n_kv_heads, nrb * 128)[:, :, :G * w]
+        win_lse = (tab.reshape(wl.batch, wl.n_q_heads, w) * 0.6931471805599453).contiguous()
+        comp_lse_us = timed(lambda i: bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=stream,
+                                                    win_lse=win_lse), stream, 5)
+        bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=stream)
+        torch.cuda.synchronize()
+        E = 2
+        tokens = sum(wl.seq_lens)
+        k_bytes = tokens * wl.n_kv_heads * wl.head_dim * E
+        flop = 2.0 * wl.n_q_heads * w * tokens * wl.head_dim                  # one Q_win K^T pass
+        pass1_us = comp_us - comp_lse_us
+        # decode: bytes of the live rows actually streamed
+        live = bufs.cache_lens.cpu().numpy().astype(np.int64)
+        dbytes = int(2 * wl.n_kv_heads * wl.head_dim * E * live.sum()
+                     + wl.batch * wl.n_q_heads * (wl.head_dim * E + (2 * wl.head_dim + 1) * 4 + wl.head_dim * E))
+        ncopy = max(2, -(-(512 << 20) // dbytes)) if dbytes >= (16 << 20) else 1
+        kc = [bufs.k_c] + [bufs.k_c.clone() for _ in range(ncopy - 1)]
+        vc = [bufs.v_c] + [bufs.v_c.clone() for _ in range(ncopy - 1)]
+        offs = None if bufs.uniform else bufs.cache_offsets
+        T = x["q_dec"].shape[0]
+
+        def dec(i):
+            cd.calidrop_decode(p, x["q_dec"][i % T], kc[i % ncopy], vc[i % ncopy], offs, bufs.cache_lens, bufs.max_cache_len,
+                               bufs.c_q, bufs.c_out, bufs.c_lse, bufs.out, bufs.a_lse, bufs.flags, bufs.ws_decode, stream)
+        dec_us = timed(dec, stream, 64 if ncopy > 1 else 200, warm=8)
+        r = {"workload": wl.name, "tokens": tokens, "compress_us_per_call": comp_us,
+             "compress_us_per_call_with_supplied_window_lse": comp_lse_us,
+             "compress_GBps_vs_read_kv_once": 2 * k_bytes / comp_us / 1e3,
+             "scoring_pass1_us_by_difference": pass1_us,
+             "scoring_pass1_TFLOPps": flop / pass1_us / 1e6 if pass1_us > 0 else None,
+             "scoring_pass1_pct_bf16_mfma_peak": 100.0 * flop / pass1_us / 1e6 / MFMA_BF16_PEAK_TFLOPS if pass1_us > 0 else None,
+             "scoring_pass1_K_GBps": k_bytes / pass1_us / 1e3 if pass1_us > 0 else None,
+             "scoring_flop_per_K_byte": w * G,
+             "decode_us_per_call": dec_us, "decode_bytes_per_call": dbytes, "cache_copies_rotated": ncopy,
+             "cache_offsets_array": offs is not None}
+        if ncopy > 1:
+            r["decode_GBps"] = dbytes / dec_us / 1e3
+            r["decode_pct_hbm_peak"] = 100.0 * dbytes / dec_us / 1e3 / HBM_PEAK_GBPS
+        else:
+            r["decode_note"] = "under 16 MiB per call: bound by launch and memory latency, no bandwidth figure"
+        res[f"config{idx}"] = r
+        del bufs, kc, vc, x
+        torch.cuda.empty_cache()
+    return res
+
+
+def alg2_loop(cd, bufs, x, T, stream):
+    """The complete decode step of Alg. 2 with the state carried on the GPU: calidrop_decode, then
+    calidrop_recalibrate for the heads it flagged (rho < theta1).  The headline figure times the
+    decode calls alone; this says what the recomputation branch adds on these synthetic queries and
+    how many heads take it."""
+    import torch
+    steps = min(T, 64)
+    bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=stream)
+    hist = torch.zeros(4, dtype=torch.int64, device=bufs.flags.device)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for t in range(steps):
+        bufs.decode(x["q_dec"][t], stream=stream)
+        hist += torch.bincount(bufs.flags.flatten().long(), minlength=4)[:4]
+        bufs.recalibrate(x["q_dec"][t], x["k"], x["v"], x["seq_offsets"], stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    h = hist.cpu().tolist()
+    return {"steps": steps, "us_per_step_decode_plus_recalibrate": e0.elapsed_time(e1) * 1e3 / steps,
+            "flags_after_decode_none_calibrated_recompute": h[:3],
+            "fraction_of_heads_recomputed_per_step": h[2] / max(1, sum(h)),
+            "note": "includes a small flag-histogram kernel per step"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -180,6 +312,7 @@ def main():
         del src, dst
 
     wl = synth.config(3, layers=args.layers, budget=args.budget, decode_steps=args.decode_steps)
+    default_cfg_early = args.budget == 512 and args.layers == 32
     x = synth.make_inputs(wl, device=dev)
     p = cd.make_params(dtype=wl.dtype, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                        head_dim=wl.head_dim, window=wl.window, budget=wl.budget, pool_kernel=wl.pool_kernel,
@@ -410,11 +543,21 @@ def main():
         del b4, qf
 
     probes = machine_probes(dev, stream) if not args.no_extra else None
+    loop = alg2_loop(cd, bufs, x, T, stream) if not args.no_extra else None
+    flags_last = torch.bincount(bufs.flags.flatten().long(), minlength=4)[:3].cpu().tolist()
+    others = None
+    if not args.no_extra and default_cfg_early:
+        del k_copies, v_copies
+        torch.cuda.empty_cache()
+        others = other_configs(dev, stream)
 
     gbps = dbytes / (dec * 1e-3) / 1e9
     # window scoring (the two MFMA passes of compress): 2*Hq*w*n*D flop per layer and pass
     score_flop = 2.0 * wl.n_q_heads * wl.window * wl.seq_lens[0] * wl.head_dim * wl.batch
-    default_cfg = args.budget == 512 and args.layers == 32
+    default_cfg = default_cfg_early
+    # the kernel calidrop_decode launches for this shape (4 waves per workgroup when the pairs fill the chip)
+    decode_kernel = "decode_fused_kernel<bf16_t, 128, %d>" % (4 if wl.batch * wl.n_kv_heads >= 192 or wl.budget <= 128 else 8)
+    traffic, traffic_src = decode_traffic_from_profile(decode_kernel) if default_cfg else (None, "not the profiled workload")
     out = {
         "metric": "decode attn GB/s (% HBM peak) + compress us/layer at 32k ctx, budget 512",
         "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -443,11 +586,16 @@ def main():
         "recalibrate_all_heads_from_packed_evicted": packed,
         "compress_h2o_strategy": h2o,
         "machine_probes": probes,
-        "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel<bf16,128,8>",
+        "alg2_loop_with_recomputation": loop,
+        "flags_of_last_decode_call_none_calibrated_recompute": flags_last,
+        "timed_step_note": "one step = compress + T decode calls; heads that a decode call flags for recomputation "
+                           "(rho < theta1) are not recomputed inside the timed step - see alg2_loop_with_recomputation",
+        "other_configs": others,
+        "roofline": {"bound": "hbm", "kernel": decode_kernel,
                      "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
-                     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of this kernel on this workload,
-                     # scaled by the counters' readings for a plain 1 GiB copy (x2.0 / x1.0)
-                     "traffic": DECODE_TRAFFIC_BYTES_PMC if default_cfg else None,
+                     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of this kernel on this workload, read
+                     # from the committed counter summary (null when that summary is of another kernel build)
+                     "traffic": traffic, "traffic_source": traffic_src,
                      "duration_us": dec * 1e3,
                      "note": "duration = HIP-event time over all decode calls of the timed region / calls; "
                              "one kernel per call"},

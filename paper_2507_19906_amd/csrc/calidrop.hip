@@ -380,12 +380,14 @@ int decode_impl(const calidrop_params* p, const void* q_t, const void* k_c, cons
     fa.c_q = c_q; fa.c_out = c_out; fa.c_lse = c_lse; fa.out = out; fa.a_lse = a_lse; fa.flags = flags;
     const int tiles = ceil_div(max_cache_len, cd::kTileRows);
     const size_t lds_per_wave = static_cast<size_t>(G) * (D + 2) * sizeof(float);
-    // 8 waves per workgroup for mid-sized caches (one or two tiles per wave) and whenever the pairs
-    // do not fill the chip: with 1024 rows or more and enough pairs, 4-wave workgroups - three of which fit a compute unit, so that one's merge overlaps the
-    // others' streaming - measured 2-4 % faster (256 MiB per call: 6.6 vs 6.3 TB/s)
+    // 4 waves per workgroup when the pairs fill the chip (measured against 8 waves, same call: 12.8 vs
+    // 13.0 us at 512 rows; 40.5 vs 42.0 us at 2048 rows, where three such workgroups share a compute
+    // unit and one's merge overlaps the others' streaming) and for caches of at most 4 tiles; 8 waves
+    // when few pairs have to cover the latency with more rows in flight each.
     const bool many_pairs = p->batch * p->n_kv_heads >= kFusedMinPairs;
-    int nw = (tiles <= 4 || (tiles >= 32 && many_pairs)) ? 4 : 8;
+    int nw = (tiles <= 4 || many_pairs) ? 4 : 8;
     while (nw > 4 && nw * lds_per_wave > 48 * 1024) nw /= 2;     // what a launch may use without raising the limit
+    fa.xcd_blocks = (tiles >= 32 && p->batch % 8 == 0) ? 1 : 0;
     const dim3 grid(p->n_kv_heads, p->batch);
     const size_t lds = nw * lds_per_wave;
     if (nw == 8) hipLaunchKernelGGL((cd::decode_fused_kernel<T, D, 8>), grid, dim3(512), lds, st, fa);

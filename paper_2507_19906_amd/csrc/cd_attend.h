@@ -71,6 +71,13 @@ struct AttendWave {
     l = 0.f;
   }
 
+  // The K rows of the wave's first tile, requested before the number of live rows is known (it may
+  // still be on its way from memory): `clamp` is a row count that is certainly addressable.
+  u32x4 kpre[2][NK];
+  __device__ __forceinline__ void request_first_k(const T* kbase, int row0, int clamp, int i, int c) {
+    load_k(kbase, row0, clamp, i, c, kpre);
+  }
+
   __device__ __forceinline__ void load_k(const T* kbase, int row0, int rows, int i, int c, u32x4 (&kf)[2][NK]) const {
 #pragma unroll
     for (int g2 = 0; g2 < 2; ++g2) {
@@ -159,21 +166,28 @@ struct AttendWave {
   struct NoWork { __device__ __forceinline__ void operator()() const {} };
   // `while_waiting` runs once, after the loads of the wave's first tile have been issued and before
   // anything waits for them: arithmetic placed there is hidden behind the memory latency.
+  // `k_requested`: the K rows of the wave's first tile are already on their way into kpre
+  // (request_first_k).
   template <bool kPrefetch = true, bool kLogits = false, typename F = NoWork>
   __device__ __forceinline__ void run(const T* kbase, const T* vbase, const uint32_t* bm, int rows, int row_first,
                                       int row_end, int row_step, float sl2, int i, int c,
-                                      const float* zhead = nullptr, bool zvalid = false, int first_clamp = 0,
+                                      const float* zhead = nullptr, bool zvalid = false, bool k_requested = false,
                                       F while_waiting = F()) {
     u32x4 kf[2][NK];
     f32x4 zf[2];
-    if constexpr (!kLogits) {
-      // first_clamp > 0: the K rows of the first tile are requested before `rows` is known (it may
-      // still be on its way from memory), clamped to a row count that is certainly addressable
-      if (first_clamp > 0) load_k(kbase, row_first, first_clamp, i, c, kf);
-    }
     if (row_first >= row_end) { while_waiting(); return; }
-    if constexpr (kLogits) load_z(zhead, row_first, c, zvalid, zf);
-    else if (first_clamp <= 0) load_k(kbase, row_first, rows, i, c, kf);
+    if constexpr (kLogits) {
+      load_z(zhead, row_first, c, zvalid, zf);
+    } else {
+      if (k_requested) {
+#pragma unroll
+        for (int g2 = 0; g2 < 2; ++g2)
+#pragma unroll
+          for (int kk = 0; kk < NK; ++kk) kf[g2][kk] = kpre[g2][kk];
+      } else {
+        load_k(kbase, row_first, rows, i, c, kf);
+      }
+    }
     for (int row0 = row_first; row0 < row_end; row0 += row_step) {
       // V of this tile first, then K of the next tile: both in flight during the QK product
       u32x4 vf[8];
@@ -462,6 +476,7 @@ struct DecodeFusedArgs {
   const void* q; const void* k; const void* v;
   const int32_t* row_off; const int32_t* row_len;
   int batch, Hq, Hkv, G, max_len;
+  int xcd_blocks;   // 1: workgroups are re-dealt so that each XCD takes a contiguous block of sequences (batch % 8 == 0)
   float sl2, theta1, theta2;
   const float* c_q; const float* c_out; const float* c_lse;
   void* out; float* a_lse; uint8_t* flags;
@@ -489,11 +504,21 @@ __device__ __forceinline__ float cosine_of(const float (&q)[N], const float (&cv
 #endif
 template <typename T, int D, int NW>
 __global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fused_kernel(DecodeFusedArgs a) {
-  const int g = blockIdx.x, b = blockIdx.y;
+  // Workgroups are dealt to the 8 XCDs round-robin in launch order.  With xcd_blocks the launch index
+  // is re-read so that XCD x takes the sequences [x * batch/8, (x+1) * batch/8) with all their heads:
+  // the outputs, log-sum-exps and flags of neighbouring heads and sequences, which share cache lines,
+  // are then written through one L2 instead of eight (measured on long caches: 2-3 % per call).
+  int g = blockIdx.x, b = blockIdx.y;
+  if (a.xcd_blocks) {
+    const int L = static_cast<int>(blockIdx.x + gridDim.x * blockIdx.y);
+    const int slot = L >> 3;
+    g = slot % static_cast<int>(gridDim.x);
+    b = (L & 7) * static_cast<int>(gridDim.y >> 3) + slot / static_cast<int>(gridDim.x);
+  }
   const int lane = threadIdx.x & 63, wv = wave_index();
   const int i = lane & 15, c = lane >> 4;
   // row_off == NULL: every sequence has capacity max_len and starts at b * max_len, so the K/V
-  // addresses need no load and the first K tile can be requested before row_len[b] has arrived
+  // addresses need no load
   const bool uniform = a.row_off == nullptr;
   const int off0 = uniform ? b * a.max_len : a.row_off[b];
   const int cap = uniform ? a.max_len : a.row_off[b + 1] - off0;
@@ -504,8 +529,20 @@ __global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fuse
   const T* vbase = static_cast<const T*>(a.v) + head_tok * D;
   const T* qbase = static_cast<const T*>(a.q) + static_cast<int64_t>(b * a.Hq + g * a.G) * D;
 
-  // Operands of the gate/merge tail, fetched up front so they arrive with the K/V stream
-  // (wave wv finishes head wv; groups larger than the wave count loop and reload).
+  AttendWave<T, D> w;
+  w.init(qbase + static_cast<int64_t>(i) * D, i < a.G, c);
+
+  // The wave's first K rows are requested at once, clamped to the capacity (addressable whatever the
+  // number of live rows turns out to be; rows beyond it are masked later): with a uniform layout
+  // not a single load has to return before this request can go out.
+  if (cap > 0) w.request_first_k(kbase, wv * kTileRows, cap, i, c);
+
+  // Operands of the gate/merge tail (wave wv finishes head wv; groups larger than the wave count loop
+  // and reload), requested right behind those K rows - nothing may delay that request - and only
+  // looked at (not even converted) once the first tile's loads are all on their way: a conversion at
+  // the point of the load would make the wave wait for the data there, a full memory round trip
+  // before its stream has started.
+  uint32_t qraw[D / 64];      // storage bits of the query elements
   float qd[D / 64], cq[D / 64], co[D / 64];
   float c_lse0 = -INFINITY;
   const bool has_tail = wv < a.G;
@@ -513,15 +550,12 @@ __global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fuse
     const int64_t hd = static_cast<int64_t>(b * a.Hq + g * a.G + wv);
 #pragma unroll
     for (int u = 0; u < D / 64; ++u) {
-      qd[u] = load_elem<T>(qbase, static_cast<int64_t>(wv) * D + lane + 64 * u);
+      qraw[u] = load_bits<T>(qbase, static_cast<int64_t>(wv) * D + lane + 64 * u);
       cq[u] = a.c_q[hd * D + lane + 64 * u];
       co[u] = a.c_out[hd * D + lane + 64 * u];
     }
     c_lse0 = a.c_lse[hd];
   }
-
-  AttendWave<T, D> w;
-  w.init(qbase + static_cast<int64_t>(i) * D, i < a.G, c);
   // (issuing the loads of both tiles of a wave before any arithmetic was measured slower than this
   // one-tile-ahead pipeline: 5 % more time per call at 512 rows)
   // The gate of Alg. 2 step 2 depends on the query and C_q only: wave wv works out the cosine of its
@@ -530,10 +564,19 @@ __global__ __launch_bounds__(NW * 64, CD_DECODE_WAVES_PER_SIMD) void decode_fuse
   // when they sit between the merge barrier and the output store instead.
   float rho0 = 0.f;
   auto gate_cosine = [&]() {
-    if (has_tail) rho0 = cosine_of(qd, cq);
+    if (has_tail) {
+#pragma unroll
+      for (int u = 0; u < D / 64; ++u) {
+        // (the empty statement pins the conversion here: the compiler would otherwise move it, and the
+        // wait for the data that comes with it, up to the load)
+        asm volatile("" : "+v"(qraw[u]) : : "memory");
+        qd[u] = bits_to_f32<T>(qraw[u]);
+      }
+      rho0 = cosine_of(qd, cq);
+    }
   };
   w.template run<true, false>(kbase, vbase, nullptr, rows, wv * kTileRows, rows, NW * kTileRows, a.sl2, i, c, nullptr,
-                              false, (uniform && (wv + 1) * kTileRows <= cap) ? cap : 0, gate_cosine);
+                              false, true, gate_cosine);
 
   extern __shared__ __attribute__((aligned(16))) float s_dyn[];                 // [NW][G][D] outputs, then [NW][G] (max, sum)
   float* s_o = s_dyn;

@@ -105,6 +105,17 @@ template <> __device__ __forceinline__ float load_elem<bf16_t>(const bf16_t* p, 
 }
 template <> __device__ __forceinline__ float load_elem<float>(const float* p, int64_t i) { return p[i]; }
 
+// An element as its storage bits (zero-extended), and those bits as a float: a load split from its
+// conversion, for places where the value must not be touched until later.
+template <typename T> __device__ __forceinline__ uint32_t load_bits(const T* p, int64_t i);
+template <> __device__ __forceinline__ uint32_t load_bits<bf16_t>(const bf16_t* p, int64_t i) { return p[i].bits; }
+template <> __device__ __forceinline__ uint32_t load_bits<float>(const float* p, int64_t i) {
+  return __builtin_bit_cast(uint32_t, p[i]);
+}
+template <typename T> __device__ __forceinline__ float bits_to_f32(uint32_t u);
+template <> __device__ __forceinline__ float bits_to_f32<bf16_t>(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+template <> __device__ __forceinline__ float bits_to_f32<float>(uint32_t u) { return __builtin_bit_cast(float, u); }
+
 template <typename T> __device__ __forceinline__ void store_elem(T* p, int64_t i, float v);
 template <> __device__ __forceinline__ void store_elem<bf16_t>(bf16_t* p, int64_t i, float v) {
   p[i].bits = f32_to_bf16(v);

@@ -648,3 +648,70 @@ def test_compress_with_the_window_log_sum_exp_supplied(dtype, D, lens, w, B, m):
     bufs2 = H.gpu_compress(wl, x, win_lse=skew, calib_size=m)
     for b in range(wl.batch):
         H.check_compress(wl, x, bufs2, b, win_lse=skew)
+
+
+@pytest.mark.parametrize("wl", [
+    small("bf16", 8, 2, 128, [900, 40, 2100], 16, 128, 5, T=2, name="no_export_8_per_thread"),
+    small("bf16", 8, 2, 64, [9000, 12000], 16, 300, 5, T=2, name="no_export_16_per_thread"),
+    small("fp32", 4, 2, 64, [20000, 500], 16, 200, 7, T=2, name="no_export_32_per_thread"),
+], ids=lambda w: w.name)
+def test_compress_with_default_options_no_score_export(wl):
+    # flags = 0 is what a caller (and the benchmark) uses: the selection kernel then skips the store
+    # of the pooled scores.  Same checks as everywhere else minus the scores, and bit-identical
+    # outputs to the call that exports them.
+    x = to_dev(synth.make_inputs(wl, 88))
+    bufs = H.gpu_compress(wl, x, flags=0)
+    twin = H.gpu_compress(wl, x, flags=cd.OPT_WRITE_SCORES)
+    rep = {}
+    for b in range(wl.batch):
+        H.check_compress(wl, x, bufs, b, report=rep)
+    assert "score_rel_err" not in rep
+    for name in ["indices", "k_c", "v_c", "c_out", "c_lse", "c_q", "cache_lens"]:
+        assert torch.equal(getattr(bufs, name), getattr(twin, name)), name
+    for t in range(2):
+        bufs.decode(x["q_dec"][t])
+        torch.cuda.synchronize()
+        for b in range(wl.batch):
+            H.check_decode_step(wl, bufs, x["q_dec"][t], b, report=rep)
+
+
+def test_first_library_call_of_a_process_may_be_under_stream_capture():
+    # the only host-side setting the library makes (the dynamic-LDS limit of the selection kernel, once
+    # per device) enqueues nothing, so even the very first call of a process can be captured: a fresh
+    # interpreter captures compress + decode of a prompt whose selection needs more than 48 KiB of LDS
+    # without any warm-up, replays the graph and compares with eager calls made afterwards
+    import subprocess
+    import sys
+    code = r"""
+import torch
+from paper_2507_19906_amd import binding as cd, synth
+wl = synth.Workload("capture_first", 2, 8, 2, 128, [20000, 700], 16, 128, 5, "bf16", 1)
+x = {k: v.to("cuda:0") for k, v in synth.make_inputs(wl, 501).items()}
+p = cd.make_params(dtype="bf16", batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, window=16, budget=128, pool_kernel=5)
+a, b = cd.CompressBuffers(p, wl.seq_lens, "cuda:0"), cd.CompressBuffers(p, wl.seq_lens, "cuda:0")
+torch.cuda.synchronize()
+side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+with torch.cuda.stream(side):
+    with torch.cuda.graph(graph, stream=side):
+        st = torch.cuda.current_stream()
+        a.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=st)
+        a.decode(x["q_dec"][0], stream=st)
+torch.cuda.synchronize()
+for rep in range(2):
+    a.out.zero_(); a.indices.zero_(); a.c_out.zero_()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    if rep == 0:
+        b.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"])
+        b.decode(x["q_dec"][0])
+        torch.cuda.synchronize()
+    for name in ("indices", "k_c", "v_c", "c_out", "c_lse", "out", "a_lse", "flags"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), (rep, name)
+assert int(a.indices[0, 0, -1]) == 19999
+print("captured first call ok")
+"""
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=240, cwd=root)
+    assert r.returncode == 0 and "captured first call ok" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
