@@ -200,8 +200,7 @@ def other_configs(dev, stream):
         bufs = cd.CompressBuffers(p, wl.seq_lens, dev, capacities=caps)
         comp_us = timed(lambda i: bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=stream), stream, 5)
         G, w = wl.group, wl.window
-        nrb = -(-G * w // 128)
-        tab = bufs.region(cd.REGION_ROW_LSE).view(wl.batch, wl.n_kv_heads, nrb * 128)[:, :, :G * w]
+        tab = bufs.region(cd.REGION_ROW_LSE).view(wl.batch, wl.n_kv_heads, -1)[:, :, :G * w]
         win_lse = (tab.reshape(wl.batch, wl.n_q_heads, w) * 0.6931471805599453).contiguous()
         comp_lse_us = timed(lambda i: bufs.compress(x["q_win"], x["k"], x["v"], x["seq_offsets"], stream=stream,
                                                     win_lse=win_lse), stream, 5)
@@ -451,9 +450,9 @@ def main():
     # taken from the library's own row table of the last compress call (log2 units, rows of a KV
     # head = head-in-group x window index), which is what such a caller would have.
     comp_lse_us = None
-    if not args.no_extra and wl.n_q_heads // wl.n_kv_heads * wl.window <= 128:
+    if not args.no_extra:
         G_ = wl.n_q_heads // wl.n_kv_heads
-        tab = bufs.region(cd.REGION_ROW_LSE).view(wl.batch, wl.n_kv_heads, 128)[:, :, :G_ * wl.window]
+        tab = bufs.region(cd.REGION_ROW_LSE).view(wl.batch, wl.n_kv_heads, -1)[:, :, :G_ * wl.window]
         win_lse = (tab.reshape(wl.batch, wl.n_q_heads, wl.window) * 0.6931471805599453).contiguous()
         times = []
         for it in range(5):

@@ -112,9 +112,10 @@ size_t calidrop_decode_workspace_bytes(const calidrop_params* p, int32_t max_cac
 /* Named regions inside the compress workspace, for inspection by tests and tools after the
  * stream has finished (SCORE needs CALIDROP_OPT_WRITE_SCORES in the compress call's params).
  * Layouts:
- *   ROW_LSE   float [batch][Hkv][NRB*128]: per window-query row, log2 of its softmax
- *             denominator over all visible keys (logits in log2 units); rows of a KV head are
- *             ordered (query head in group, window position); NRB = ceil(G*w / 128).
+ *   ROW_LSE   float [batch][Hkv][S]: per window-query row, log2 of its softmax denominator over
+ *             all visible keys (logits in log2 units); rows of a KV head are ordered (query head in
+ *             group, window position) and padded with +inf to the stride S = bytes / (batch*Hkv*4)
+ *             (G*w rounded up to a multiple of 128, or of 256 when G*w > 128).
  *   SCORE     float, packed like K with D = 1: pooled score of prefix position j of KV head g
  *             of sequence b at [seq_offsets[b]*Hkv + g*n_b + j], j < n_b - w.
  * Returns CALIDROP_OK and fills offset/bytes, or CALIDROP_EINVAL.                            */

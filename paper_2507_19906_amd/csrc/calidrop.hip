@@ -120,17 +120,18 @@ SplitPlan plan_splits(int heads_kv_total, int max_rows) {
 
 struct CompressLayout {
   size_t rowpart, row_lse, vote, score, bitmap, cal_logit, part_o, part_ml, sel_hist, sel_cnt, total;
-  int NRB, NCH, W32, chunk_keys, zstride, NSEG;
+  int RB, NRB, NCH, W32, chunk_keys, zstride, NSEG;
   SplitPlan sp;
 };
 
 CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, int32_t max_seq_len) {
   CompressLayout L{};
   const int G = p->n_q_heads / p->n_kv_heads;
-  L.NRB = ceil_div(G * p->window, cd::kRowBlock);
-  {  // keys per scoring workgroup: as large as keeps >= ~4096 workgroups in the launch, 256..2048
+  L.RB = G * p->window > cd::kRowBlock ? 2 * cd::kRowBlock : cd::kRowBlock;     // 256-row blocks: such heads stream K once
+  L.NRB = ceil_div(G * p->window, L.RB);
+  {  // keys per scoring workgroup: as large as keeps >= ~2048 workgroups in the launch, 256..2048
     const int64_t groups256 = static_cast<int64_t>(p->batch) * p->n_kv_heads * L.NRB * ceil_div(max_seq_len, cd::kMinChunkKeys);
-    int mult = static_cast<int>(groups256 / 4096);
+    int mult = static_cast<int>(groups256 / 2048);
     if (mult < 1) mult = 1;
     if (mult > 8) mult = 8;
     L.chunk_keys = mult * cd::kMinChunkKeys;
@@ -138,7 +139,7 @@ CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, i
   L.NCH = ceil_div(max_seq_len, L.chunk_keys);
   L.W32 = ceil_div(max_seq_len, 64) * 2;
   L.sp = plan_splits(p->batch * p->n_kv_heads, max_seq_len);
-  const size_t rows = static_cast<size_t>(p->batch) * p->n_kv_heads * L.NRB * cd::kRowBlock;
+  const size_t rows = static_cast<size_t>(p->batch) * p->n_kv_heads * L.NRB * L.RB;
   const size_t toks = static_cast<size_t>(total_tokens) * p->n_kv_heads;
   size_t off = 0;
   L.rowpart = off; off += round256(rows * L.NCH * sizeof(float2));
@@ -196,16 +197,19 @@ int launch_status(const char* what) {
 // stream capture) only launch.
 constexpr size_t kSelMaxLdsBytes = (static_cast<size_t>(cd::kSelMaxLdsKeys) + cd::kSelMaxLdsKeys / 32 + 1) * sizeof(float);
 constexpr int kMaxDevices = 64;
-std::atomic<uint8_t> g_sel_lds_ready[3][kMaxDevices];     // zero-initialised: nothing raised yet
+constexpr int kLdsSlots = 16;                             // kernels that ask for more than 48 KiB of dynamic LDS
+enum { kLdsSelect8 = 0, kLdsSelect16, kLdsSelect32, kLdsVotes };   // first slot of each family (votes: + variant)
+std::atomic<uint8_t> g_lds_ready[kLdsSlots][kMaxDevices]; // zero-initialised: nothing raised yet
 
-int ensure_select_lds(int variant, const void* fn) {
+// `bytes` is the largest size any call can ask of this kernel, so one setting per (slot, device) is enough.
+int ensure_kernel_lds(int slot, const void* fn, size_t bytes, const char* what) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
     return fail(CALIDROP_EHIP, "hipGetDevice failed or device index %d is beyond %d", dev, kMaxDevices - 1);
-  if (g_sel_lds_ready[variant][dev].load(std::memory_order_acquire)) return CALIDROP_OK;
-  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kSelMaxLdsBytes));
-  if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(select_gather): %s", hipGetErrorString(e));
-  g_sel_lds_ready[variant][dev].store(1, std::memory_order_release);
+  if (g_lds_ready[slot][dev].load(std::memory_order_acquire)) return CALIDROP_OK;
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+  if (e != hipSuccess) return fail(CALIDROP_EHIP, "hipFuncSetAttribute(%s): %s", what, hipGetErrorString(e));
+  g_lds_ready[slot][dev].store(1, std::memory_order_release);
   return CALIDROP_OK;
 }
 
@@ -249,7 +253,7 @@ int run_selection(const calidrop_params* p, int window, int pool_k, int max_seq_
     const void* fn = per == 8    ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 8>)
                      : per == 16 ? reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 16>)
                                  : reinterpret_cast<const void*>(&cd::select_gather_lds_kernel<cd::kSelThreads, 32>);
-    if ((rc = ensure_select_lds(per == 8 ? 0 : per == 16 ? 1 : 2, fn))) return rc;
+    if ((rc = ensure_kernel_lds(per == 8 ? kLdsSelect8 : per == 16 ? kLdsSelect16 : kLdsSelect32, fn, kSelMaxLdsBytes, "select_gather"))) return rc;
     const dim3 grid(bg), block(cd::kSelThreads);
     if (per == 8) hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 8>), grid, block, lds, st, se);
     else if (per == 16) hipLaunchKernelGGL((cd::select_gather_lds_kernel<cd::kSelThreads, 16>), grid, block, lds, st, se);
@@ -292,7 +296,7 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   cd::ScoreArgs sa{};
   sa.q_win = q_win; sa.k = k; sa.seq_off = seq_offsets; sa.total_tokens = total_tokens;
   sa.batch = p->batch; sa.Hq = p->n_q_heads; sa.Hkv = p->n_kv_heads; sa.G = G; sa.w = p->window;
-  sa.B = p->budget; sa.R = G * p->window; sa.NRB = L.NRB; sa.NCH = L.NCH; sa.max_seq_len = max_seq_len;
+  sa.B = p->budget; sa.R = G * p->window; sa.RB = L.RB; sa.row_stride = L.NRB * L.RB; sa.NRB = L.NRB; sa.NCH = L.NCH; sa.max_seq_len = max_seq_len;
   sa.pool_k = p->pool_kernel; sa.sl2 = sl2; sa.chunk_keys = L.chunk_keys;
   // K of the whole call well inside the 256 MB last-level cache: pass 1 reads it with cached loads so
   // that pass 2 finds it there; larger calls stream it both times
@@ -310,18 +314,21 @@ int compress_impl(const calidrop_params* p, const void* q_win, const void* k, co
   const int bg = p->batch * p->n_kv_heads;
   if (max_seq_len > p->budget) {       // otherwise no sequence can need eviction
     dim3 grid_s(L.NCH, bg * L.NRB);
-    const int64_t rows = static_cast<int64_t>(bg) * L.NRB * cd::kRowBlock;
+    const int64_t rows = static_cast<int64_t>(bg) * L.NRB * L.RB;
     if (win_lse) {      // pass 1 is the caller's: only a unit conversion into the row table
       hipLaunchKernelGGL(cd::rowlse_import_kernel, dim3(static_cast<unsigned>((rows + 255) / 256)), dim3(256), 0, st, sa,
                          win_lse);
       if ((rc = launch_status("rowlse_import"))) return rc;
     } else {
-      hipLaunchKernelGGL((cd::score_rowstats_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
+      if (L.RB == 256) hipLaunchKernelGGL((cd::score_rowstats_direct_kernel<T, D, 4>), grid_s, dim3(256), 0, st, sa);
+      else hipLaunchKernelGGL((cd::score_rowstats_direct_kernel<T, D, 2>), grid_s, dim3(256), 0, st, sa);
       if ((rc = launch_status("score_rowstats"))) return rc;
-      hipLaunchKernelGGL(cd::rowstats_merge_kernel, dim3(static_cast<unsigned>((rows + 255) / 256)), dim3(256), 0, st, sa);
+      if (L.NCH > 64) hipLaunchKernelGGL(cd::rowstats_merge_kernel<64>, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, sa);
+      else hipLaunchKernelGGL(cd::rowstats_merge_kernel<16>, dim3(static_cast<unsigned>((rows + 15) / 16)), dim3(256), 0, st, sa);
       if ((rc = launch_status("rowstats_merge"))) return rc;
     }
-    hipLaunchKernelGGL((cd::score_votes_kernel<T, D>), grid_s, dim3(256), 0, st, sa);
+    if (L.RB == 256) hipLaunchKernelGGL((cd::score_votes_kernel<T, D, 8>), grid_s, dim3(512), 0, st, sa);
+    else hipLaunchKernelGGL((cd::score_votes_kernel<T, D, 4>), grid_s, dim3(256), 0, st, sa);
     if ((rc = launch_status("score_votes"))) return rc;
   }
 
@@ -724,7 +731,7 @@ int calidrop_compress_workspace_region(const calidrop_params* p_in, int64_t tota
   const CompressLayout L = compress_layout(p, total_tokens, max_seq_len);
   if (region == CALIDROP_REGION_ROW_LSE) {
     *offset = L.row_lse;
-    *bytes = static_cast<size_t>(p->batch) * p->n_kv_heads * L.NRB * cd::kRowBlock * sizeof(float);
+    *bytes = static_cast<size_t>(p->batch) * p->n_kv_heads * L.NRB * L.RB * sizeof(float);
   } else if (region == CALIDROP_REGION_SCORE) {
     *offset = L.score;
     *bytes = static_cast<size_t>(total_tokens) * p->n_kv_heads * sizeof(float);

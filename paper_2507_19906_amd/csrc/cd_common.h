@@ -59,6 +59,11 @@ __device__ __forceinline__ void load_to_lds16(const void* g, void* lds) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                    (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
 }
+// the same with the non-temporal hint (rows that are read once and not again soon)
+__device__ __forceinline__ void load_to_lds16_stream(const void* g, void* lds) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)lds, 16, 0, 2);
+}
 __device__ __forceinline__ void load_to_lds4(const void* g, void* lds) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                    (__attribute__((address_space(3))) void*)lds, 4, 0, 0);
