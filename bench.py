@@ -174,7 +174,7 @@ def timed(fn, stream, n, warm=2):
     return e0.elapsed_time(e1) * 1e3 / n
 
 
-def other_configs(dev, stream):
+def other_configs(dev, stream, which=(2, 4, 5)):
     """The other workloads of the brief, each through the same two entry points: the single 8k-context
     layer (config 2), the batch of 64 variable-length sequences with the compressed caches packed behind an
     offsets array (config 4) and the 131k-context layer (config 5).  Compress time per call, decode time per
@@ -187,7 +187,7 @@ def other_configs(dev, stream):
     from paper_2507_19906_amd import binding as cd
     from paper_2507_19906_amd import synth
     res = {}
-    for idx in (2, 4, 5):
+    for idx in which:
         wl = synth.config(idx, decode_steps=8)
         x = synth.make_inputs(wl, device=dev)
         p = cd.make_params(dtype=wl.dtype, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
@@ -283,6 +283,9 @@ def main():
     ap.add_argument("--offset-array", action="store_true",
                     help="pass cache_offsets to calidrop_decode (default: NULL = uniform capacity)")
     ap.add_argument("--no-extra", action="store_true", help="skip the additional budget-2048 decode measurement")
+    ap.add_argument("--profile-config", type=int, choices=(2, 4, 5), default=0,
+                    help="run only this other configuration (compress and decode calls, no headline workload) and print "
+                         "its figures: the command the rocprofv3 summaries of configs 2, 4 and 5 are made with")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy 4 times (calibrates the profiler's HBM byte counters)")
     args = ap.parse_args()
@@ -309,6 +312,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.profile_config:
+        print(json.dumps(other_configs(dev, torch.cuda.current_stream(), which=(args.profile_config,))))
+        return
 
     wl = synth.config(3, layers=args.layers, budget=args.budget, decode_steps=args.decode_steps)
     default_cfg_early = args.budget == 512 and args.layers == 32
