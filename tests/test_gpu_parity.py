@@ -69,6 +69,12 @@ def test_config2_bf16_llama8b_8k():
     # longest prefix one workgroup selects over (32768 positions), heads starting 1, 2 and 3 floats
     # past a 16-byte boundary in the vote buffer, and shorter odd-length neighbours
     small("bf16", 4, 4, 64, [32768 + 17, 8193 + 17, 16390 + 17], 17, 90, 5, T=1, name="full_length_prefix_misaligned_heads"),
+    # more than 128 window rows per KV head: 256-row blocks (K streamed once per pass), one full, one
+    # with a ragged second block (384 rows), one in fp32, one with a window that is no multiple of 4
+    small("bf16", 32, 4, 128, [5000, 900], 32, 256, 7, T=2, name="g8_w32_256_rows_per_head"),
+    small("bf16", 16, 1, 128, [1200], 24, 200, 5, T=2, name="g16_w24_two_256_row_blocks"),
+    small("fp32", 16, 2, 64, [700, 2300], 32, 100, 3, T=2, name="g8_fp32_256_rows"),
+    small("bf16", 8, 2, 128, [1500], 50, 300, 5, T=2, name="g4_w50_200_rows_odd_window"),
 ], ids=lambda w: w.name)
 def test_shapes_and_ragged_tails(wl):
     run_case(wl)
