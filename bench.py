@@ -160,6 +160,30 @@ def machine_probes(dev, stream):
     return res
 
 
+def pinned_read_probe(host_tensor, stream):
+    """GB/s of the streaming-read probe kernel over a page-locked host tensor (the ceiling for any
+    kernel that pulls its operands over the host link itself)."""
+    import ctypes
+    import torch
+    import paper_2507_19906_amd
+    path = os.path.join(os.path.dirname(os.path.abspath(paper_2507_19906_amd.__file__)), "libcalidrop_probes.so")
+    L = ctypes.CDLL(path)
+    L.calidrop_probe_stream_read_nt.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    blocks = 1024
+    nbytes = (host_tensor.numel() * host_tensor.element_size()) // (16 * blocks) * (16 * blocks)
+    out = torch.zeros(blocks, dtype=torch.int32, device="cuda")
+    st = stream.cuda_stream or None
+    best = 0.0
+    for it in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        assert L.calidrop_probe_stream_read_nt(host_tensor.data_ptr(), nbytes, blocks, out.data_ptr(), st) == 0
+        e1.record(stream)
+        torch.cuda.synchronize()
+        best = max(best, nbytes / (e0.elapsed_time(e1) * 1e3) / 1e3)
+    return best
+
+
 def timed(fn, stream, n, warm=2):
     """Mean microseconds per call of fn(i), HIP events on `stream` around n calls after `warm` calls."""
     import torch
@@ -501,8 +525,8 @@ def main():
         q3 = x["q_dec"][0][:L2].contiguous()
         b3.compress(x["q_win"][:L2].contiguous(), k3, v3, so3, stream=stream)
         packed = {}
-        for where in ("device", "host"):
-            store = cd.EvictedStore(b3, wl3.seq_lens, host=(where == "host"))
+        for where in ("device", "host", "host_staged"):
+            store = cd.EvictedStore(b3, wl3.seq_lens, host=(where != "device"), staged=(where == "host_staged"))
             store.pack(k3, v3, so3, stream=stream)
             b3.decode(q3, stream=stream)
             times = []
@@ -517,6 +541,20 @@ def main():
             us = sorted(times)[len(times) // 2]
             nbytes = 2 * store.k_e.numel() * store.k_e.element_size()
             packed[where] = {"us_per_layer": us / L2, "GBps": nbytes / us / 1e3, "bytes_per_layer": nbytes // L2}
+            if where == "host":
+                # the plain copy rate of the host link for the same bytes, and what a kernel that only
+                # reads the page-locked rows reaches (the probe's streaming read)
+                kd, vd = torch.empty_like(store.k_dev), torch.empty_like(store.v_dev)
+                for it in range(3):
+                    e0, e1 = ev(), ev()
+                    e0.record(stream)
+                    kd.copy_(store.k_e, non_blocking=True)
+                    vd.copy_(store.v_e, non_blocking=True)
+                    e1.record(stream)
+                    torch.cuda.synchronize()
+                packed["host_link_plain_copy_GBps"] = nbytes / (e0.elapsed_time(e1) * 1e3) / 1e3
+                packed["host_link_kernel_read_GBps"] = pinned_read_probe(store.k_e, stream)
+                del kd, vd
             del store
         del b3
 

@@ -327,7 +327,14 @@ class EvictedStore:
     `host=True` moves the packed rows to page-locked host memory after packing (the offloaded
     form); recalibrate() then reads them from there."""
 
-    def __init__(self, bufs: "CompressBuffers", seq_lens, host: bool = False, extra_rows=None):
+    def __init__(self, bufs: "CompressBuffers", seq_lens, host: bool = False, extra_rows=None,
+                 staged: bool = False):
+        """`staged=True` (with `host=True`): recalibrate() brings the rows back with plain copies into two
+        device staging buffers, one sequence ahead of the recomputation, instead of letting the kernel
+        read page-locked memory over the host link (Alg. 2 step 4's load overlapped with steps 5-8)."""
+        assert host or not staged
+        self.staged = staged
+        self._stage = None
         p = bufs.p
         dev = bufs.out.device
         dt = torch.bfloat16 if p.dtype == BF16 else torch.float32
@@ -366,7 +373,57 @@ class EvictedStore:
             self.k_dev, self.v_dev = self.k_e, self.v_e
             self.k_e, self.v_e = k_h, v_h
 
+    def _recalibrate_staged(self, q_t, stream=None):
+        """Per sequence: a copy stream fills one staging buffer with the sequence's packed rows while
+        the recomputation of the previous sequence reads the other one.  Copies, events and
+        per-sequence calls of calidrop_recalibrate_packed (batch 1); no arithmetic here."""
+        p, b = self.p, self.bufs
+        Hkv, D = p.n_kv_heads, p.head_dim
+        dev = b.out.device
+        if stream is None:
+            stream = torch.cuda.current_stream()
+        elif isinstance(stream, int):
+            stream = torch.cuda.ExternalStream(stream)
+        if self._stage is None:
+            cap = max(self.offs[i + 1] - self.offs[i] for i in range(p.batch))
+            p1 = Params.from_buffer_copy(p)
+            p1.batch = 1
+            self._stage = {
+                "p1": p1, "copy": torch.cuda.Stream(device=dev),
+                "k": [torch.empty(cap * Hkv * D, dtype=self.k_e.dtype, device=dev) for _ in range(2)],
+                "v": [torch.empty(cap * Hkv * D, dtype=self.k_e.dtype, device=dev) for _ in range(2)],
+                # per-sequence (offsets, length) arguments, each row 16-byte aligned as the library asks
+                "offs": torch.tensor([[0, self.offs[i + 1] - self.offs[i], 0, 0] for i in range(p.batch)],
+                                     dtype=torch.int32, device=dev),
+                "lens": torch.zeros((p.batch, 4), dtype=torch.int32, device=dev),
+                "ready": [torch.cuda.Event() for _ in range(2)],
+                "free": [torch.cuda.Event() for _ in range(2)],
+            }
+        st = self._stage
+        copy = st["copy"]
+        assert p.n_q_heads % 4 == 0                # per-sequence slices of the fp32 state stay 16-byte aligned
+        with torch.cuda.stream(stream):
+            st["lens"][:, 0].copy_(self.evict_lens)
+        for s in range(2):
+            st["free"][s].record(stream)          # what ran before on `stream` may still read the buffers
+        for i in range(p.batch):
+            s = i & 1
+            lo, hi = self.offs[i] * Hkv * D, self.offs[i + 1] * Hkv * D
+            copy.wait_event(st["free"][s])
+            with torch.cuda.stream(copy):
+                st["k"][s][:hi - lo].copy_(self.k_e[lo:hi], non_blocking=True)
+                st["v"][s][:hi - lo].copy_(self.v_e[lo:hi], non_blocking=True)
+                st["ready"][s].record(copy)
+            stream.wait_event(st["ready"][s])
+            calidrop_recalibrate_packed(st["p1"], q_t[i:i + 1], st["k"][s], st["v"][s], st["offs"][i],
+                                        st["lens"][i], max(self.rows[i], 1), b.flags[i:i + 1],
+                                        b.a_lse[i:i + 1], b.out[i:i + 1], b.c_q[i:i + 1], b.c_out[i:i + 1],
+                                        b.c_lse[i:i + 1], self.ws_recal, stream)
+            st["free"][s].record(stream)
+
     def recalibrate(self, q_t, stream=None):
+        if self.staged:
+            return self._recalibrate_staged(q_t, stream)
         b = self.bufs
         calidrop_recalibrate_packed(self.p, q_t, self.k_e, self.v_e, self.evict_offsets, self.evict_lens,
                                     self.max_evict_len, b.flags, b.a_lse, b.out, b.c_q, b.c_out, b.c_lse,

@@ -571,6 +571,15 @@ int pack_impl(const calidrop_params* p, const void* k, const void* v, const int3
 
 // Recomputation branch over the packed rows: the same streaming pass and tail as calidrop_recalibrate,
 // with the geometry of a packed buffer (offsets + live rows) instead of a prompt and its skip bitmap.
+bool is_host_memory(const void* ptr) {
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, ptr) != hipSuccess) {
+    (void)hipGetLastError();                     // a pointer the runtime does not know: treat as device memory
+    return false;
+  }
+  return attr.type == hipMemoryTypeHost;
+}
+
 template <typename T, int D>
 int recal_packed_impl(const calidrop_params* p, const void* q_t, const void* k_e, const void* v_e,
                       const int32_t* evict_offsets, const int32_t* evict_lens, int32_t max_evict_len, uint8_t* flags,
@@ -586,8 +595,11 @@ int recal_packed_impl(const calidrop_params* p, const void* q_t, const void* k_e
   aa.only_flagged = flags;
   aa.part_o = reinterpret_cast<float*>(ws + L.part_o);
   aa.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
-  hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false>), dim3(L.sp.NS, p->n_kv_heads, p->batch), dim3(256), 0,
-                     st, aa);
+  // rows in host memory (the offloaded form) are requested as whole rows: the host link moves the
+  // 64-byte pieces of the operand layout a quarter slower
+  const dim3 grid(L.sp.NS, p->n_kv_heads, p->batch);
+  if (is_host_memory(k_e)) hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false, true>), grid, dim3(256), 0, st, aa);
+  else hipLaunchKernelGGL((cd::attend_partial_kernel<T, D, false>), grid, dim3(256), 0, st, aa);
   if ((rc = launch_status("attend_partial(recalibrate, packed)"))) return rc;
   cd::FinalArgs fa{};
   fa.part_o = aa.part_o; fa.part_ml = aa.part_ml; fa.row_off = evict_offsets; fa.row_len = evict_lens;

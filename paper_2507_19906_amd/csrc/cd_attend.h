@@ -88,6 +88,41 @@ struct AttendWave {
     }
   }
 
+  // The same K rows requested as whole rows: instruction kk of a 16-row group reads the group's bytes
+  // 1024 kk .. 1024 kk + 1023 (16 bytes per lane in lane order) - what a link that moves small reads
+  // badly wants (rows in page-locked host memory: 55 GB/s against 41 GB/s for the 64-byte pieces of
+  // the operand layout).  regroup_k() turns the result into the operand layout.
+  __device__ __forceinline__ void load_k_rows(const T* kbase, int row0, int rows, int lane, u32x4 (&kf)[2][NK]) const {
+    constexpr int kRowBytes = D * static_cast<int>(sizeof(T));
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2)
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) {
+        const int o = kk * 1024 + lane * 16;
+        const int krow = min(row0 + 16 * g2 + o / kRowBytes, rows - 1);
+        kf[g2][kk] = ld16_stream(reinterpret_cast<const char*>(kbase + static_cast<int64_t>(krow) * D) + o % kRowBytes);
+      }
+  }
+  // Through a wave-private LDS area of 16 rows: written in the order loaded, read back as lane (i, c),
+  // step kk = bytes 64 kk + 16 c of row i.  One wave only, so the in-order LDS queue is all the
+  // synchronisation needed; the fences keep the compiler from moving the accesses across each other.
+  __device__ __forceinline__ void regroup_k(char* stage, u32x4 (&kf)[2][NK], int lane, int i, int c) const {
+    constexpr int kRowBytes = D * static_cast<int>(sizeof(T));
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2) {
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) *reinterpret_cast<u32x4*>(stage + kk * 1024 + lane * 16) = kf[g2][kk];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) kf[g2][kk] = *reinterpret_cast<const u32x4*>(stage + i * kRowBytes + kk * 64 + c * 16);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+  }
+
   // bf16 V rows of a tile: lane (i, c) loads, for e = 4 g2 + r, the 16-byte piece i of row
   // row0 + 16 g2 + 4 c + r (each instruction reads four whole rows, fully coalesced)
   __device__ __forceinline__ void load_v(const T* vbase, int row0, int rows, int i, int c, u32x4 (&vf)[8]) const {
@@ -168,13 +203,18 @@ struct AttendWave {
   // anything waits for them: arithmetic placed there is hidden behind the memory latency.
   // `k_requested`: the K rows of the wave's first tile are already on their way into kpre
   // (request_first_k).
-  template <bool kPrefetch = true, bool kLogits = false, typename F = NoWork>
+  // `kRowsK`: K is fetched as whole rows and regrouped through `k_stage` (16 rows of wave-private LDS).
+  template <bool kPrefetch = true, bool kLogits = false, typename F = NoWork, bool kRowsK = false>
   __device__ __forceinline__ void run(const T* kbase, const T* vbase, const uint32_t* bm, int rows, int row_first,
                                       int row_end, int row_step, float sl2, int i, int c,
                                       const float* zhead = nullptr, bool zvalid = false, bool k_requested = false,
-                                      F while_waiting = F()) {
+                                      F while_waiting = F(), char* k_stage = nullptr) {
     u32x4 kf[2][NK];
     f32x4 zf[2];
+    auto fetch_k = [&](int row0) {
+      if constexpr (kRowsK) load_k_rows(kbase, row0, rows, 16 * c + i, kf);
+      else load_k(kbase, row0, rows, i, c, kf);
+    };
     if (row_first >= row_end) { while_waiting(); return; }
     if constexpr (kLogits) {
       load_z(zhead, row_first, c, zvalid, zf);
@@ -185,7 +225,7 @@ struct AttendWave {
 #pragma unroll
           for (int kk = 0; kk < NK; ++kk) kf[g2][kk] = kpre[g2][kk];
       } else {
-        load_k(kbase, row_first, rows, i, c, kf);
+        fetch_k(row_first);
       }
     }
     for (int row0 = row_first; row0 < row_end; row0 += row_step) {
@@ -200,6 +240,7 @@ struct AttendWave {
         acc_s[1] = zf[1];
         if (next0 < row_end) load_z(zhead, next0, c, zvalid, zf);
       } else {
+        if constexpr (kRowsK) regroup_k(k_stage, kf, 16 * c + i, i, c);
 #pragma unroll
         for (int g2 = 0; g2 < 2; ++g2) {
           acc_s[g2] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -207,7 +248,7 @@ struct AttendWave {
           for (int kk = 0; kk < NK; ++kk) mma_step<T>(acc_s[g2], kf[g2][kk], qf[kk]);
         }
         if constexpr (kPrefetch) {
-          if (next0 < row_end) load_k(kbase, next0, rows, i, c, kf);
+          if (next0 < row_end) fetch_k(next0);
         }
       }
       const uint32_t skip = bm ? bm[row0 >> 5] : 0u;
@@ -232,7 +273,7 @@ struct AttendWave {
         }
       }
       if constexpr (!kPrefetch && !kLogits) {
-        if (next0 < row_end) load_k(kbase, next0, rows, i, c, kf);
+        if (next0 < row_end) fetch_k(next0);
       }
     }
   }
@@ -267,7 +308,8 @@ struct AttendWave {
 };
 
 // kLogits: calibration mode with the logits precomputed by the scoring pass (K is not read).
-template <typename T, int D, bool kLogits>
+// kRowsK: K rows are requested whole and regrouped in LDS (rows that live in host memory).
+template <typename T, int D, bool kLogits, bool kRowsK = false>
 __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
   // grid: x = split of the rows (rotated per head so that the splits every sequence has do not
   // all land on the same XCDs of the round-robin deal), y = KV head, z = sequence
@@ -290,6 +332,8 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
   const T* vbase = static_cast<const T*>(a.v) + head_tok * D;
   const uint32_t* bm = a.bitmap ? a.bitmap + static_cast<int64_t>(b * a.Hkv + g) * a.W32 : nullptr;
 
+  __shared__ __attribute__((aligned(16))) float s_o[kAttWaves][16 * D];
+  __shared__ float2 s_ml[kAttWaves][16];
   AttendWave<T, D> w;
   {
     const int h = g * a.G + i;
@@ -303,13 +347,17 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a) {
     const float* zhead = a.cal_logit + static_cast<int64_t>(b * a.Hq + g * a.G + i) * a.zstride;
     w.template run<true, true>(kbase, vbase, bm, rows, row_begin + wv * kTileRows, row_end, kAttWaves * kTileRows,
                                a.sl2, i, c, zhead, i < a.G);
+  } else if constexpr (kRowsK) {
+    // 16 rows of K fit the area the wave publishes its outputs to afterwards
+    static_assert(16 * D * sizeof(T) <= sizeof(s_o[0]), "K staging area");
+    w.template run<true, false, typename AttendWave<T, D>::NoWork, true>(
+        kbase, vbase, bm, rows, row_begin + wv * kTileRows, row_end, kAttWaves * kTileRows, a.sl2, i, c, nullptr, false,
+        false, typename AttendWave<T, D>::NoWork(), reinterpret_cast<char*>(s_o[wv]));
   } else {
     w.run(kbase, vbase, bm, rows, row_begin + wv * kTileRows, row_end, kAttWaves * kTileRows, a.sl2, i, c);
   }
 
   // ---- merge the 4 waves through LDS and write this split's partial ------------------------
-  __shared__ __attribute__((aligned(16))) float s_o[kAttWaves][16 * D];
-  __shared__ float2 s_ml[kAttWaves][16];
   w.publish(s_o[wv], s_ml[wv], a.G, i, c);
   __syncthreads();
   for (int t = threadIdx.x; t < a.G * D; t += 256) {

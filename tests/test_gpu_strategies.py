@@ -184,6 +184,11 @@ def check_packed(wl, x, bufs, store, orc_evicted):
     (small("fp32", 8, 2, 64, [1031, 97], 16, 96, 3, T=4, name="pack_fp32_calib"), 50, False),
     (small("fp32", 8, 2, 64, [1031, 97], 16, 96, 3, T=4, name="pack_fp32_calib_host"), 50, True),
     (small("bf16", 32, 8, 128, [4099], 32, 512, 7, T=3, name="pack_llama_shape"), 0, True),
+    (small("fp32", 8, 2, 128, [777, 1290], 16, 96, 3, T=4, name="pack_fp32_d128_host"), 0, True),
+    (small("bf16", 8, 4, 64, [1100, 333], 8, 64, 5, T=4, name="pack_bf16_d64_host"), 0, True),
+    # brought back by plain copies through two staging buffers, one sequence ahead of the recomputation
+    (small("bf16", 8, 2, 128, [900, 40, 2100, 700, 1300], 16, 128, 5, T=6, name="pack_varlen_bf16_staged"), 0, "staged"),
+    (small("fp32", 8, 2, 64, [1031, 97, 400], 16, 96, 3, T=4, name="pack_fp32_calib_staged"), 50, "staged"),
 ], ids=lambda v: v.name if hasattr(v, "name") else str(v))
 def test_packed_evicted_rows_and_recomputation_from_them(wl, m, host):
     x = to_dev(synth.make_inputs(wl, 21))
@@ -194,7 +199,7 @@ def test_packed_evicted_rows_and_recomputation_from_them(wl, m, host):
         orc, _ = H.check_compress(wl, x, bufs, b, report=rep)
         orc_evicted.append(orc["evicted"])
     assert rep.get("tie_band_heads", 0) == 0 and rep.get("tie_band_cal_heads", 0) == 0
-    store = cd.EvictedStore(bufs, wl.seq_lens, host=host)
+    store = cd.EvictedStore(bufs, wl.seq_lens, host=bool(host), staged=(host == "staged"))
     store.pack(x["k"], x["v"], x["seq_offsets"])
     torch.cuda.synchronize()
     check_packed(wl, x, bufs, store, orc_evicted)
