@@ -129,7 +129,9 @@ def machine_probes(dev, stream):
     out = torch.zeros(1 << 21, dtype=torch.float32, device=dev)
     ev = lambda: torch.cuda.Event(enable_timing=True)
     res = {}
-    for label, nbytes, blocks, reps in (("64MiB", 64 << 20, 2048, 32), ("256MiB", 256 << 20, 8192, 16), ("2GiB", 2 << 30, 32768, 6)):
+    # "64MiB_256wg": the launch shape of the headline decode call (one workgroup of 256 threads per compute unit)
+    for label, nbytes, blocks, reps in (("64MiB", 64 << 20, 2048, 32), ("64MiB_256wg", 64 << 20, 256, 32),
+                                        ("256MiB", 256 << 20, 8192, 16), ("2GiB", 2 << 30, 32768, 6)):
         nrot = (2 << 30) // nbytes                 # rotate through the buffer: never re-read cached data
         for kind, fn in (("", L.calidrop_probe_stream_read), ("_nontemporal", L.calidrop_probe_stream_read_nt)):
             def launch(r):
@@ -525,9 +527,13 @@ def main():
         q3 = x["q_dec"][0][:L2].contiguous()
         b3.compress(x["q_win"][:L2].contiguous(), k3, v3, so3, stream=stream)
         packed = {}
+        store = None
         for where in ("device", "host", "host_staged"):
-            store = cd.EvictedStore(b3, wl3.seq_lens, host=(where != "device"), staged=(where == "host_staged"))
-            store.pack(k3, v3, so3, stream=stream)
+            if where == "host_staged":        # the same page-locked buffers as "host" (their placement decides the link rate)
+                store.staged = True
+            else:
+                store = cd.EvictedStore(b3, wl3.seq_lens, host=(where == "host"))
+                store.pack(k3, v3, so3, stream=stream)
             b3.decode(q3, stream=stream)
             times = []
             for _ in range(4):
@@ -555,8 +561,7 @@ def main():
                 packed["host_link_plain_copy_GBps"] = nbytes / (e0.elapsed_time(e1) * 1e3) / 1e3
                 packed["host_link_kernel_read_GBps"] = pinned_read_probe(store.k_e, stream)
                 del kd, vd
-            del store
-        del b3
+        del store, b3
 
     # H2O as the eviction strategy (accumulated attention of every prompt query: two dense causal
     # passes on the matrix cores) for one layer of the same shape
