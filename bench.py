@@ -158,6 +158,22 @@ def machine_probes(dev, stream):
     flop = blocks * 4 * iters * 8 * 16384.0
     ms = e0.elapsed_time(e1)
     res["mfma_bf16_loop"] = {"ms": ms, "TFLOPps": flop / ms / 1e9, "pct_published_peak": 100.0 * flop / ms / 1e9 / 2500.0}
+    # matrix and vector instructions on the same SIMDs: alone and together (4 waves per SIMD)
+    L.calidrop_probe_mfma_valu.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p]
+    def coissue(matrix, nv, use_exp, iters=4000):
+        for n in (200, iters):
+            e0, e1 = ev(), ev()
+            e0.record(stream)
+            assert L.calidrop_probe_mfma_valu(out.data_ptr(), 1024, n, matrix, nv, use_exp, st) == 0
+            e1.record(stream)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e6 / (iters * 8 * 4)      # ns per pair of matrix instructions and SIMD
+    t_m = coissue(1, 0, 0)
+    co = {"ns_per_pair_of_matrix_instructions": t_m}
+    for kind, use_exp in (("fma", 0), ("exp2", 1)):
+        t_v, t_b = coissue(0, 8, use_exp), coissue(1, 8, use_exp)
+        co["8_" + kind] = {"vector_only_ns": t_v, "both_ns": t_b, "hidden_share_of_vector_time": (t_m + t_v - t_b) / t_v}
+    res["matrix_and_vector_together_4_waves_per_simd"] = co
     del buf, out
     return res
 

@@ -400,7 +400,10 @@ int calidrop_compress_h2o(const calidrop_params* p, int32_t n_local, const void*
  * same results, same in/out arguments (q_t, flags, a_lse, out, c_q, c_out, c_lse).  k_e and v_e may
  * be device memory or page-locked host memory that the device can address (hipHostMalloc): in the
  * second case the kernel pulls the rows of the flagged KV groups over the host link while it
- * computes, and nothing is staged in device memory.  evict_offsets / evict_lens are device memory.
+ * computes, and nothing is staged in device memory (the library asks the runtime what kind of
+ * memory k_e is - hipPointerGetAttributes, a host-side query - and requests host-resident rows as
+ * whole rows, which the host link moves a third faster than the pieces of the matrix-operand
+ * layout).  evict_offsets / evict_lens are device memory.
  * max_evict_len >= every evict_lens[b] (host copy; sizes the grid).  workspace >=
  * calidrop_recalibrate_packed_workspace_bytes(p, max_evict_len) bytes, 256-byte aligned.
  */

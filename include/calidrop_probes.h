@@ -1,8 +1,8 @@
 /*
  * calidrop_probes.h - machine probes used by the benchmark (libcalidrop_probes.so).
  *
- * Not part of the CaliDrop path: two plain kernels that show what the GPU at hand reaches on a
- * streaming read and on a dense bf16 matrix-core loop, so that roofline fractions can be quoted
+ * Not part of the CaliDrop path: plain kernels that show what the GPU at hand reaches on a
+ * streaming read, on a dense bf16 matrix-core loop and on matrix and vector instructions issued together, so that roofline fractions can be quoted
  * against measured ceilings next to the published peaks.  Device pointers, caller-owned; the
  * calls enqueue one kernel on `stream` (a hipStream_t, NULL = default) and return 0, or -1 on
  * bad arguments or a failed launch.  The caller times them (events on the same stream).
@@ -27,6 +27,15 @@ int calidrop_probe_stream_read_nt(const void* buf, uint64_t bytes, int32_t block
  * v_mfma_f32_16x16x32_bf16 instructions (16384 flop each) and nothing else.  `out`: blocks * 256
  * floats.  Total flop = blocks * 4 * iters * 8 * 16384. */
 int calidrop_probe_mfma_loop(void* out, int32_t blocks, int32_t iters, void* stream);
+
+/* Matrix and ordinary vector instructions side by side: `blocks` workgroups of 4 waves (1024 puts 4
+ * waves on every SIMD), every wave runs iters rounds of 16 v_mfma_f32_16x16x32_bf16 (`matrix` != 0)
+ * with valu_per_pair / 2 independent vector instructions behind each (valu_per_pair: 0 or 8; fused
+ * multiply-adds, or exp2 when `use_exp` != 0).  Timing the three launches (matrix only, vector
+ * only, both) shows how much of the vector work issues in the shadow of the matrix pipe.  `out`:
+ * blocks * 256 floats. */
+int calidrop_probe_mfma_valu(void* out, int32_t blocks, int32_t iters, int32_t matrix, int32_t valu_per_pair,
+                             int32_t use_exp, void* stream);
 
 #ifdef __cplusplus
 }

@@ -48,6 +48,42 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(float* out, int iters) {
   out[static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x] = s[0] + s[1] + s[2] + s[3];
 }
 
+// Matrix instructions and ordinary vector instructions side by side.  A round is 8 x (two bf16
+// 16x16x32 matrix instructions, each followed by NV / 2 independent vector instructions): fused
+// multiply-adds, or exp2 when kExp.  kMatrix = false leaves the matrix instructions out, NV = 0 the
+// vector ones: three launches (matrix only, vector only, both) show how much of the vector work
+// issues in the shadow of the matrix pipe.  The register budget is held to 128 so that 4 waves fit
+// a SIMD (launch 4 workgroups per compute unit).
+template <bool kMatrix, int NV, bool kExp>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void mfma_valu_kernel(float* out, int iters) {
+  const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});   // 1.0
+  const bf16x8 b = __builtin_bit_cast(bf16x8, u32x4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u});   // 2^-7
+  f32x4 acc[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float v[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) v[j] = 0.001f * static_cast<float>(threadIdx.x + j);
+  const float c1 = 0.999f, c2 = 1e-6f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      if constexpr (kMatrix) acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[u], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < NV / 2; ++q) {
+        const int x = (u * (NV / 2) + q) % 16;
+        v[x] = kExp ? __builtin_amdgcn_exp2f(v[x]) : fmaf(v[x], c1, c2);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) s += acc[j][0] + acc[j][1] + acc[j][2] + acc[j][3] + v[j];
+  out[static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x] = s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -75,6 +111,24 @@ int calidrop_probe_mfma_loop(void* out, int32_t blocks, int32_t iters, void* str
   if (!out || blocks < 1 || iters < 1) return -1;
   hipLaunchKernelGGL(mfma_loop_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<float*>(out), iters);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// `blocks` workgroups of 4 waves (1024 = 4 waves on every SIMD of the chip); every wave runs iters
+// rounds of 16 matrix instructions (`matrix` != 0) with `valu_per_pair` / 2 vector instructions
+// behind each: fused multiply-adds, or exp2 when `use_exp` != 0.  valu_per_pair: 0 or 8.  `out`:
+// blocks * 256 floats.
+int calidrop_probe_mfma_valu(void* out, int32_t blocks, int32_t iters, int32_t matrix, int32_t valu_per_pair,
+                             int32_t use_exp, void* stream) {
+  if (!out || blocks < 1 || iters < 1 || (valu_per_pair != 0 && valu_per_pair != 8) || (!matrix && !valu_per_pair)) return -1;
+  const dim3 g(blocks), t(256);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* o = static_cast<float*>(out);
+  if (matrix && !valu_per_pair) hipLaunchKernelGGL((mfma_valu_kernel<true, 0, false>), g, t, 0, st, o, iters);
+  else if (matrix && !use_exp) hipLaunchKernelGGL((mfma_valu_kernel<true, 8, false>), g, t, 0, st, o, iters);
+  else if (matrix) hipLaunchKernelGGL((mfma_valu_kernel<true, 8, true>), g, t, 0, st, o, iters);
+  else if (!use_exp) hipLaunchKernelGGL((mfma_valu_kernel<false, 8, false>), g, t, 0, st, o, iters);
+  else hipLaunchKernelGGL((mfma_valu_kernel<false, 8, true>), g, t, 0, st, o, iters);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
