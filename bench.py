@@ -158,6 +158,21 @@ def machine_probes(dev, stream):
     flop = blocks * 4 * iters * 8 * 16384.0
     ms = e0.elapsed_time(e1)
     res["mfma_bf16_loop"] = {"ms": ms, "TFLOPps": flop / ms / 1e9, "pct_published_peak": 100.0 * flop / ms / 1e9 / 2500.0}
+    # a 2 GiB streaming read alone and with 32 / 160 MiB of full-line stores mixed in (what the votes and the
+    # exported logits of scoring pass 2 are to its K stream)
+    L.calidrop_probe_stream_read_store.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2
+    dst = torch.empty(5 * 4096 * 32 * 64, dtype=torch.float32, device=dev)
+    mix = {}
+    for rows in (0, 1, 5, 0):
+        for it in range(3):
+            e0, e1 = ev(), ev()
+            e0.record(stream)
+            assert L.calidrop_probe_stream_read_store(buf.data_ptr(), dst.data_ptr(), 4096, 32, rows, out.data_ptr(), st) == 0
+            e1.record(stream)
+            torch.cuda.synchronize()
+        mix[f"{rows * 32}MiB_of_stores"] = e0.elapsed_time(e1) * 1e3
+    res["stream_read_2GiB_with_stores_us"] = mix
+    del dst
     # matrix and vector instructions on the same SIMDs: alone and together (4 waves per SIMD)
     L.calidrop_probe_mfma_valu.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p]
     def coissue(matrix, nv, use_exp, iters=4000):
@@ -179,26 +194,30 @@ def machine_probes(dev, stream):
 
 
 def pinned_read_probe(host_tensor, stream):
-    """GB/s of the streaming-read probe kernel over a page-locked host tensor (the ceiling for any
-    kernel that pulls its operands over the host link itself)."""
+    """GB/s of the streaming-read probe kernels over a page-locked host tensor (the ceiling for any kernel
+    that pulls its operands over the host link itself): requested as whole rows, and as the 64-byte
+    pieces of a matrix-operand fragment load."""
     import ctypes
     import torch
     import paper_2507_19906_amd
     path = os.path.join(os.path.dirname(os.path.abspath(paper_2507_19906_amd.__file__)), "libcalidrop_probes.so")
     L = ctypes.CDLL(path)
     L.calidrop_probe_stream_read_nt.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    L.calidrop_probe_stream_read_pieces.argtypes = L.calidrop_probe_stream_read_nt.argtypes
     blocks = 1024
-    nbytes = (host_tensor.numel() * host_tensor.element_size()) // (16 * blocks) * (16 * blocks)
+    nbytes = (host_tensor.numel() * host_tensor.element_size()) // (32768 * blocks) * (32768 * blocks)
     out = torch.zeros(blocks, dtype=torch.int32, device="cuda")
     st = stream.cuda_stream or None
-    best = 0.0
-    for it in range(3):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        assert L.calidrop_probe_stream_read_nt(host_tensor.data_ptr(), nbytes, blocks, out.data_ptr(), st) == 0
-        e1.record(stream)
-        torch.cuda.synchronize()
-        best = max(best, nbytes / (e0.elapsed_time(e1) * 1e3) / 1e3)
+    best = {}
+    for name, fn in (("whole_rows", L.calidrop_probe_stream_read_nt), ("64_byte_pieces", L.calidrop_probe_stream_read_pieces)):
+        best[name] = 0.0
+        for it in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            assert fn(host_tensor.data_ptr(), nbytes, blocks, out.data_ptr(), st) == 0
+            e1.record(stream)
+            torch.cuda.synchronize()
+            best[name] = max(best[name], nbytes / (e0.elapsed_time(e1) * 1e3) / 1e3)
     return best
 
 

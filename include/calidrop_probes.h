@@ -23,6 +23,17 @@ int calidrop_probe_stream_read(const void* buf, uint64_t bytes, int32_t blocks, 
 /* The same read issued as non-temporal loads (the hint for data that is not read again soon). */
 int calidrop_probe_stream_read_nt(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream);
 
+/* The same read requested the way a matrix-operand fragment load requests 256-byte rows: 16 rows x
+ * 64 bytes per wave instruction (what a link that moves small requests badly shows).  bytes must be
+ * a multiple of 32768 * blocks. */
+int calidrop_probe_stream_read_pieces(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream);
+
+/* A non-temporal streaming read of blocks * stages * 16 KiB from `src` with full-line stores mixed
+ * in: `rows` x 256 bytes per workgroup and stage into `dst` (rows * blocks * stages * 256 bytes;
+ * rows = 0: the read alone, dst unused).  `out`: blocks uint32. */
+int calidrop_probe_stream_read_store(const void* src, void* dst, int32_t blocks, int32_t stages, int32_t rows, void* out,
+                                     void* stream);
+
 /* `blocks` workgroups of 4 waves; every wave executes iters * 8 independent-chain
  * v_mfma_f32_16x16x32_bf16 instructions (16384 flop each) and nothing else.  `out`: blocks * 256
  * floats.  Total flop = blocks * 4 * iters * 8 * 16384. */

@@ -30,6 +30,48 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) out[blockIdx.x] = 1u;   // keeps the loads alive
 }
 
+// The same bytes requested the way a matrix-operand fragment load requests rows of 256 bytes: per
+// wave instruction 16 rows x 64 bytes (lane (i, c) = 16 bytes at row i, piece c), four instructions
+// per 16 rows.  Every wave owns a contiguous slice (a multiple of 8 KiB).
+__global__ __launch_bounds__(256) void stream_read_pieces_kernel(const char* __restrict__ p, uint64_t bytes_per_wave, uint32_t* out) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int i = lane & 15, c = lane >> 4;
+  const char* q = p + (static_cast<uint64_t>(blockIdx.x) * 4 + wv) * bytes_per_wave;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (uint64_t off = 0; off < bytes_per_wave; off += 8192) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + off + (u >> 2) * 4096 + i * 256 + (u & 3) * 64 + c * 16));
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) out[blockIdx.x] = 1u;
+}
+
+// A streaming read (non-temporal, 16 KiB per workgroup and stage) with full-line stores mixed in: after
+// every stage 64 threads store one float each to each of `rows` output streams (256 bytes per stream
+// and stage).  rows = 0: the read alone.
+__global__ __launch_bounds__(256) void stream_read_store_kernel(const u32x4* __restrict__ src, float* __restrict__ dst, int stages, int rows,
+                                                                int64_t row_stride, uint32_t* out) {
+  const int64_t wg = blockIdx.x;
+  const u32x4* q = src + wg * stages * 1024;
+  float* w = dst + wg * stages * 64;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (int s = 0; s < stages; ++s) {
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(q + s * 1024 + u * 256 + threadIdx.x);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc ^= v[u];
+    if (threadIdx.x < 64) {
+      const float val = __uint_as_float(acc[0] & 0x3fffffffu);
+      for (int r = 0; r < rows; ++r) w[r * row_stride + s * 64 + threadIdx.x] = val;
+    }
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) out[blockIdx.x] = 1u;
+}
+
 // Each wave runs `iters` rounds of 8 independent accumulate chains of the bf16 16x16x32 matrix
 // instruction: 8 * 16384 flop per round and wave, nothing else in the loop.
 __global__ __launch_bounds__(256) void mfma_loop_kernel(float* out, int iters) {
@@ -102,6 +144,25 @@ int calidrop_probe_stream_read_nt(const void* buf, uint64_t bytes, int32_t block
   if (!buf || !out || blocks < 1 || bytes == 0 || bytes % (16ull * blocks) != 0) return -1;
   hipLaunchKernelGGL(stream_read_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(buf), bytes / 16 / blocks, static_cast<uint32_t*>(out));
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Reads `bytes` (a multiple of 32768 * blocks) in 64-byte pieces, 16 rows of 256 bytes per wave instruction.
+int calidrop_probe_stream_read_pieces(const void* buf, uint64_t bytes, int32_t blocks, void* out, void* stream) {
+  if (!buf || !out || blocks < 1 || bytes == 0 || bytes % (32768ull * blocks) != 0) return -1;
+  hipLaunchKernelGGL(stream_read_pieces_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(buf), bytes / blocks / 4, static_cast<uint32_t*>(out));
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// `blocks` workgroups read `stages` x 16 KiB each from `src` (blocks * stages * 16 KiB bytes) and store
+// `rows` x 256 bytes per stage into `dst` (rows * blocks * stages * 256 bytes).  `out`: blocks uint32.
+int calidrop_probe_stream_read_store(const void* src, void* dst, int32_t blocks, int32_t stages, int32_t rows, void* out,
+                                     void* stream) {
+  if (!src || !out || blocks < 1 || stages < 1 || rows < 0 || (rows > 0 && !dst)) return -1;
+  hipLaunchKernelGGL(stream_read_store_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4*>(src), static_cast<float*>(dst), stages, rows,
+                     static_cast<int64_t>(blocks) * stages * 64, static_cast<uint32_t*>(out));
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -261,7 +261,7 @@ def test_probe_library_exports_its_header():
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(calidrop_probe_[a-z_]+)\s*\(", hdr))
     assert names == {"calidrop_probe_stream_read", "calidrop_probe_stream_read_nt", "calidrop_probe_mfma_loop",
-                     "calidrop_probe_mfma_valu"}
+                     "calidrop_probe_mfma_valu", "calidrop_probe_stream_read_pieces", "calidrop_probe_stream_read_store"}
     L = ctypes.CDLL(os.path.join(ROOT, "paper_2507_19906_amd", "libcalidrop_probes.so"))
     for n in names:
         assert hasattr(L, n), n
@@ -270,6 +270,10 @@ def test_probe_library_exports_its_header():
     assert L.calidrop_probe_stream_read(4096, (1 << 20) + 16, 64, 4096, None) == -1
     L.calidrop_probe_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
     assert L.calidrop_probe_mfma_loop(None, 8, 8, None) == -1
+    L.calidrop_probe_stream_read_pieces.argtypes = L.calidrop_probe_stream_read.argtypes
+    assert L.calidrop_probe_stream_read_pieces(4096, (1 << 20) + 16, 8, 4096, None) == -1
+    L.calidrop_probe_stream_read_store.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 2
+    assert L.calidrop_probe_stream_read_store(4096, None, 8, 8, 5, 4096, None) == -1      # stores asked for, nowhere to put them
     L.calidrop_probe_mfma_valu.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p]
     assert L.calidrop_probe_mfma_valu(4096, 8, 8, 1, 4, 0, None) == -1             # 0 or 8 vector instructions per pair
     assert L.calidrop_probe_mfma_valu(4096, 8, 8, 0, 0, 0, None) == -1             # nothing to run
