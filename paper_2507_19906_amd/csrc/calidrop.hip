@@ -190,6 +190,13 @@ int launch_status(const char* what) {
   return CALIDROP_OK;
 }
 
+// The skip bitmap of a sequence fits LDS up to 48 KiB (393216 positions): built there, stored once.
+void launch_bitmap(const cd::BitmapArgs& ba, int pairs, hipStream_t st) {
+  const size_t lds = static_cast<size_t>(ba.W32) * sizeof(uint32_t);
+  if (lds <= 48 * 1024) hipLaunchKernelGGL(cd::bitmap_from_indices_lds_kernel, dim3(pairs), dim3(256), lds, st, ba);
+  else hipLaunchKernelGGL(cd::bitmap_from_indices_kernel, dim3(pairs), dim3(256), 0, st, ba);
+}
+
 // The single-workgroup selection kernels stage up to kSelMaxLdsKeys votes (padded) in dynamic LDS, more
 // than the 48 KiB a kernel may use without asking.  The limit is raised to the largest size any call
 // can need, once per (kernel variant, device) at that variant's first use on the device - a host-side
@@ -450,7 +457,8 @@ int recal_impl(const calidrop_params* p, const void* q_t, const void* k, const v
   ba.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap); ba.calib = p->calib_size;
   ba.total_tokens = total_tokens; ba.batch = p->batch; ba.Hkv = p->n_kv_heads; ba.B = p->budget;
   ba.max_seq_len = max_seq_len; ba.W32 = L.W32;
-  hipLaunchKernelGGL(cd::bitmap_from_indices_kernel, dim3(p->batch * p->n_kv_heads), dim3(256), 0, st, ba);
+  ba.only_flagged = flags; ba.Hq = p->n_q_heads; ba.G = G;
+  launch_bitmap(ba, p->batch * p->n_kv_heads, st);
   if ((rc = launch_status("bitmap_from_indices"))) return rc;
 
   cd::AttendArgs aa{};
@@ -550,7 +558,8 @@ int pack_impl(const calidrop_params* p, const void* k, const void* v, const int3
   ba.bitmap = reinterpret_cast<uint32_t*>(ws + L.bitmap); ba.calib = p->calib_size;
   ba.total_tokens = total_tokens; ba.batch = p->batch; ba.Hkv = p->n_kv_heads; ba.B = p->budget;
   ba.max_seq_len = max_seq_len; ba.W32 = L.W32;
-  hipLaunchKernelGGL(cd::bitmap_from_indices_kernel, dim3(bg), dim3(256), 0, st, ba);
+  ba.only_flagged = nullptr; ba.Hq = p->n_q_heads; ba.G = p->n_q_heads / p->n_kv_heads;
+  launch_bitmap(ba, bg, st);
   if ((rc = launch_status("bitmap_from_indices"))) return rc;
   cd::PackArgs pa{};
   pa.seq_off = seq_offsets; pa.evict_off = evict_offsets; pa.total_tokens = total_tokens; pa.batch = p->batch;

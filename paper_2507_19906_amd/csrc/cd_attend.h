@@ -490,6 +490,8 @@ struct BitmapArgs {
   const int32_t* seq_off; const int32_t* indices; const int32_t* cal_indices; uint32_t* bitmap;
   int64_t total_tokens;
   int batch, Hkv, B, calib, max_seq_len, W32;
+  const uint8_t* only_flagged;   // [batch][Hq] or NULL: KV groups without a head flagged 2 are left alone
+  int Hq, G;
 };
 
 // Rebuild the skip bitmap of the calibration pass for every (sequence, KV head): either "not
@@ -518,6 +520,42 @@ __global__ __launch_bounds__(256) void bitmap_from_indices_kernel(BitmapArgs a) 
       if (pos >= 0 && pos < n) atomicOr(&bm[pos >> 5], 1u << (pos & 31));
     }
   }
+}
+
+// The same bitmap built in LDS (W32 words of dynamic shared memory) and written out once, whole words,
+// coalesced: the bits are set with LDS atomics instead of one trip to L2 per retained position.
+__global__ __launch_bounds__(256) void bitmap_from_indices_lds_kernel(BitmapArgs a) {
+  extern __shared__ uint32_t s_bits[];
+  const int bg = blockIdx.x;
+  const int b = bg / a.Hkv;
+  if (a.only_flagged) {
+    const int g = bg - b * a.Hkv;
+    bool any = false;
+    for (int hh = 0; hh < a.G; ++hh) any |= a.only_flagged[b * a.Hq + g * a.G + hh] == 2;
+    if (!any) return;                              // the recomputation skips this KV group as well
+  }
+  int off0;
+  const int n = seq_len_checked(a.seq_off, b, a.max_seq_len, a.total_tokens, off0);
+  uint32_t* bm = a.bitmap + static_cast<int64_t>(bg) * a.W32;
+  const int words = min((n + 31) / 32, a.W32);
+  const bool from_cal = a.cal_indices != nullptr && a.calib > 0;
+  for (int wd = threadIdx.x; wd < words; wd += 256) s_bits[wd] = from_cal ? 0xFFFFFFFFu : 0u;
+  __syncthreads();
+  if (from_cal) {
+    const int32_t* cal = a.cal_indices + static_cast<int64_t>(bg) * a.calib;
+    for (int r = threadIdx.x; r < a.calib; r += 256) {
+      const int pos = cal[r];
+      if (pos >= 0 && pos < n) atomicAnd(&s_bits[pos >> 5], ~(1u << (pos & 31)));
+    }
+  } else {
+    const int32_t* idx = a.indices + static_cast<int64_t>(bg) * a.B;
+    for (int r = threadIdx.x; r < a.B; r += 256) {
+      const int pos = idx[r];
+      if (pos >= 0 && pos < n) atomicOr(&s_bits[pos >> 5], 1u << (pos & 31));
+    }
+  }
+  __syncthreads();
+  for (int wd = threadIdx.x; wd < words; wd += 256) bm[wd] = s_bits[wd];
 }
 
 struct DecodeFusedArgs {
