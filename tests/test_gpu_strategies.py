@@ -68,6 +68,9 @@ def decode_and_recalibrate(wl, x, bufs, rep, steps):
     (small("bf16", 32, 8, 128, [4096, 513], 32, 512, 7, T=3, name="slm_llama_shape"), 32),
     (small("fp32", 4, 2, 64, [300], 8, 64, 1, T=3, name="slm_window_only"), 0),
     (small("fp32", 4, 2, 64, [300], 8, 64, 1, T=3, name="slm_sinks_only"), 64),
+    # a prompt whose skip bitmap (one bit per position) no longer fits the 48 KiB of LDS the recomputation
+    # builds it in: the bitmap is then built in global memory
+    (small("bf16", 2, 1, 64, [400000, 3000], 16, 256, 1, T=3, name="slm_400k_bitmap_in_global_memory"), 32),
 ], ids=lambda v: v.name if hasattr(v, "name") else str(v))
 def test_streaming_llm_strategy(wl, n_sink):
     x = to_dev(synth.make_inputs(wl, 77))
