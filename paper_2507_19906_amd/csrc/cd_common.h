@@ -163,13 +163,6 @@ __device__ __forceinline__ float row16_sum(float x) {
   x += dpp_f32<0x140>(x);   // row_mirror
   return x;
 }
-__device__ __forceinline__ float row16_max(float x) {
-  x = fmaxf(x, dpp_f32<0xB1>(x));
-  x = fmaxf(x, dpp_f32<0x4E>(x));
-  x = fmaxf(x, dpp_f32<0x141>(x));
-  x = fmaxf(x, dpp_f32<0x140>(x));
-  return x;
-}
 // Lane l's value together with that of lane l ^ 16 (pair16) or l ^ 32 (pair32), the lower lane's
 // first, through the gfx950 lane-swap instructions: two registers that start as copies of x trade
 // rows (odd rows of one with even rows of the other) or halves (upper half of one with the lower
@@ -223,13 +216,6 @@ __device__ __forceinline__ void xcd_head_major(int& vx, int& vh) {
     vx = slot % gx;
     vh = (L % 8) * (H / 8) + slot / gx;
   }
-}
-
-// Three-input maximum in one instruction (operands are never NaN here, so no canonicalisation).
-__device__ __forceinline__ float max3(float a, float b, float c) {
-  float d;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-  return d;
 }
 
 // Merge two (max, sum-of-exp2) pairs in the log2 domain; (-inf, 0) is the identity.

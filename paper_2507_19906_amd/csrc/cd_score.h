@@ -53,12 +53,11 @@ __device__ __forceinline__ int seq_len_checked(const int32_t* seq_off, int b, in
   return n;
 }
 
-// Streams the keys of one workgroup's chunk through LDS: global -> registers (two stages in
-// flight) -> LDS (two buffers), so that the four waves, which own 32 query rows each, all read
-// every key tile from LDS instead of each loading it from memory.  LDS rows are 16-byte chunks
-// stored at chunk' = chunk ^ swz(key), chosen so that 16 consecutive lanes always touch 16
-// different 16-byte bank groups of a 256-byte window, both for the row-wise writes (lanes =
-// consecutive chunks) and for the column-wise fragment reads (lanes = consecutive keys).
+// Layout of a stage of keys in LDS, shared by the waves of a workgroup (which own different query
+// rows and all read every key tile from LDS instead of each loading it from memory).  LDS rows
+// are 16-byte chunks stored at chunk' = chunk ^ swz(key), chosen so that 16 consecutive lanes
+// always touch 16 different 16-byte bank groups of a 256-byte window, both for row-wise writes
+// (lanes = consecutive chunks) and for the column-wise fragment reads (lanes = consecutive keys).
 template <typename T, int D, int NT = 256>
 struct KeyStream {
   static constexpr int EPL = Elem<T>::kPer16B;
@@ -72,41 +71,6 @@ struct KeyStream {
   static_assert(CH == 8 || CH == 16 || CH == 32, "row size not covered by the LDS swizzle");
   __device__ __forceinline__ static int swz(int key) { return CH == 8 ? ((key >> 1) & 7) : (key & 15); }
 
-  // registers of one in-flight stage
-  struct Regs { u32x4 v[NLD]; };
-
-  // keep: the stream is read again soon and fits the last-level cache (cached loads); otherwise
-  // the loads are non-temporal
-  __device__ __forceinline__ static void load(Regs& r, const T* kbase, int key0, int n, bool keep = false) {
-    const char* base = reinterpret_cast<const char*>(kbase);
-    if (key0 + kStageKeys <= n) {
-      // whole stage in range: rows are contiguous, so slot order is memory order - one uniform
-      // base per stage plus a per-thread constant, no per-load address arithmetic
-      const char* sbase = base + static_cast<int64_t>(key0) * (CH * 16) + threadIdx.x * 16;
-      if (keep) {
-#pragma unroll
-        for (int u = 0; u < NLD; ++u) r.v[u] = ld16(sbase + u * (NT * 16));
-      } else {
-#pragma unroll
-        for (int u = 0; u < NLD; ++u) r.v[u] = ld16_stream(sbase + u * (NT * 16));
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < NLD; ++u) {
-        const int slot = threadIdx.x + u * NT;         // (key, chunk) in row-major order
-        const int key = min(key0 + slot / CH, n - 1);  // the tail repeats the last row
-        r.v[u] = ld16(base + static_cast<int64_t>(key) * (CH * 16) + (slot % CH) * 16);
-      }
-    }
-  }
-  __device__ __forceinline__ static void store(const Regs& r, char* lds) {
-#pragma unroll
-    for (int u = 0; u < NLD; ++u) {
-      const int slot = threadIdx.x + u * NT;
-      const int key = slot / CH, ch = slot % CH;
-      st16(lds + key * (CH * 16) + ((ch ^ swz(key)) * 16), r.v[u]);
-    }
-  }
   // fragment of key tile kt for mma step kk: lane (i, c) gets key 16 kt + i, chunk 4 kk + c
   __device__ __forceinline__ static u32x4 frag(const char* lds, int kt, int kk, int i, int c) {
     const int key = 16 * kt + i;
