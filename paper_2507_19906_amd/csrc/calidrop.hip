@@ -129,9 +129,12 @@ CompressLayout compress_layout(const calidrop_params* p, int64_t total_tokens, i
   const int G = p->n_q_heads / p->n_kv_heads;
   L.RB = G * p->window > cd::kRowBlock ? 2 * cd::kRowBlock : cd::kRowBlock;     // 256-row blocks: such heads stream K once
   L.NRB = ceil_div(G * p->window, L.RB);
-  {  // keys per scoring workgroup: as large as keeps >= ~2048 workgroups in the launch, 256..2048
-    const int64_t groups256 = static_cast<int64_t>(p->batch) * p->n_kv_heads * L.NRB * ceil_div(max_seq_len, cd::kMinChunkKeys);
-    int mult = static_cast<int>(groups256 / 2048);
+  {  // keys per scoring workgroup, 256..2048: as large as keeps >= ~4096 workgroups in the launch (four rounds
+     // of the chip: with sequences of different lengths the last round is otherwise too ragged), but never
+     // below 512 for the sake of that while >= ~2048 workgroups remain
+    const int64_t groups256 = (total_tokens + cd::kMinChunkKeys - 1) / cd::kMinChunkKeys * p->n_kv_heads * L.NRB;
+    int mult = static_cast<int>(groups256 / 4096);
+    if (mult < 2) mult = static_cast<int>(std::min<int64_t>(groups256 / 2048, 2));
     if (mult < 1) mult = 1;
     if (mult > 8) mult = 8;
     L.chunk_keys = mult * cd::kMinChunkKeys;
