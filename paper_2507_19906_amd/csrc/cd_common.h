@@ -218,6 +218,23 @@ __device__ __forceinline__ void xcd_head_major(int& vx, int& vh) {
   }
 }
 
+// The same for a grid (chunks, rows) whose rows are (sequence, KV head, ...) units of possibly very
+// different lengths: XCD x takes the rows x, x + 8, x + 16, ... (every sequence's work is spread over
+// the XCDs the same way) and works through them chunk by chunk, so that all workgroups which share a
+// row's stationary operand sit behind one L2.  Returns false (vx, vy = the launch indices) when the
+// row count does not divide by 8.
+__device__ __forceinline__ bool xcd_rows_interleaved(int& vx, int& vy) {
+  vx = static_cast<int>(blockIdx.x);
+  vy = static_cast<int>(blockIdx.y);
+  const int gx = static_cast<int>(gridDim.x), H = static_cast<int>(gridDim.y);
+  if (H % 8 != 0) return false;
+  const int L = vx + gx * vy;
+  const int slot = L / 8;
+  vx = slot % gx;
+  vy = (slot / gx) * 8 + (L % 8);
+  return true;
+}
+
 // Merge two (max, sum-of-exp2) pairs in the log2 domain; (-inf, 0) is the identity.
 __device__ __forceinline__ void merge_ml(float& m, float& l, float m2, float l2) {
   float mn = fmaxf(m, m2);

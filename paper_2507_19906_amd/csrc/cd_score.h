@@ -161,8 +161,11 @@ __global__ __launch_bounds__(256) void score_rowstats_direct_kernel(ScoreArgs a)
   using KS = KeyStream<T, D>;
   constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys, EPL = KS::EPL, KD = KS::KD;
   constexpr int WR = 16 * RT, RB = 4 * WR;
-  const int y = blockIdx.y;
-  const int chunk = (blockIdx.x + y) % gridDim.x;
+  // every chunk of a (sequence, KV head, row block) behind the same L2, so that its query rows are fetched
+  // from memory once and not once per XCD; when the rows do not divide over the XCDs, the chunk index is
+  // rotated instead so that the chunks every sequence has do not all land on the same XCDs
+  int chunk, y;
+  if (!xcd_rows_interleaved(chunk, y)) chunk = (chunk + y) % static_cast<int>(gridDim.x);
   const int rb = y % a.NRB;
   const int bg = y / a.NRB;
   const int g = bg % a.Hkv;
@@ -353,12 +356,13 @@ template <typename T, int D, int NW>
 __global__ __launch_bounds__(NW * 64, sizeof(T) == 2 ? CD_VOTES_WAVES : 2) void score_votes_kernel(ScoreArgs a) {
   using KS = KeyStream<T, D, NW * 64>;
   constexpr int KT = KS::KT, NK = KS::NK, SK = KS::kStageKeys, RB = 32 * NW;
-  // grid: x = key chunk (fastest: neighbouring workgroups stream neighbouring keys), y = (sequence,
-  // KV head, row block).  Workgroups are dealt to the 8 XCDs round-robin in launch order; the chunk
-  // index is rotated by y so that, with sequences of different lengths, the chunks every sequence
-  // has do not all land on the same XCDs.
-  const int y = blockIdx.y;
-  const int chunk = (blockIdx.x + y) % gridDim.x;
+  // grid: x = key chunk, y = (sequence, KV head, row block).  Workgroups are dealt to the 8 XCDs
+  // round-robin in launch order: the launch index is re-read so that every chunk of a y sits behind the
+  // same L2 (the stationary query rows are then fetched from memory once, not once per XCD); when y
+  // does not divide over the XCDs the chunk index is rotated by y instead, so that with sequences of
+  // different lengths the chunks every sequence has do not all land on the same XCDs.
+  int chunk, y;
+  if (!xcd_rows_interleaved(chunk, y)) chunk = (chunk + y) % static_cast<int>(gridDim.x);
   const int rb = y % a.NRB;
   const int bg = y / a.NRB;
   const int g = bg % a.Hkv;
