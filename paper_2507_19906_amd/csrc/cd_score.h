@@ -451,7 +451,7 @@ __global__ __launch_bounds__(NW * 64, sizeof(T) == 2 ? CD_VOTES_WAVES : 2) void 
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww)
           tot += sv[ww][0][threadIdx.x] + sv[ww][1][threadIdx.x];
-        vote[key] = tot;
+        __builtin_nontemporal_store(tot, vote + key);    // written once, read by a later kernel: kept out of the caches the K stream uses
       }
     } else if (zrow != nullptr && threadIdx.x >= 64 && threadIdx.x < 64 + SK) {
       const int t = threadIdx.x - 64;
@@ -459,7 +459,7 @@ __global__ __launch_bounds__(NW * 64, sizeof(T) == 2 ? CD_VOTES_WAVES : 2) void 
       if (key < P)
         for (int hh = 0; hh < a.G; ++hh)
           if ((hh * a.w + a.w - 1) / RB == rb)             // heads whose last window row is in this row block
-            zrow[static_cast<int64_t>(hh) * a.zstride + key] = sz[hh][t];
+            __builtin_nontemporal_store(sz[hh][t], zrow + static_cast<int64_t>(hh) * a.zstride + key);
     }
   };
 
